@@ -1,0 +1,155 @@
+"""CPU fp64 oracle of the SpecPV verification path.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes front end of ``specpv_oracle.c`` (plain C loops that follow the
+paper's Section 3.2 / 3.3 definitions one by one).  Only ``tests/``, the smoke
+check and the bench's ``cpu_baseline`` leg may import this package; the product
+package never does, and this package never imports the product.
+
+Every function takes ONE sequence of ONE layer.  Arrays may be numpy arrays or
+torch tensors of any float dtype; they are widened to float64 (exactly) before
+the C code sees them.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "specpv_oracle.c")
+_LIB = os.path.join(_HERE, "libspecpv_oracle.so")
+
+REDUCE_MEAN, REDUCE_MAX, REDUCE_LAST = 0, 1, 2
+_REDUCE = {"mean": 0, "max": 1, "last": 2, 0: 0, 1: 1, 2: 2}
+
+
+def build(force=False):
+    """Compile specpv_oracle.c with gcc (no -ffast-math, generic x86-64)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    tmp = _LIB + ".tmp%d" % os.getpid()
+    subprocess.run(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall",
+                    "-o", tmp, _SRC, "-lm"], check=True)
+    os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def _f64(x):
+    if x is None:
+        return None
+    if hasattr(x, "detach"):  # torch tensor (bf16 has no numpy dtype: widen first)
+        import torch
+        x = x.detach().to("cpu").to(torch.float64).numpy()
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _i32(x):
+    if x is None:
+        return None
+    if hasattr(x, "detach"):
+        x = x.detach().to("cpu").numpy()
+    return np.ascontiguousarray(np.asarray(x, dtype=np.int32))
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def block_summarize(K, B):
+    """eq. 1.  K [L,Hkv,D] -> (kmax, kmin) each [nb,Hkv,D]."""
+    K = _f64(K)
+    L, Hkv, D = K.shape
+    nb = (L + B - 1) // B
+    kmax = np.empty((nb, Hkv, D))
+    kmin = np.empty((nb, Hkv, D))
+    _load().oracle_block_summarize(_p(K), L, Hkv, D, B, _p(kmax), _p(kmin))
+    return kmax, kmin
+
+
+def row_scores(Q, kmax, kmin):
+    """eq. 2.  Q [M,Hq,D], summaries [nb,Hkv,D] -> s [Hkv,nb,M*G]."""
+    Q, kmax, kmin = _f64(Q), _f64(kmax), _f64(kmin)
+    M, Hq, D = Q.shape
+    nb, Hkv, _ = kmax.shape
+    s = np.empty((Hkv, nb, M * (Hq // Hkv)))
+    _load().oracle_row_scores(_p(Q), M, Hq, _p(kmax), _p(kmin), nb, Hkv, D, _p(s))
+    return s
+
+
+def reduce_scores(s, M, G, reduce="mean", last_node=0):
+    """eq. 3.  s [Hkv,nb,M*G] -> scores [Hkv,nb]."""
+    s = _f64(s)
+    Hkv, nb, R = s.shape
+    assert R == M * G
+    out = np.empty((Hkv, nb))
+    _load().oracle_reduce_scores(_p(s), Hkv, nb, M, G, _REDUCE[reduce], int(last_node), _p(out))
+    return out
+
+
+def block_scores(Q, kmax, kmin, reduce="mean", last_node=0):
+    """eq. 2 then eq. 3."""
+    Q = _f64(Q)
+    M, Hq, _ = Q.shape
+    Hkv = kmax.shape[1]
+    return reduce_scores(row_scores(Q, kmax, kmin), M, Hq // Hkv, reduce, last_node)
+
+
+def select_blocks(scores, ns, nr, k):
+    """Sink + top-k + local selection.  scores [Hkv,nb] ->
+    (sel_idx [Hkv,ns+k+nr] int32 ascending / -1 padded, sel_count [Hkv])."""
+    scores = _f64(scores)
+    Hkv, nb = scores.shape
+    n_sel = ns + k + nr
+    sel_idx = np.empty((Hkv, n_sel), dtype=np.int32)
+    sel_count = np.empty((Hkv,), dtype=np.int32)
+    _load().oracle_select_blocks(_p(scores), Hkv, nb, ns, nr, k, _p(sel_idx), _p(sel_count))
+    return sel_idx, sel_count
+
+
+def tree_attention(Q, K, V, Kd, Vd, parent, B, sel_idx=None, sel_count=None):
+    """Tree-masked GQA attention over the kept context blocks plus the draft
+    nodes on each node's root path.  sel_idx None = every block (full
+    verification).  Returns (O [M,Hq,D], lse [M,Hq], psum [M,Hq])."""
+    Q, K, V, Kd, Vd = _f64(Q), _f64(K), _f64(V), _f64(Kd), _f64(Vd)
+    parent = _i32(parent)
+    M, Hq, D = Q.shape
+    L, Hkv, _ = K.shape
+    assert parent[0] == -1 and all(parent[i] < i for i in range(1, M))
+    n_sel = 0
+    if sel_idx is not None:
+        sel_idx, sel_count = _i32(sel_idx), _i32(sel_count)
+        n_sel = sel_idx.shape[1]
+    O = np.empty((M, Hq, D))
+    lse = np.empty((M, Hq))
+    psum = np.empty((M, Hq))
+    _load().oracle_tree_attention(_p(Q), _p(K), _p(V), _p(Kd), _p(Vd), _p(parent),
+                                  M, Hq, Hkv, D, L, B, _p(sel_idx), _p(sel_count),
+                                  n_sel, _p(O), _p(lse), _p(psum))
+    return O, lse, psum
+
+
+def full_verify_refresh(Q, K, V, Kd, Vd, parent, B, ns, nr, k, reduce="mean", last_node=0):
+    """Section 3.3: attention over the whole cache, then new summaries, scores
+    (with this pass's queries) and a fresh block selection.
+    Returns (O, lse, sel_idx, sel_count, scores)."""
+    O, lse, _ = tree_attention(Q, K, V, Kd, Vd, parent, B)
+    kmax, kmin = block_summarize(K, B)
+    scores = block_scores(Q, kmax, kmin, reduce, last_node)
+    sel_idx, sel_count = select_blocks(scores, ns, nr, k)
+    return O, lse, sel_idx, sel_count, scores
