@@ -1,0 +1,159 @@
+/*
+ * specpv.h -- C ABI of the SpecPV verification-attention library for MI355X (gfx950).
+ *
+ * The library implements the verification hot path of SpecPV ("partial
+ * verification" self-speculative decoding for long contexts): per-block key
+ * summaries (Section 3.2, eq. 1), query-aware block scores (eq. 2, eq. 3),
+ * selection of sink + top-k retrieval + local blocks (Section 3.2), tree-masked
+ * grouped-query attention of the draft tree over only the selected blocks
+ * (Section 3.2; tree decode of Algorithm 1), and the periodic full-verification
+ * pass that attends over the whole cache and refreshes the selection
+ * (Section 3.3).
+ *
+ * Conventions for every entry point
+ *  - extern "C"; returns SPECPV_OK (0) or a negative specpv_status; never throws.
+ *  - Pointers inside the descriptor structs and all buffer arguments are DEVICE
+ *    pointers owned by the caller, except where "host" is stated.  The structs
+ *    themselves are HOST memory and are only read during the call.
+ *  - No allocation and no host synchronisation happen inside a call: kernels are
+ *    enqueued on `stream` (a hipStream_t passed as void*; NULL = null stream) and
+ *    outputs are valid once the stream reaches that point.
+ *  - Arguments are validated on the host before anything is launched; on error
+ *    nothing has been enqueued.  Device-side quantities (ctx_len, sel_count,
+ *    entries of sel_idx, parent) are bounds-checked inside the kernels: blocks or
+ *    tokens outside the sequence are ignored, they are never dereferenced.
+ *  - The calls keep no mutable global state and may be issued from several
+ *    threads on different streams.  Two calls that share a workspace must be
+ *    ordered by the caller (same stream, or events).
+ *
+ * Notation: L_b committed tokens of sequence b, B block size, nb_b = ceil(L_b/B),
+ * Hq query heads, Hkv KV heads, G = Hq/Hkv, D head dim, M draft-tree nodes (the
+ * query tokens of this verify step).  Query head h reads KV head h / G.
+ *
+ * Supported: D in {64, 128}; dtype f32 or bf16 (q, k, v, kd, vd, summaries and
+ * out share one dtype); 1 <= M <= 128; 1 <= G <= 16; B >= 1; batch >= 1.
+ */
+#ifndef SPECPV_H
+#define SPECPV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPECPV_OK = 0,
+    SPECPV_EINVAL = -1,     /* null pointer, bad shape, unsupported dtype / D / strides  */
+    SPECPV_EWORKSPACE = -2, /* workspace pointer null or workspace_bytes too small        */
+    SPECPV_ELIMIT = -3,     /* M, G, k or block counts beyond the documented limits       */
+    SPECPV_EHIP = -4        /* a HIP launch failed; see specpv_last_hip_error()           */
+} specpv_status;
+
+typedef enum { SPECPV_F32 = 0, SPECPV_BF16 = 1 } specpv_dtype;
+
+/* eq. 3: how the per-query scores of a block are reduced to one score. */
+typedef enum { SPECPV_REDUCE_MEAN = 0, SPECPV_REDUCE_MAX = 1, SPECPV_REDUCE_LAST = 2 } specpv_reduce;
+
+#define SPECPV_MAX_M 128
+#define SPECPV_MAX_G 16
+
+/* One layer's committed KV cache for a batch of sequences, read in place.
+ * Element (b, t, g, d) of k (and v) lives at  base + b*stride_b + g*stride_h +
+ * t*stride_t + d  (strides in ELEMENTS; d is contiguous; every row start must be
+ * 16-byte aligned).  Both the head-major [batch, Hkv, T, D] and the token-major
+ * [batch, T, Hkv, D] layouts fit.  Rows t >= ctx_len[b] are never read. */
+typedef struct specpv_kv {
+    const void *k, *v;
+    int64_t stride_b, stride_h, stride_t;
+    const int32_t *ctx_len; /* device, [batch]: L_b                                      */
+    int32_t batch, n_kv_heads, head_dim, block_size;
+    int32_t max_blocks;     /* >= max_b nb_b; second-to-last extent of the summary / score arrays */
+    specpv_dtype dtype;
+} specpv_kv;
+
+/* The draft tree: the query tokens of this verify step, and their own K/V (the
+ * "buffer" part of the partial cache, Section 3.2).  On a refresh step the
+ * partially verified tokens are a chain prefix of parent[] (Section 3.3). */
+typedef struct specpv_tree {
+    const void *q;         /* [batch, M, Hq, D] contiguous, post-RoPE                    */
+    const void *kd, *vd;   /* [batch, M, Hkv, D] contiguous; may be NULL for select      */
+    const int32_t *parent; /* device, [batch, M]; parent[0] = -1, parent[i] < i          */
+    int32_t M, n_q_heads;
+    int32_t last_node;     /* node whose queries SPECPV_REDUCE_LAST keeps (normally 0)   */
+} specpv_tree;
+
+/* Composition of the partial cache in blocks (Section 3.2): always the first
+ * n_sink_blocks, always the last n_recent_blocks, and the k_blocks best-scoring
+ * blocks in between. */
+typedef struct specpv_select_cfg {
+    int32_t n_sink_blocks, n_recent_blocks, k_blocks;
+    specpv_reduce reduce;
+} specpv_select_cfg;
+
+/* Bytes of workspace that any of the calls below needs for these descriptors
+ * (host-only computation; 0 on invalid descriptors).  cfg may be NULL if only
+ * specpv_block_summarize is used. */
+size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, const specpv_select_cfg *cfg);
+
+/* Section 3.2, eq. 1.  For every sequence b, KV head g and block i in
+ * [blk_begin, blk_end) (blk_end < 0: up to nb_b; blocks >= nb_b are skipped):
+ *   kmax[b, g, i, :] = element-wise max of k over the block's tokens t < L_b,
+ *   kmin likewise.  kmax / kmin: [batch, Hkv, max_blocks, D], kv dtype.
+ * Exact in any dtype (only comparisons). */
+int specpv_block_summarize(const specpv_kv *kv, int32_t blk_begin, int32_t blk_end,
+                           void *kmax, void *kmin, void *stream);
+
+/* Section 3.2, eq. 2 + eq. 3 + block selection.  Per (b, g):
+ *   s[i, r] = max(q_r . kmax_i, q_r . kmin_i) for the M*G query rows r of the KV
+ *   head (fp32 accumulation); score[i] = mean / max over all rows, or the mean
+ *   over the G rows of tree->last_node;
+ *   kept = blocks [0, ns) + the k best candidates of [ns, nb_b - nr) by (fp32
+ *   score descending, block index ascending) + blocks [nb_b - nr, nb_b);
+ *   every block if nb_b <= ns + k + nr.
+ * sel_idx   [batch, Hkv, n_sel] int32, n_sel = ns + k + nr, ascending, padded with -1.
+ * sel_count [batch, Hkv] int32.
+ * scores    optional [batch, Hkv, max_blocks] fp32 (NULL: kept in the workspace). */
+int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree,
+                         const void *kmax, const void *kmin, const specpv_select_cfg *cfg,
+                         int32_t *sel_idx, int32_t *sel_count, float *scores,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Section 3.2 (attention over the partial cache as one KV segment) with the tree
+ * decode of Algorithm 1.  For node j and query head h (KV head g = h / G):
+ *   keys = tokens t < L_b of the blocks sel_idx[b, g, 0..sel_count[b, g])
+ *          + draft nodes a that are j or an ancestor of j;
+ *   out[b, j, h, :] = softmax(q . k / sqrt(D)) . v over those keys (fp32
+ *   accumulation, result in the q dtype); lse[b, j, h] = log sum exp (natural log).
+ * sel_idx == NULL attends over every block (full verification).  The order of
+ * sel_idx does not matter; entries < 0 or >= nb_b are ignored; a block listed
+ * twice is attended twice.
+ * out [batch, M, Hq, D]; lse optional [batch, M, Hq] fp32. */
+int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree,
+                               const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
+                               void *out, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Section 3.3: full verification that also refreshes the partial cache.
+ *   1. summaries of blocks [stale_blk_begin, nb_b) are recomputed in place
+ *      (stale_blk_begin < 0: none);
+ *   2. attention of the tree over the whole cache -> out, lse;
+ *   3. eq. 2 / eq. 3 scores with this pass's queries and a fresh selection
+ *      -> sel_idx, sel_count (and scores if not NULL).
+ * Same result as the three calls above issued one after another. */
+int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree,
+                               void *kmax, void *kmin, int32_t stale_blk_begin,
+                               const specpv_select_cfg *cfg, void *out, float *lse,
+                               int32_t *sel_idx, int32_t *sel_count, float *scores,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+const char *specpv_strerror(int status);
+/* Text of the HIP error behind the calling thread's last SPECPV_EHIP. */
+const char *specpv_last_hip_error(void);
+int specpv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECPV_H */

@@ -1,0 +1,15 @@
+"""SpecPV verification attention for MI355X: Python binding of libspecpv.so.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels
+behind the C ABI declared in include/specpv.h.  torch is used for device memory
+and streams.  There is no CPU fallback: if the HIP library is not built, load()
+raises.
+"""
+from .binding import (REDUCE_LAST, REDUCE_MAX, REDUCE_MEAN, SpecPVError, KV, Tree, SelectCfg, load,
+                      lib_path, specpv_block_summarize, specpv_full_verify_refresh,
+                      specpv_partial_verify_attn, specpv_select_blocks, specpv_workspace_bytes,
+                      specpv_strerror, specpv_version, EXPORTS)
+
+__all__ = ["REDUCE_LAST", "REDUCE_MAX", "REDUCE_MEAN", "SpecPVError", "KV", "Tree", "SelectCfg", "load",
+           "lib_path", "specpv_block_summarize", "specpv_full_verify_refresh", "specpv_partial_verify_attn",
+           "specpv_select_blocks", "specpv_workspace_bytes", "specpv_strerror", "specpv_version", "EXPORTS"]

@@ -1,0 +1,280 @@
+// C ABI of libspecpv: argument validation, workspace layout, split planning and
+// the launch sequences of the four calls.  No kernels live here.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "internal.h"
+
+namespace specpv {
+
+static thread_local char g_hip_err[256] = "";
+
+static int fail_hip(hipError_t e)
+{
+    snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
+    return SPECPV_EHIP;
+}
+
+int device_cu_count()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            return 256;
+        return cus;
+    }();
+    return n;
+}
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int check_kv(const specpv_kv *kv)
+{
+    if (!kv || !kv->k || !kv->v || !kv->ctx_len) return SPECPV_EINVAL;
+    if (kv->dtype != SPECPV_F32 && kv->dtype != SPECPV_BF16) return SPECPV_EINVAL;
+    if (kv->head_dim != 64 && kv->head_dim != 128) return SPECPV_EINVAL;
+    if (kv->batch < 1 || kv->n_kv_heads < 1 || kv->block_size < 1 || kv->max_blocks < 1) return SPECPV_EINVAL;
+    const int64_t vec = kv->dtype == SPECPV_BF16 ? 8 : 4;  // elements per 16 bytes
+    if (kv->stride_t < kv->head_dim || kv->stride_t % vec || kv->stride_h % vec || kv->stride_b % vec)
+        return SPECPV_EINVAL;
+    if (kv->stride_h < 0 || kv->stride_b < 0) return SPECPV_EINVAL;
+    if (((uintptr_t)kv->k | (uintptr_t)kv->v) & 15) return SPECPV_EINVAL;
+    if ((int64_t)kv->max_blocks * kv->block_size > ((int64_t)1 << 30)) return SPECPV_ELIMIT;
+    return SPECPV_OK;
+}
+
+static int check_tree(const specpv_kv *kv, const specpv_tree *tree, bool need_draft_kv)
+{
+    if (!tree || !tree->q) return SPECPV_EINVAL;
+    if (tree->M < 1 || tree->n_q_heads < 1) return SPECPV_EINVAL;
+    if (tree->n_q_heads % kv->n_kv_heads) return SPECPV_EINVAL;
+    if (tree->M > SPECPV_MAX_M || tree->n_q_heads / kv->n_kv_heads > SPECPV_MAX_G) return SPECPV_ELIMIT;
+    if ((uintptr_t)tree->q & 15) return SPECPV_EINVAL;
+    if (need_draft_kv) {
+        if (!tree->kd || !tree->vd || !tree->parent) return SPECPV_EINVAL;
+        if (((uintptr_t)tree->kd | (uintptr_t)tree->vd) & 15) return SPECPV_EINVAL;
+    }
+    return SPECPV_OK;
+}
+
+static int check_cfg(const specpv_tree *tree, const specpv_select_cfg *cfg)
+{
+    if (!cfg) return SPECPV_EINVAL;
+    if (cfg->n_sink_blocks < 0 || cfg->n_recent_blocks < 0 || cfg->k_blocks < 0) return SPECPV_EINVAL;
+    if (cfg->reduce != SPECPV_REDUCE_MEAN && cfg->reduce != SPECPV_REDUCE_MAX && cfg->reduce != SPECPV_REDUCE_LAST)
+        return SPECPV_EINVAL;
+    if (cfg->reduce == SPECPV_REDUCE_LAST && (tree->last_node < 0 || tree->last_node >= tree->M))
+        return SPECPV_EINVAL;
+    if ((int64_t)cfg->n_sink_blocks + cfg->n_recent_blocks + cfg->k_blocks > ((int64_t)1 << 24)) return SPECPV_ELIMIT;
+    return SPECPV_OK;
+}
+
+static Shape make_shape(const specpv_kv *kv, const specpv_tree *tree)
+{
+    Shape s;
+    memset(&s, 0, sizeof(s));
+    s.k = kv->k; s.v = kv->v;
+    s.sb = kv->stride_b; s.sh = kv->stride_h; s.st = kv->stride_t;
+    s.ctx_len = kv->ctx_len;
+    s.batch = kv->batch; s.Hkv = kv->n_kv_heads; s.D = kv->head_dim; s.B = kv->block_size;
+    s.max_blocks = kv->max_blocks;
+    if (tree) {
+        s.q = tree->q; s.kd = tree->kd; s.vd = tree->vd; s.parent = tree->parent;
+        s.M = tree->M; s.Hq = tree->n_q_heads; s.G = s.Hq / s.Hkv;
+    }
+    return s;
+}
+
+// How many KV splits the context part of the attention uses when it covers
+// n_blocks blocks per (sequence, KV head).  Host-only and deterministic in its
+// arguments, so specpv_workspace_bytes and the calls agree.
+static int plan_splits(const Shape &s, int dtype, int64_t n_blocks)
+{
+    const int64_t tokens = n_blocks * s.B;
+    if (tokens <= 0) return 1;
+    int64_t ns;
+    if (attn_ctx_mfma_supported(s, dtype)) {
+        // one workgroup (4 wavefronts, one 32-token chunk at a time each) per
+        // (sequence, query head, 64-node row tile, split); one workgroup per CU
+        const int64_t base = (int64_t)s.batch * s.Hq * ((s.M + 63) / 64);
+        const int64_t chunks = (tokens + 31) / 32;
+        const int64_t cus = device_cu_count();
+        const int64_t max_ns = chunks / 4 > 1 ? (chunks / 4 < 64 ? chunks / 4 : 64) : 1;
+        int64_t best = 1, best_cost = -1;
+        for (int64_t c = 1; c <= max_ns; ++c) {
+            const int64_t rounds = (base * c + cus - 1) / cus;
+            const int64_t per_wave = (chunks + 4 * c - 1) / (4 * c);
+            // chunk-times on the critical path, plus a charge for the epilogue and the partials
+            const int64_t cost = rounds * (per_wave * 8 + 10) + c;
+            if (best_cost < 0 || cost < best_cost) { best = c; best_cost = cost; }
+        }
+        ns = best;
+    } else {
+        const int64_t rows = (int64_t)s.batch * s.Hq * s.M;
+        const int64_t chunks = (tokens + 63) / 64;
+        ns = (4096 + rows - 1) / rows;
+        if (ns > chunks) ns = chunks;
+        if (ns > 64) ns = 64;
+        if (ns < 1) ns = 1;
+    }
+    return (int)ns;
+}
+
+struct Workspace {
+    float *part_o, *part_ml, *scores;
+    size_t total;
+};
+
+static Workspace layout_workspace(const Shape &s, int nsplit, void *base)
+{
+    Workspace w;
+    const size_t po = align_up((size_t)s.batch * s.Hq * nsplit * s.M * s.D * sizeof(float));
+    const size_t pm = align_up((size_t)s.batch * s.Hq * nsplit * s.M * 2 * sizeof(float));
+    const size_t sc = align_up((size_t)s.batch * s.Hkv * s.max_blocks * sizeof(float));
+    char *p = (char *)base;
+    w.part_o = (float *)p;
+    w.part_ml = (float *)(p + po);
+    w.scores = (float *)(p + po + pm);
+    w.total = po + pm + sc;
+    return w;
+}
+
+static int run_attention(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count,
+                         int n_sel, void *out, float *lse, void *workspace, size_t workspace_bytes,
+                         hipStream_t st)
+{
+    const int nsplit = plan_splits(s, dtype, sel_idx ? n_sel : s.max_blocks);
+    const Workspace w = layout_workspace(s, nsplit, workspace);
+    if (!workspace || workspace_bytes < w.total) return SPECPV_EWORKSPACE;
+    Partials p{w.part_o, w.part_ml, nsplit};
+    hipError_t e;
+    if (attn_ctx_mfma_supported(s, dtype)) e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, st);
+    else e = launch_attn_ctx_generic(s, dtype, sel_idx, sel_count, n_sel, p, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_combine(s, dtype, p, out, lse, st);
+    if (e != hipSuccess) return fail_hip(e);
+    return SPECPV_OK;
+}
+
+static int run_select(const Shape &s, int dtype, const specpv_tree *tree, const void *kmax, const void *kmin,
+                      const specpv_select_cfg *cfg, int32_t *sel_idx, int32_t *sel_count, float *scores,
+                      hipStream_t st)
+{
+    hipError_t e = launch_scores(s, dtype, kmax, kmin, (int)cfg->reduce, tree->last_node, scores, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_topk(s, scores, cfg->n_sink_blocks, cfg->n_recent_blocks, cfg->k_blocks, sel_idx, sel_count, st);
+    if (e != hipSuccess) return fail_hip(e);
+    return SPECPV_OK;
+}
+
+}  // namespace specpv
+
+using namespace specpv;
+
+extern "C" {
+
+size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, const specpv_select_cfg *cfg)
+{
+    if (check_kv(kv) != SPECPV_OK) return 0;
+    if (!tree) return 256;
+    if (check_tree(kv, tree, false) != SPECPV_OK) return 0;
+    const Shape s = make_shape(kv, tree);
+    int nsplit = plan_splits(s, kv->dtype, s.max_blocks);
+    if (cfg) {
+        const int64_t n_sel = (int64_t)cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks;
+        const int n2 = plan_splits(s, kv->dtype, n_sel);
+        if (n2 > nsplit) nsplit = n2;
+    }
+    return layout_workspace(s, nsplit, nullptr).total;
+}
+
+int specpv_block_summarize(const specpv_kv *kv, int32_t blk_begin, int32_t blk_end,
+                           void *kmax, void *kmin, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if (!kmax || !kmin || blk_begin < 0) return SPECPV_EINVAL;
+    if (((uintptr_t)kmax | (uintptr_t)kmin) & 15) return SPECPV_EINVAL;
+    const Shape s = make_shape(kv, nullptr);
+    const hipError_t e = launch_summarize(s, kv->dtype, blk_begin, blk_end, kmax, kmin, (hipStream_t)stream);
+    return e == hipSuccess ? SPECPV_OK : fail_hip(e);
+}
+
+int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree, const void *kmax, const void *kmin,
+                         const specpv_select_cfg *cfg, int32_t *sel_idx, int32_t *sel_count, float *scores,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if ((rc = check_tree(kv, tree, false)) != SPECPV_OK) return rc;
+    if ((rc = check_cfg(tree, cfg)) != SPECPV_OK) return rc;
+    if (!kmax || !kmin || !sel_idx || !sel_count) return SPECPV_EINVAL;
+    if (((uintptr_t)kmax | (uintptr_t)kmin) & 15) return SPECPV_EINVAL;
+    const Shape s = make_shape(kv, tree);
+    if (!scores) {
+        const size_t need = align_up((size_t)s.batch * s.Hkv * s.max_blocks * sizeof(float));
+        if (!workspace || workspace_bytes < need) return SPECPV_EWORKSPACE;
+        scores = (float *)workspace;
+    }
+    return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores, (hipStream_t)stream);
+}
+
+int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree, const int32_t *sel_idx,
+                               const int32_t *sel_count, int32_t n_sel, void *out, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if ((rc = check_tree(kv, tree, true)) != SPECPV_OK) return rc;
+    if (!out || ((uintptr_t)out & 15)) return SPECPV_EINVAL;
+    if (sel_idx && (!sel_count || n_sel < 0)) return SPECPV_EINVAL;
+    if (sel_idx && n_sel > (1 << 24)) return SPECPV_ELIMIT;
+    const Shape s = make_shape(kv, tree);
+    return run_attention(s, kv->dtype, sel_idx, sel_count, n_sel, out, lse, workspace, workspace_bytes,
+                         (hipStream_t)stream);
+}
+
+int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree, void *kmax, void *kmin,
+                               int32_t stale_blk_begin, const specpv_select_cfg *cfg, void *out, float *lse,
+                               int32_t *sel_idx, int32_t *sel_count, float *scores,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if ((rc = check_tree(kv, tree, true)) != SPECPV_OK) return rc;
+    if ((rc = check_cfg(tree, cfg)) != SPECPV_OK) return rc;
+    if (!kmax || !kmin || !out || !sel_idx || !sel_count) return SPECPV_EINVAL;
+    if (((uintptr_t)kmax | (uintptr_t)kmin | (uintptr_t)out) & 15) return SPECPV_EINVAL;
+    const Shape s = make_shape(kv, tree);
+    const int nsplit = plan_splits(s, kv->dtype, s.max_blocks);
+    const Workspace w = layout_workspace(s, nsplit, workspace);
+    if (!workspace || workspace_bytes < w.total) return SPECPV_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (stale_blk_begin >= 0) {
+        const hipError_t e = launch_summarize(s, kv->dtype, stale_blk_begin, -1, kmax, kmin, st);
+        if (e != hipSuccess) return fail_hip(e);
+    }
+    rc = run_attention(s, kv->dtype, nullptr, nullptr, 0, out, lse, workspace, workspace_bytes, st);
+    if (rc != SPECPV_OK) return rc;
+    return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores ? scores : w.scores, st);
+}
+
+const char *specpv_strerror(int status)
+{
+    switch (status) {
+    case SPECPV_OK: return "ok";
+    case SPECPV_EINVAL: return "invalid argument (null pointer, shape, dtype, head dim, stride or alignment)";
+    case SPECPV_EWORKSPACE: return "workspace missing or too small (see specpv_workspace_bytes)";
+    case SPECPV_ELIMIT: return "size beyond the documented limits";
+    case SPECPV_EHIP: return "HIP launch failed (see specpv_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+const char *specpv_last_hip_error(void) { return g_hip_err; }
+
+int specpv_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Internal declarations shared by the HIP translation units of libspecpv.
+// Each .hip file owns its kernels and exposes one host launcher; api.hip
+// validates arguments and calls the launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "specpv.h"
+
+namespace specpv {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Flat view of one call's tensors, passed by value to the kernels.
+struct Shape {
+    const void *k, *v;            // context KV, read in place
+    int64_t sb, sh, st;           // element strides of k / v: batch, head, token
+    const int32_t *ctx_len;       // [batch]
+    const void *q;                // [batch, M, Hq, D]
+    const void *kd, *vd;          // [batch, M, Hkv, D]
+    const int32_t *parent;        // [batch, M]
+    int batch, Hkv, Hq, G, D, B, M, max_blocks;
+};
+
+// Split-KV partial results of the context part, one per (b, h, split, node):
+//   part_o  [batch, Hq, nsplit, M, D] fp32   sum_t 2^(z_t - m) v_t   (not normalised)
+//   part_ml [batch, Hq, nsplit, M, 2] fp32   (m, l): m = max_t z_t, l = sum_t 2^(z_t - m),
+// with z = q.k * log2(e)/sqrt(D).  A split without any valid token stores m = -inf, l = 0.
+struct Partials {
+    float *o;
+    float *ml;
+    int nsplit;
+};
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerVec = 4;  // elements per 16-byte vector
+    static __device__ __forceinline__ void unpack(const uint4 &u, float *f) {
+        f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
+        f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
+    }
+    static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
+    static __device__ __forceinline__ void store(void *p, int64_t i, float x) { ((float *)p)[i] = x; }
+};
+struct bf16_t { uint16_t bits; };
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+// round-to-nearest-even fp32 -> bf16 (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+template <> struct Elem<bf16_t> {
+    static constexpr int kPerVec = 8;
+    static __device__ __forceinline__ void unpack(const uint4 &u, float *f) {
+        f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
+        f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+        f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
+        f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float load(const void *p, int64_t i) {
+        return bf16_bits_to_float(((const uint16_t *)p)[i]);
+    }
+    static __device__ __forceinline__ void store(void *p, int64_t i, float x) {
+        ((uint16_t *)p)[i] = float_to_bf16_bits(x);
+    }
+};
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// ---- launchers (each returns the hipError_t of its launches) ----
+hipError_t launch_summarize(const Shape &s, int dtype, int blk_begin, int blk_end,
+                            void *kmax, void *kmin, hipStream_t st);
+hipError_t launch_scores(const Shape &s, int dtype, const void *kmax, const void *kmin,
+                         int reduce, int last_node, float *scores, hipStream_t st);
+hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k,
+                       int32_t *sel_idx, int32_t *sel_count, hipStream_t st);
+hipError_t launch_attn_ctx_generic(const Shape &s, int dtype, const int32_t *sel_idx,
+                                   const int32_t *sel_count, int n_sel, Partials p, hipStream_t st);
+bool attn_ctx_mfma_supported(const Shape &s, int dtype);
+hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
+                                int n_sel, Partials p, hipStream_t st);
+hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st);
+
+int device_cu_count();
+
+}  // namespace specpv

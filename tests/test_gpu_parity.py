@@ -1,0 +1,214 @@
+"""GPU parity: every call of the C ABI against the fp64 oracle, element by element,
+on the same seeded inputs.  Bars: summaries and kept-block lists bit-exact (lists
+under the near-tie margin rule), attention outputs max-abs <= 1e-5 (fp32 inputs)
+or 2e-2 (bf16 inputs)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import ATOL, GpuRun, check_selection, oracle_select, say, topk_margin
+
+pytestmark = pytest.mark.gpu
+
+
+def _to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64) if t.dtype != torch.int32 else t.cpu().numpy()
+
+
+def _oracle_attn(case, b, sel_idx=None, sel_count=None):
+    o = workloads.oracle_views(case, b)
+    return oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"], sel_idx, sel_count)
+
+
+def _check_attn(run, case, sel=None, tag="", lse_tol=None):
+    """sel: per-sequence list of (idx, cnt) numpy arrays, or None for all blocks."""
+    atol = ATOL[case["dtype"]]
+    out, lse = _to_np(run.out), _to_np(run.lse)
+    worst = 0.0
+    for b in range(case["batch"]):
+        O, L, ps = _oracle_attn(case, b, *(sel[b] if sel is not None else (None, None)))
+        np.testing.assert_allclose(ps, 1.0, atol=1e-12)
+        err = np.abs(out[b] - O).max()
+        worst = max(worst, err)
+        assert err <= atol, (tag, b, "max-abs %.3g > %.3g" % (err, atol))
+        np.testing.assert_allclose(lse[b], L, atol=lse_tol or (2e-5 if case["dtype"] == "f32" else 2e-3), rtol=1e-5)
+    say("   %s attention max-abs err %.3g (bar %.1g)" % (tag, worst, atol))
+
+
+@pytest.mark.parametrize("name,seed", [("tiny_f32", 2), ("llama8b_16k", 3)])
+def test_whole_path_matches_oracle(gpu_lib, name, seed):
+    """summarize -> select -> partial attention, then full verify + refresh."""
+    say("case", name, "seed", seed)
+    case = workloads.to_device(workloads.make_case(name, seed=seed), "cuda")   # CPU stream: seeds searched offline
+    run = GpuRun(gpu_lib, case)
+    o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0)
+    # eq. 1: bit-exact
+    run.summarize()
+    torch.cuda.synchronize()
+    assert np.array_equal(_to_np(run.kmax)[0].transpose(1, 0, 2), kmax)
+    assert np.array_equal(_to_np(run.kmin)[0].transpose(1, 0, 2), kmin)
+    # eq. 2-3 + selection
+    run.select()
+    torch.cuda.synchronize()
+    got_sc = run.scores.cpu().numpy()[0]
+    np.testing.assert_allclose(got_sc, sc, rtol=2e-5, atol=2e-5)
+    margin = topk_margin(sc, case["ns"], case["nr"], case["k_blocks"])
+    say("   top-k margins", np.array2string(margin, precision=4))
+    assert (margin > 1e-3).all(), "pick a seed whose k-th / (k+1)-th scores are separated"
+    assert check_selection(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0], idx, cnt, sc,
+                           case["ns"], case["nr"], case["k_blocks"], name)
+    # partial verification attention on the GPU's own list
+    run.attend()
+    torch.cuda.synchronize()
+    _check_attn(run, case, [(idx, cnt)], name + " partial")
+    # full verification + refresh, summaries recomputed from block 0
+    run.kmax.zero_(); run.kmin.zero_(); run.sel_idx.fill_(-9); run.out.zero_()
+    run.refresh(stale=0)
+    torch.cuda.synchronize()
+    _check_attn(run, case, None, name + " full")
+    assert np.array_equal(_to_np(run.kmax)[0].transpose(1, 0, 2), kmax)
+    assert check_selection(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0], idx, cnt, sc,
+                           case["ns"], case["nr"], case["k_blocks"], name + " refresh")
+
+
+SMALL = dict(Hq=8, Hkv=2, D=128, dtype="bf16", ctx=[1000], B=16, M=24, tree="bounded",
+             ns=2, nr=3, k=9, rho=[0.1], beta=1.5, layers=1, name="small")
+
+
+@pytest.mark.parametrize("over,tag", [
+    (dict(), "bf16 ragged tail L=1000 B=16"),
+    (dict(dtype="f32", D=64), "f32 D=64"),
+    (dict(dtype="f32", D=128, B=64, ctx=[1500]), "f32 D=128 B=64"),
+    (dict(D=64, ctx=[777], B=32), "bf16 D=64 B=32"),
+    (dict(M=1, tree="chain"), "single token decode"),
+    (dict(M=128, tree="chain", ctx=[512]), "chain of 128 (refresh-style pending prefix)"),
+    (dict(M=100, tree="uniform", Hq=10, Hkv=2), "M=100 G=5"),
+    (dict(ctx=[100], k=20), "context shorter than the budget: every block kept"),
+    (dict(ctx=[640, 1000, 48, 333], rho=[0.1] * 4), "ragged batch of 4"),
+    (dict(Hq=16, Hkv=1), "G=16"),
+    (dict(B=7, ctx=[500], ns=3, nr=5, k=11), "odd block size 7"),
+])
+def test_shapes_and_edges(gpu_lib, over, tag):
+    say("case", tag)
+    cfg = dict(SMALL); cfg.update(over)
+    case = workloads.to_device(workloads.make_case(cfg, seed=11), "cuda")
+    for layout in ("bhtd", "bthd"):
+        run = GpuRun(gpu_lib, case, layout=layout)
+        run.summarize(); run.select(); run.attend()
+        torch.cuda.synchronize()
+        sel = []
+        for b in range(case["batch"]):
+            o, kmax, kmin, sc, idx, cnt = oracle_select(case, b)
+            nb = kmax.shape[0]
+            assert np.array_equal(_to_np(run.kmax)[b].transpose(1, 0, 2)[:nb], kmax)
+            assert np.array_equal(_to_np(run.kmin)[b].transpose(1, 0, 2)[:nb], kmin)
+            np.testing.assert_allclose(run.scores.cpu().numpy()[b][:, :nb], sc, rtol=2e-5, atol=2e-5)
+            got_idx, got_cnt = run.sel_idx.cpu().numpy()[b], run.sel_count.cpu().numpy()[b]
+            check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], tag)
+            sel.append((got_idx, got_cnt))     # attention is judged on the list it was given
+        _check_attn(run, case, sel, tag + " " + layout)
+        run.out.zero_()
+        run.refresh(stale=0)
+        torch.cuda.synchronize()
+        _check_attn(run, case, None, tag + " full " + layout)
+
+
+@pytest.mark.parametrize("reduce,last_node", [("max", 0), ("last", 0), ("last", 5), ("mean", 0)])
+def test_reducers(gpu_lib, reduce, last_node):
+    say("reducer", reduce, last_node)
+    case = workloads.to_device(workloads.make_case(SMALL, seed=21), "cuda")
+    run = GpuRun(gpu_lib, case, reduce=reduce, last_node=last_node)
+    run.summarize(); run.select()
+    torch.cuda.synchronize()
+    o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0, reduce, last_node)
+    np.testing.assert_allclose(run.scores.cpu().numpy()[0], sc, rtol=2e-5, atol=2e-5)
+    check_selection(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0], idx, cnt, sc,
+                    case["ns"], case["nr"], case["k_blocks"], reduce)
+
+
+def test_selection_ties_and_extremes(gpu_lib):
+    """Exact ties (duplicated blocks) must go to the lower index; k = 0, no sink, no
+    local window and k larger than the candidates are all legal."""
+    cfg = dict(SMALL); cfg.update(ctx=[64 * 16], rho=[0.0])
+    case = workloads.to_device(workloads.make_case(cfg, seed=31), "cuda")
+    B = case["B"]
+    k = case["k"]
+    # blocks 10, 20, 30, 40 become copies of block 5, and get a large boost so they all rank first
+    src = k[0, :, 5 * B:6 * B].clone() + 1.0
+    for i in (5, 10, 20, 30, 40):
+        k[0, :, i * B:(i + 1) * B] = src
+    for (ns, nr, kb) in [(2, 3, 3), (2, 3, 0), (0, 0, 4), (0, 0, 64), (1, 1, 61), (1, 1, 62), (70, 0, 0), (0, 0, 1)]:
+        run = GpuRun(gpu_lib, case, cfg=(ns, nr, kb))
+        run.summarize(); run.select()
+        torch.cuda.synchronize()
+        o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0, cfg=(ns, nr, kb))
+        got_idx, got_cnt = run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0]
+        say("   ns,nr,k =", (ns, nr, kb), "kept", got_idx[0, :got_cnt[0]].tolist()[:12])
+        # identical blocks give bit-identical GPU scores
+        gs = run.scores.cpu().numpy()[0]
+        assert (gs[:, [10, 20, 30, 40]] == gs[:, [5]]).all()
+        assert np.array_equal(got_cnt, cnt)
+        if kb in (3, 4, 1):   # the tie group decides: must match the oracle exactly
+            assert np.array_equal(got_idx, idx), (got_idx, idx)
+        else:
+            check_selection(got_idx, got_cnt, idx, cnt, sc, ns, nr, kb, "extremes")
+
+
+def test_attention_list_semantics(gpu_lib):
+    """Order of the list is irrelevant, entries past sel_count / negative / out of
+    range are ignored, an empty list leaves only the draft segment."""
+    case = workloads.to_device(workloads.make_case(SMALL, seed=41), "cuda")
+    run = GpuRun(gpu_lib, case)
+    nb = 63
+    idx = torch.tensor([[[5, 1, 62, 17, 9, -1, 200, 3], [0, 62, 61, 2, 8, 8, 8, 8]]], dtype=torch.int32, device="cuda")
+    cnt = torch.tensor([[7, 4]], dtype=torch.int32, device="cuda")
+    run.attend(idx, cnt)
+    torch.cuda.synchronize()
+    # head 0: -1 and 200 are skipped, the 8th entry (3) lies past sel_count = 7
+    ref_idx = np.array([[1, 5, 9, 17, 62, -1, -1, -1], [0, 2, 61, 62, -1, -1, -1, -1]], np.int32)
+    _check_attn(run, case, [(ref_idx, np.array([5, 4], np.int32))], "list semantics")
+    # sorted list gives the same numbers as the shuffled one up to rounding order
+    a = run.out.float().clone()
+    run.attend(torch.from_numpy(ref_idx)[None].cuda(), torch.tensor([[5, 4]], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert (run.out.float() - a).abs().max() <= 2e-2
+    # empty list
+    run.attend(idx, torch.zeros_like(cnt))
+    torch.cuda.synchronize()
+    _check_attn(run, case, [(ref_idx, np.array([0, 0], np.int32))], "empty list")
+
+
+def test_incremental_summaries_and_stale_refresh(gpu_lib):
+    case = workloads.to_device(workloads.make_case(SMALL, seed=51), "cuda")
+    run = GpuRun(gpu_lib, case)
+    run.summarize(0, 40)
+    torch.cuda.synchronize()
+    o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0)
+    got = _to_np(run.kmax)[0].transpose(1, 0, 2)
+    assert np.array_equal(got[:40], kmax[:40]) and (got[40:] == 0).all()
+    run.refresh(stale=40)      # recomputes only blocks 40..: the result must now be complete
+    torch.cuda.synchronize()
+    assert np.array_equal(_to_np(run.kmax)[0].transpose(1, 0, 2), kmax)
+    assert np.array_equal(_to_np(run.kmin)[0].transpose(1, 0, 2), kmin)
+    check_selection(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0], idx, cnt, sc,
+                    case["ns"], case["nr"], case["k_blocks"], "stale refresh")
+    _check_attn(run, case, None, "stale refresh full")
+
+
+def test_runs_on_a_side_stream_and_is_deterministic(gpu_lib):
+    case = workloads.to_device(workloads.make_case(SMALL, seed=61), "cuda")
+    run = GpuRun(gpu_lib, case)
+    st = torch.cuda.Stream()
+    outs = []
+    for _ in range(2):
+        st.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(st):
+            run.out.zero_()
+            run.summarize(); run.select(); run.attend()
+        st.synchronize()
+        outs.append((run.out.clone(), run.sel_idx.clone(), run.lse.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
+    o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0)
+    _check_attn(run, case, [(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0])], "side stream")

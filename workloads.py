@@ -157,3 +157,12 @@ def oracle_views(case, b):
     V = case["v"][b, :, :L].permute(1, 0, 2).contiguous().cpu()
     return dict(Q=case["q"][b].cpu(), K=K, V=V, Kd=case["kd"][b].cpu(), Vd=case["vd"][b].cpu(),
                 parent=case["parent"][b].cpu().numpy(), L=L)
+
+
+def to_device(case, device):
+    """Copy of a case with every tensor moved to `device` (values unchanged)."""
+    out = dict(case)
+    for key, val in case.items():
+        if torch.is_tensor(val):
+            out[key] = val.to(device)
+    return out
