@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecPV verification path on one MI355X.
+
+Metric (the benchmark spec): partial-verify attention microseconds per verify step at
+128K context, LLaMA-3.1-8B attention shape, plus achieved HBM GB/s.
+
+One step = the partial-verification attention of a 60-node draft tree over the
+4096-token partial KV cache (1 sink + 55 retrieval + 8 local blocks of 64 tokens),
+for all 32 layers one after another, each layer with its own seeded K/V, queries
+and kept-block list.  The block lists come from an untimed full-verify refresh
+(summaries -> scores -> top-k), as in the paper's schedule where selection happens
+only on refresh steps.  Inputs are synthetic and resident in HBM before timing.
+
+Prints ONE JSON line.  Extra keys: "roofline", "cpu_baseline", "extras".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b_128k")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (default: the workload's)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def algorithmic_bytes_per_layer(case):
+    """Bytes one layer's partial-verify attention must move: the kept K and V blocks,
+    the draft tokens' K/V, the queries and the outputs (bf16 = 2 bytes)."""
+    sz = 2 if case["dtype"] == "bf16" else 4
+    kv = 0
+    for b in range(case["batch"]):
+        nb = (int(case["ctx_len"][b]) + case["B"] - 1) // case["B"]
+        kv += min(case["n_sel"], nb) * case["B"] * case["Hkv"] * case["D"] * 2 * sz
+    M, Hq, Hkv, D, batch = case["M"], case["Hq"], case["Hkv"], case["D"], case["batch"]
+    draft = batch * M * Hkv * D * 2 * sz
+    qo = batch * M * Hq * D * 2 * sz
+    return kv + draft + qo, kv
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads
+    import paper_2512_02337_amd as specpv
+    specpv.load()   # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = workloads.CONFIGS[args.workload]
+    n_layers = args.layers or cfg["layers"]
+
+    # ---- build every layer's inputs on the device, then the untimed refresh ----------
+    layers = []
+    t0 = time.time()
+    for layer in range(n_layers):
+        case = workloads.make_case(args.workload, seed=args.seed, layer=layer, device=dev)
+        kv = specpv.KV(case["k"], case["v"], case["ctx_len"], case["B"], case["max_blocks"])
+        tree = specpv.Tree(case["q"], case["kd"], case["vd"], case["parent"])
+        scfg = specpv.SelectCfg(case["ns"], case["nr"], case["k_blocks"], "mean")
+        shp = kv.summary_shape()
+        st = dict(case=case, kv=kv, tree=tree, cfg=scfg,
+                  kmax=torch.empty(shp, dtype=case["q"].dtype, device=dev),
+                  kmin=torch.empty(shp, dtype=case["q"].dtype, device=dev),
+                  sel_idx=torch.empty((case["batch"], case["Hkv"], scfg.n_sel), dtype=torch.int32, device=dev),
+                  sel_count=torch.empty((case["batch"], case["Hkv"]), dtype=torch.int32, device=dev),
+                  out=torch.empty_like(case["q"]),
+                  out_full=torch.empty_like(case["q"]))
+        layers.append(st)
+    ws_bytes = max(specpv.specpv_workspace_bytes(l["kv"], l["tree"], l["cfg"]) for l in layers)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)
+    for l in layers:   # untimed: the refresh that produces the kept-block lists
+        specpv.specpv_full_verify_refresh(l["kv"], l["tree"], l["kmax"], l["kmin"], 0, l["cfg"], l["out_full"], None,
+                                          l["sel_idx"], l["sel_count"], None, ws)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def partial_step():
+        for l in layers:
+            specpv.specpv_partial_verify_attn(l["kv"], l["tree"], l["sel_idx"], l["sel_count"], l["out"], None, ws)
+
+    def select_attend_step():
+        for l in layers:
+            specpv.specpv_select_blocks(l["kv"], l["tree"], l["kmax"], l["kmin"], l["cfg"], l["sel_idx"],
+                                        l["sel_count"], None, ws)
+            specpv.specpv_partial_verify_attn(l["kv"], l["tree"], l["sel_idx"], l["sel_count"], l["out"], None, ws)
+
+    def refresh_step():
+        for l in layers:
+            specpv.specpv_full_verify_refresh(l["kv"], l["tree"], l["kmax"], l["kmin"], -1, l["cfg"], l["out_full"],
+                                              None, l["sel_idx"], l["sel_count"], None, ws)
+
+    def timed(fn, steps, warmup, graph):
+        """ms per step over `steps` steps, after `warmup` untimed ones, with HIP events on
+        the stream the library launches on."""
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            run = fn
+            if graph:
+                fn()
+                stream.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    fn()
+                run = g.replay
+            for _ in range(warmup):
+                run()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(steps):
+                run()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+    use_graph = not args.no_graph
+    ms = timed(partial_step, args.steps, args.warmup, use_graph)
+    us_step = ms * 1e3
+    bytes_layer, kv_bytes_layer = algorithmic_bytes_per_layer(layers[0]["case"])
+    us_layer = us_step / n_layers
+    achieved = bytes_layer / (us_layer * 1e-6) / 1e9
+
+    extras = {}
+    if not args.no_extras:
+        k2 = max(3, args.steps // 10)
+        extras["partial_eager_us_per_step"] = round(timed(partial_step, k2, 3, False) * 1e3, 2)
+        extras["select_plus_attend_us_per_step"] = round(timed(select_attend_step, k2, 3, use_graph) * 1e3, 2)
+        rf = timed(refresh_step, max(2, k2 // 4), 1, use_graph) * 1e3
+        extras["full_verify_refresh_us_per_step"] = round(rf, 2)
+        c0 = layers[0]["case"]
+        full_bytes = sum(int(x) for x in c0["ctx_len"]) * c0["Hkv"] * c0["D"] * 2 * 2
+        extras["full_verify_refresh_kv_GBs"] = round(full_bytes * n_layers / (rf * 1e-6) / 1e9, 1)
+        extras["setup_s"] = round(setup_s, 1)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(layers[0], n_layers)
+
+    line = {
+        "metric": "partial_verify_attention_us_per_step",
+        "value": round(us_step, 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": layers[0]["case"]["dtype"],
+        "data": "synthetic",
+        "config": {"workload": args.workload, "layers": n_layers, "context": [int(x) for x in layers[0]["case"]["ctx_len"]],
+                   "block": layers[0]["case"]["B"], "kept_blocks": layers[0]["case"]["n_sel"], "tree_nodes": layers[0]["case"]["M"],
+                   "q_heads": layers[0]["case"]["Hq"], "kv_heads": layers[0]["case"]["Hkv"], "head_dim": layers[0]["case"]["D"],
+                   "launch": "hip_graph" if use_graph else "eager"},
+        "achieved_hbm_GBs": round(achieved, 1),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "specpv_partial_verify_attn (context attention + combine), per layer",
+                     "algorithmic_bytes_per_launch": bytes_layer, "us_per_launch": round(us_layer, 3)},
+        "cpu_baseline": cpu,
+        "extras": extras,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(layer, n_layers):
+    """The fp64 oracle, as it stands, on the host's cores: one layer of the same
+    workload (layer 0), attention-only partial step; scaled to the whole step."""
+    import numpy as np
+    import torch
+    import oracle
+    case = layer["case"]
+    B, Hkv = case["B"], case["Hkv"]
+    idx = layer["sel_idx"][0].cpu().numpy()
+    cnt = layer["sel_count"][0].cpu().numpy()
+    n = int(cnt.max())
+    # hand the oracle only the kept blocks (per KV head, renumbered 0..n-1): attention
+    # does not depend on where a block sits, so this is the same computation
+    blocks = torch.from_numpy(idx[:, :n].astype(np.int64)).to(case["k"].device)          # [Hkv, n]
+    tok = (blocks[:, :, None] * B + torch.arange(B, device=blocks.device)[None, None]).reshape(Hkv, n * B)
+    K = torch.gather(case["k"][0], 1, tok[:, :, None].expand(-1, -1, case["D"])).permute(1, 0, 2).contiguous().cpu()
+    V = torch.gather(case["v"][0], 1, tok[:, :, None].expand(-1, -1, case["D"])).permute(1, 0, 2).contiguous().cpu()
+    Q, Kd, Vd = case["q"][0].cpu(), case["kd"][0].cpu(), case["vd"][0].cpu()
+    parent = case["parent"][0].cpu().numpy()
+    t0 = time.time()
+    O, _, _ = oracle.tree_attention(Q, K, V, Kd, Vd, parent, B)
+    dt = time.time() - t0
+    err = float(np.abs(layer["out"][0].float().cpu().numpy() - O).max())
+    return {"value": round(dt * 1e6 * n_layers, 1), "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "layer 0 of %d (partial-verify attention, fp64, %.3f s), scaled x%d" % (n_layers, dt, n_layers),
+            "gpu_vs_oracle_max_abs_err_layer0": round(err, 6)}
+
+
+if __name__ == "__main__":
+    main()

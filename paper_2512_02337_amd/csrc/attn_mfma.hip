@@ -2,23 +2,28 @@
 // head dim 128 (Section 3.2: the draft tree attends over the kept blocks as one KV
 // segment; with all blocks kept this is the full verification of Section 3.3).
 //
-// Work decomposition.  A workgroup (4 wavefronts) owns one query head, one tile of
-// up to 64 tree nodes and one KV split; inside it every wavefront owns the whole
-// row tile and a contiguous range of 32-token chunks, so K and V go from global
-// memory straight into MFMA operand registers -- nothing is gathered and no LDS is
-// used in the main loop.  The G query heads of a KV head that read the same split
-// are placed on one XCD, next to each other in dispatch order, so that the split's
-// K/V bytes come from HBM once and from that XCD's L2 afterwards.
+// Work decomposition.  A workgroup (4 wavefronts, one per SIMD) owns one query head,
+// one tile of up to 64 tree nodes and one KV split; inside it every wavefront owns
+// the whole row tile and a contiguous range of 32-token chunks.  Nothing is
+// gathered: K and V rows go from their place in the cache straight into a small
+// per-wavefront LDS ring by LDS-DMA (global_load_lds), two chunks ahead of the
+// arithmetic, and from there into MFMA operand registers.  The G query heads of a
+// KV head that read the same split are placed on one XCD, next to each other in
+// dispatch order, so that the split's K/V bytes come from HBM once and from that
+// XCD's L2 afterwards.
 //
 // Per chunk (v_mfma_f32_32x32x16_bf16, fp32 accumulate):
 //   S^T = K . Q^T     tokens are the M index, query rows the N index, so each
-//                     lane holds 16 tokens of ONE query row: running max, sum and
-//                     rescale are lane-local (one cross-lane exchange with lane^32);
+//                     lane holds 16 tokens of ONE query row: max, sum and rescale
+//                     are lane-local (one exchange with lane ^ 32);
 //   O^T += V^T . P^T  the S^T accumulator, converted to bf16, already has the
-//                     B-operand layout; V is loaded as 4 channels x 8 tokens per
+//                     B-operand layout; V is read as 4 channels x 8 tokens per
 //                     lane and transposed in registers with byte permutes.
 // The contraction index may be permuted freely as long as both operands agree,
 // which is what makes the register layouts line up.
+//
+// The reference maximum of a row is only moved when the true maximum runs more than
+// 2^8 ahead of it, so rescaling the accumulators is rare.
 //
 // Epilogue: the four wavefronts merge their (O, m, l) through LDS and write one
 // split-KV partial per (head, split, node); combine.hip finishes.
@@ -27,9 +32,42 @@
 namespace specpv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 
-constexpr int kOPitch = 132;  // floats per staged output row (128 + 4: conflict-free 16-byte writes)
+constexpr int kOPitch = 132;         // floats per staged output row (128 + 4: conflict-free 16-byte writes)
+constexpr int kStageBytes = 16384;   // one 32-token chunk: 8 KiB of K + 8 KiB of V
+constexpr int kStages = 2;           // ring depth per wavefront
+constexpr int kRingBytes = 4 * kStages * kStageBytes;
+constexpr float kRescaleSlack = 8.f; // the reference max may lag the true max by 2^8
+
+// Exact n / d for 0 <= n < 2^31 with a host-prepared multiplier (no integer divide
+// on the GPU: one takes about forty vector instructions).
+struct FastDiv {
+    uint32_t mul, shift, d;
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return d == 1 ? n : (__umulhi(n, mul) >> shift); }
+};
+static FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;                       // l = ceil(log2 d)
+    if (d <= 1) { f.mul = 0; f.shift = 0; return f; }
+    f.mul = (uint32_t)(((1ull << (31 + l)) + d - 1) / d);   // ceil(2^(31+l) / d) <= 2^32 - 1 for d >= 2
+    f.shift = l - 1;
+    return f;
+}
+
+struct MfmaArgs {
+    const int32_t *sel_idx, *sel_count;
+    int n_sel;
+    float scale_log2;
+    int n_units, row_tiles;
+    FastDiv div_nsplit, div_hkv, div_B, div_W;
+};
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &u) { return __builtin_bit_cast(bf16x8, u); }
 
@@ -39,76 +77,300 @@ __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __b
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
 {
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     bf16x2 v = {(__bf16)a, (__bf16)b};
     return __builtin_bit_cast(uint32_t, v);
 }
+// acc + lo(p) + hi(p) for a packed bf16 pair
+__device__ __forceinline__ float add_bf16x2(uint32_t p, float acc)
+{
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p), ones, acc, false);
+}
 
-struct ChunkRegs {
-    uint4 kf[8];     // K rows as A operand: token = lane & 31, channels 16*ks + 8*(lane >> 5) .. +8
-    uint2 vr[2][8];  // V: for k-step ks2, slot e: token tt(ks2, e, lane >> 5), channels 4*(lane & 31) .. +4
-    uint32_t vmask;  // bit t: token t of the chunk exists
-};
+// 16 bytes per lane from global memory straight into LDS (no registers involved):
+// lane l of the wavefront lands at lds_dst + 16*l.
+__device__ __forceinline__ void dma16(const char *gsrc, char *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_dst, 16, 0, 0);
+}
 
+// Wait until at most 8*groups vector-memory operations of this wavefront are outstanding
+// (every DMA group below is 8 operations).
+__device__ __forceinline__ void wait_younger_groups(int groups)
+{
+    if (groups <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (groups == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (groups == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+}
+
+// The LDS reads of staged K / V are written in assembly so that the compiler does not
+// put a full vector-memory wait in front of them (it cannot tell which in-flight
+// LDS-DMA a read depends on); the waits are placed by hand instead.
+template <int OFF>
+__device__ __forceinline__ void lds_read_k(const uint32_t (&a)[8], uint4 (&k)[8])
+{
+    asm volatile(
+        "ds_read_b128 %0, %8 offset:%16\n\t"
+        "ds_read_b128 %1, %9 offset:%16\n\t"
+        "ds_read_b128 %2, %10 offset:%16\n\t"
+        "ds_read_b128 %3, %11 offset:%16\n\t"
+        "ds_read_b128 %4, %12 offset:%16\n\t"
+        "ds_read_b128 %5, %13 offset:%16\n\t"
+        "ds_read_b128 %6, %14 offset:%16\n\t"
+        "ds_read_b128 %7, %15 offset:%16\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2]), "=&v"(k[3]), "=&v"(k[4]), "=&v"(k[5]), "=&v"(k[6]), "=&v"(k[7])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "n"(OFF)
+        : "memory");
+}
+
+// V rows (e>>2)*8 + (e&3) [+4 for the upper half-wave, folded into addr] of both k-steps.
+__device__ __forceinline__ void lds_read_v(uint32_t addr, uint2 (&v)[16])
+{
+    asm volatile(
+        "ds_read_b64 %0, %16 offset:0\n\t"
+        "ds_read_b64 %1, %16 offset:256\n\t"
+        "ds_read_b64 %2, %16 offset:512\n\t"
+        "ds_read_b64 %3, %16 offset:768\n\t"
+        "ds_read_b64 %4, %16 offset:2048\n\t"
+        "ds_read_b64 %5, %16 offset:2304\n\t"
+        "ds_read_b64 %6, %16 offset:2560\n\t"
+        "ds_read_b64 %7, %16 offset:2816\n\t"
+        "ds_read_b64 %8, %16 offset:4096\n\t"
+        "ds_read_b64 %9, %16 offset:4352\n\t"
+        "ds_read_b64 %10, %16 offset:4608\n\t"
+        "ds_read_b64 %11, %16 offset:4864\n\t"
+        "ds_read_b64 %12, %16 offset:6144\n\t"
+        "ds_read_b64 %13, %16 offset:6400\n\t"
+        "ds_read_b64 %14, %16 offset:6656\n\t"
+        "ds_read_b64 %15, %16 offset:6912\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]),
+          "=&v"(v[8]), "=&v"(v[9]), "=&v"(v[10]), "=&v"(v[11]), "=&v"(v[12]), "=&v"(v[13]), "=&v"(v[14]), "=&v"(v[15])
+        : "v"(addr)
+        : "memory");
+}
+
+// max / sum over the two half-wavefronts (lane and lane ^ 32)
+__device__ __forceinline__ float max_xor32(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xor32(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+#ifdef SPECPV_TIMING
+__device__ unsigned long long g_dbg[512 * 8];
+#define STAMP(k) do { if (threadIdx.x == 0) g_dbg[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+extern "C" void specpv_debug_read(unsigned long long *host) { hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(g_dbg)); }
+#else
+#define STAMP(k)
+#endif
+
+// grid: x = r * 8 + xcd   (r = query head within the group + G * row tile),  y = unit / 8
+// with unit = ((b * Hkv + g) * nsplit + split).  Workgroups are handed to the 8 XCDs
+// round-robin in linear order and gridDim.x is a multiple of 8, so a unit (and the G
+// query heads that share its K/V bytes) stays on XCD unit % 8.
 template <int NRB, bool ALIGNED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void attn_ctx_mfma_kernel(Shape s, const int32_t *sel_idx, const int32_t *sel_count, int n_sel,
-                          Partials part, float scale_log2, int n_units, int GR)
+void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 {
-    extern __shared__ float lds[];
+    extern __shared__ char lds_raw[];
     constexpr int ROWS = NRB * 32;
-    float *ms = lds;                 // [4][ROWS]
-    float *ls = lds + 4 * ROWS;      // [4][ROWS]
-    float *obuf = lds + 8 * ROWS;    // [4][ROWS][kOPitch]
+    float *ms = (float *)lds_raw;            // [4][ROWS]
+    float *ls = ms + 4 * ROWS;               // [4][ROWS]
+    char *ring = lds_raw + 2048;             // [4 waves][kStages][K 8 KiB | V 8 KiB]
+    float *obuf = (float *)(lds_raw + 2048); // [4][ROWS][kOPitch], reuses the ring after the main loop
 
+    STAMP(0);
     // ---- which piece of work is this workgroup -------------------------------------
-    const int id = blockIdx.x;
-    const int xcd = id & 7, qd = id >> 3;
-    const int r = qd % GR, u = (qd / GR) * 8 + xcd;
-    if (u >= n_units) return;
-    const int sp = u % part.nsplit;
-    const int g = (u / part.nsplit) % s.Hkv;
-    const int b = u / (part.nsplit * s.Hkv);
-    const int hh = r % s.G, rt = r / s.G;
+    const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
+    const int u = blockIdx.y * 8 + xcd;
+    if (u >= a.n_units) return;
+    const int bg = (int)a.div_nsplit.div((uint32_t)u);
+    const int sp = u - bg * part.nsplit;
+    const int b = (int)a.div_hkv.div((uint32_t)bg);
+    const int g = bg - b * s.Hkv;
+    const int rt = r >= s.G ? 1 : 0;          // at most two row tiles (M <= 128)
+    const int hh = r - rt * s.G;
     const int h = g * s.G + hh;
     const int m0 = rt * 64;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, kg = lane >> 5;
 
-    const int L = s.ctx_len[b];
-    int nb = L > 0 ? (L + s.B - 1) / s.B : 0;
-    if (nb > s.max_blocks) nb = s.max_blocks;
-    const int32_t *sel = sel_idx ? sel_idx + ((int64_t)b * s.Hkv + g) * n_sel : nullptr;
-    int cnt = nb;
-    if (sel) cnt = max(0, min(sel_count[(int64_t)b * s.Hkv + g], n_sel));
-    const int64_t T = nb > 0 ? (int64_t)cnt * s.B : 0;
-    const int C = (int)((T + 31) / 32);
+    // Everything whose address only depends on the kernel arguments is requested up
+    // front, so that the cold-miss latencies of these small reads overlap: context
+    // length, list length, the kept-block ids this wavefront will most likely need
+    // (assuming a full list), and the query tile.
+    const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
     const int W = part.nsplit * 4, wsid = sp * 4 + wave;
-    const int c0 = (int)((int64_t)C * wsid / W), c1 = (int)((int64_t)C * (wsid + 1) / W);
-
-    const uint16_t *kbase = (const uint16_t *)s.k + (int64_t)b * s.sb + (int64_t)g * s.sh;
-    const uint16_t *vbase = (const uint16_t *)s.v + (int64_t)b * s.sb + (int64_t)g * s.sh;
-
-    // ---- Q fragments (B operand of S^T = K . Q^T): row = lane & 31 ------------------
-    bf16x8 qf[NRB][8];
+    const uint32_t Bu = (uint32_t)s.B;
+    const int L = s.ctx_len[b];
+    const int cnt_raw = sel ? a.sel_count[bg] : 0;
+    // chunks of a list of x blocks that precede this wavefront's share
+    auto first_chunk = [&](uint32_t chunks, int w) -> int {
+        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
+        return (int)((uint32_t)w * base + min((uint32_t)w, rem));
+    };
+    int spec_slot = 0, spec_vec = 0;
+    if (ALIGNED && sel) {
+        const uint32_t Cspec = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
+        spec_slot = (int)a.div_B.div((uint32_t)first_chunk(Cspec, wsid) * 32u);
+        const int x = spec_slot + lane;
+        spec_vec = x < a.n_sel ? sel[x] : -1;
+    }
+    uint4 qraw[NRB][8];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         const int j = m0 + rb * 32 + n;
         const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + min(j, s.M - 1)) * s.Hq + h) * 128 + kg * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            uint4 x = *(const uint4 *)(qrow + ks * 16);
-            if (j >= s.M) x = make_uint4(0, 0, 0, 0);
-            qf[rb][ks] = as_bf16x8(x);
-        }
+        for (int ks = 0; ks < 8; ++ks) qraw[rb][ks] = *(const uint4 *)(qrow + ks * 16);
     }
 
+    int nb = L > 0 ? (int)a.div_B.div((uint32_t)(L + s.B - 1)) : 0;
+    if (nb > s.max_blocks) nb = s.max_blocks;
+    int cnt = nb;
+    if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
+    const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;   // host guarantees max_blocks * B <= 2^30
+    const uint32_t C = (T + 31u) >> 5;
+    const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
+    const int nch = c1 - c0;
+
+    // uniform slab bases; per-lane byte offsets inside a slab fit 32 bits (host-checked)
+    const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
+    const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
+    const uint32_t st2 = (uint32_t)s.st * 2u;   // bytes per token row step
+
+    char *my_ring = ring + wave * (kStages * kStageBytes);
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)my_ring;
+    // K tile in LDS: row-major, 256 B per token, the 16-byte pieces of row t stored at
+    // piece index (p ^ (t & 7)) so that the operand reads below (32 lanes, same piece,
+    // different rows) spread over all banks.  Operand piece of k-step ks: 2*ks + kg.
+    uint32_t kread[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u)));
+    const uint32_t vread = ring_addr + 8192u + (uint32_t)kg * 1024u + (uint32_t)n * 8u;  // + stage*16384 + row*256
+
+    // ---- chunk -> token rows ------------------------------------------------------------
+    // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive
+    // and everything about it is wavefront-uniform.  The kept-block ids of the next 64
+    // list slots sit in a register (one per lane) and are picked with readlane.
+    int slot_base = 0, blkvec = 0;
+    auto refill = [&](int slot) {
+        slot_base = slot;
+        const int x = slot + lane;
+        blkvec = (sel && x < cnt) ? sel[x] : x;
+    };
+    // first token row of chunk ci (relative to c0), or -1 if the block is not valid
+    auto chunk_row0 = [&](int ci) -> int {
+        const uint32_t p0 = (uint32_t)(c0 + ci) * 32u;
+        const uint32_t slot = a.div_B.div(p0);
+        if ((int)slot - slot_base >= 64) refill((int)slot);
+        const int blk = __builtin_amdgcn_readlane(blkvec, (int)slot - slot_base);
+        if (blk < 0 || blk >= nb) return -1;
+        return blk * s.B + (int)(p0 - slot * Bu);
+    };
+    // general case: this lane's token (t = lane & 31) of chunk ci, or -1
+    auto lane_row = [&](int ci) -> int {
+        const uint32_t p = (uint32_t)(c0 + ci) * 32u + (uint32_t)n;
+        if (p >= T) return -1;
+        const uint32_t slot = a.div_B.div(p);
+        const int blk = sel ? sel[slot] : (int)slot;
+        if (blk < 0 || blk >= nb) return -1;
+        const int tok = blk * s.B + (int)(p - slot * Bu);
+        return tok < L ? tok : -1;
+    };
+
+    // per ring stage: validity bits and this lane's (clamped) token row of the chunk whose
+    // K sits there; issue order number of the youngest K / V group put into the stage
+    uint32_t vmask_st[kStages], tk_st[kStages];
+    int seq_k[kStages], seq_v[kStages], issued = 0;
+
+    auto issue_k = [&](int ci) {
+        const int stg = ci & (kStages - 1);
+        int tok;
+        if (ALIGNED) {
+            const int r0 = chunk_row0(ci);
+            tok = (r0 >= 0 && r0 + n < L) ? r0 + n : -1;
+        } else {
+            tok = lane_row(ci);
+        }
+        const uint32_t vm = (uint32_t)__ballot(tok >= 0);
+        const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
+        vmask_st[stg] = vm;
+        tk_st[stg] = tk;
+        seq_k[stg] = issued++;
+        char *dst = my_ring + stg * kStageBytes;
+        // DMA operation i brings rows 4i .. 4i+3, one 256-byte row per 16 lanes
+        const int r4 = lane >> 4, pos = lane & 15;
+        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u;   // piece pos ^ (row & 7)
+        if (ALIGNED && vm == 0xffffffffu) {
+            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
+            const char *src = kb + (size_t)t0 * st2;
+            const uint32_t lane_row_off = (uint32_t)r4 * st2;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                dma16(src + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4);
+                dma16(kb + (tv * st2 + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+            }
+        }
+    };
+    // V of the chunk whose K was issued into the same stage number (rows from tk_st / vmask_st)
+    auto issue_v = [&](int ci) {
+        const int stg = ci & (kStages - 1);
+        const uint32_t tk = tk_st[stg];
+        seq_v[stg] = issued++;
+        char *dst = my_ring + stg * kStageBytes + 8192;
+        const int r4 = lane >> 4, dch = lane & 15;
+        if (ALIGNED && vmask_st[stg] == 0xffffffffu) {
+            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
+            const char *src = vb + (size_t)t0 * st2;
+            const uint32_t lane_off = (uint32_t)r4 * st2 + (uint32_t)dch * 16u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dma16(src + (size_t)(4 * i) * st2 + lane_off, dst + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4);
+                dma16(vb + (tv * st2 + (uint32_t)dch * 16u), dst + i * 1024);
+            }
+        }
+    };
+
+    // ---- Q fragments (B operand of S^T = K . Q^T): row = lane & 31 ------------------
+    bf16x8 qf[NRB][8];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)   // rows past M repeat row M-1; their results are never stored
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = as_bf16x8(qraw[rb][ks]);
+    if (ALIGNED && nch > 0) {
+        const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
+        if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }   // the usual case
+        else refill(slot0);
+    }
+    // every load above has been consumed here: from now on the only vector-memory
+    // operations in flight are the LDS-DMA groups counted by the waits below
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    STAMP(1);
+
     f32x16 O[NRB][4];
-    float m_run[NRB], l_run[NRB];
+    float m_ref[NRB], l_run[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-        m_run[rb] = -INFINITY;
+        m_ref[rb] = -INFINITY;
         l_run[rb] = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -116,189 +378,186 @@ void attn_ctx_mfma_kernel(Shape s, const int32_t *sel_idx, const int32_t *sel_co
             for (int i = 0; i < 16; ++i) O[rb][j][i] = 0.f;
     }
 
-    // token row of lane's token t = lane & 31 in chunk c, or -1
-    auto lookup = [&](int c) -> int {
-        if (c >= c1) return -1;
-        const int64_t p = (int64_t)c * 32 + n;
-        if (p >= T) return -1;
-        const int slot = (int)(p / s.B);
-        const int blk = sel ? sel[slot] : slot;
-        if (blk < 0 || blk >= nb) return -1;
-        const int tok = blk * s.B + (int)(p - (int64_t)slot * s.B);
-        return tok < L ? tok : -1;
-    };
+    // ---- main loop ---------------------------------------------------------------------
+    // The K stages and the V stages are two independent rings of two chunks each:
+    // K(i+2) is requested as soon as K(i) has been read into registers, V(i+2) as soon
+    // as V(i) has been read.
+    if (nch > 0) { issue_k(0); issue_v(0); }
+    if (nch > 1) { issue_k(1); issue_v(1); }
+    for (int i = 0; i < nch; ++i) {
+        const int stg = i & 1;
+        const uint32_t vmask = vmask_st[stg];
+        uint4 kf[8];
+        wait_younger_groups(issued - 1 - seq_k[stg]);
+        if (stg) lds_read_k<kStageBytes>(kread, kf); else lds_read_k<0>(kread, kf);
+        if (i < 4) STAMP(2 + i);
+        const int seqv_keep = seq_v[stg];
+        if (i + 2 < nch) issue_k(i + 2);
 
-    auto issue = [&](ChunkRegs &cr, int tok) {
-        const uint32_t vm = (uint32_t)__ballot(tok >= 0);
-        cr.vmask = vm;
-        const int tk = tok >= 0 ? tok : 0;  // L > 0 here, row 0 exists: masked out later
-        const uint16_t *kr = kbase + (int64_t)tk * s.st + kg * 8;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) cr.kf[ks] = *(const uint4 *)(kr + ks * 16);
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int tt = 16 * ks2 + 8 * (e >> 2) + 4 * kg + (e & 3);
-                int tv;
-                if (ALIGNED) tv = min(__builtin_amdgcn_readfirstlane(tk) + tt, L - 1);  // 32 consecutive rows of one block
-                else tv = __shfl(tk, tt);
-                cr.vr[ks2][e] = *(const uint2 *)(vbase + (int64_t)tv * s.st + n * 4);
-            }
-    };
-
-    auto compute = [&](const ChunkRegs &cr) {
         f32x16 S[NRB];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) S[rb][i] = 0.f;
+            for (int x = 0; x < 16; ++x) S[rb][x] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb)
-                S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(cr.kf[ks]), qf[rb][ks], S[rb], 0, 0, 0);
-        const bool full = cr.vmask == 0xffffffffu;
+                S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[rb][ks], S[rb], 0, 0, 0);
+
         uint4 pf[NRB][2];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
-            if (!full) {
+            if (vmask != 0xffffffffu) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int tt = (i >> 2) * 8 + kg * 4 + (i & 3);
-                    if (!((cr.vmask >> tt) & 1u)) S[rb][i] = -INFINITY;
+                for (int x = 0; x < 16; ++x) {
+                    const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
+                    if (!((vmask >> tt) & 1u)) S[rb][x] = -INFINITY;
                 }
             }
-            float mx = S[rb][0];
+            float mx = fmaxf(S[rb][0], S[rb][1]);
 #pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[rb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[rb], mx * scale_log2);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_use);
-            float p[16], lsum = 0.f;
+            for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, S[rb][x]), S[rb][x + 1]);
+            mx = max_xor32(mx) * a.scale_log2;
+            // the reference max only moves when the true max gets more than 2^slack ahead
+            if (__any(mx > m_ref[rb] + kRescaleSlack)) {
+                const float m_new = mx > m_ref[rb] + kRescaleSlack ? mx : m_ref[rb];
+                const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref[rb] - m_new);
+                m_ref[rb] = m_new;
+                l_run[rb] *= alpha;
+                if (__any(alpha != 1.f && l_run[rb] != 0.f)) {   // nothing to rescale while O is still zero
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                p[i] = __builtin_amdgcn_exp2f(fmaf(S[rb][i], scale_log2, -m_use));
-                lsum += p[i];
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int x = 0; x < 16; ++x) O[rb][j][x] *= alpha;
+                }
             }
-            l_run[rb] = fmaf(l_run[rb], alpha, lsum);
-            m_run[rb] = m_new;
-            pf[rb][0] = make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
-                                   pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
-            pf[rb][1] = make_uint4(pack_bf16x2(p[8], p[9]), pack_bf16x2(p[10], p[11]),
-                                   pack_bf16x2(p[12], p[13]), pack_bf16x2(p[14], p[15]));
-            if (__any(alpha != 1.f)) {
+            const float m_use = m_ref[rb] == -INFINITY ? 0.f : m_ref[rb];
+            uint32_t pk[8];
+            float lsum = 0.f;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) O[rb][j][i] *= alpha;
+            for (int x = 0; x < 16; x += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(S[rb][x], a.scale_log2, -m_use));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(S[rb][x + 1], a.scale_log2, -m_use));
+                pk[x >> 1] = pack_bf16x2(p0, p1);
+                lsum = add_bf16x2(pk[x >> 1], lsum);   // the sum runs over the rounded weights the MFMA sees
             }
+            l_run[rb] += lsum;
+            pf[rb][0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            pf[rb][1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
         }
+
+        wait_younger_groups(issued - 1 - seqv_keep);
+        uint2 v[16];
+        lds_read_v(vread + stg * kStageBytes, v);
+        if (i + 2 < nch) issue_v(i + 2);
 #pragma unroll
         for (int ks2 = 0; ks2 < 2; ++ks2) {
             // 8 tokens x 4 channels  ->  4 channels x 8 tokens
+            const uint2 *w = v + 8 * ks2;
             uint4 vt[4];
-            const uint2 *v = cr.vr[ks2];
-            vt[0] = make_uint4(pack_lo(v[0].x, v[1].x), pack_lo(v[2].x, v[3].x), pack_lo(v[4].x, v[5].x), pack_lo(v[6].x, v[7].x));
-            vt[1] = make_uint4(pack_hi(v[0].x, v[1].x), pack_hi(v[2].x, v[3].x), pack_hi(v[4].x, v[5].x), pack_hi(v[6].x, v[7].x));
-            vt[2] = make_uint4(pack_lo(v[0].y, v[1].y), pack_lo(v[2].y, v[3].y), pack_lo(v[4].y, v[5].y), pack_lo(v[6].y, v[7].y));
-            vt[3] = make_uint4(pack_hi(v[0].y, v[1].y), pack_hi(v[2].y, v[3].y), pack_hi(v[4].y, v[5].y), pack_hi(v[6].y, v[7].y));
+            vt[0] = make_uint4(pack_lo(w[0].x, w[1].x), pack_lo(w[2].x, w[3].x), pack_lo(w[4].x, w[5].x), pack_lo(w[6].x, w[7].x));
+            vt[1] = make_uint4(pack_hi(w[0].x, w[1].x), pack_hi(w[2].x, w[3].x), pack_hi(w[4].x, w[5].x), pack_hi(w[6].x, w[7].x));
+            vt[2] = make_uint4(pack_lo(w[0].y, w[1].y), pack_lo(w[2].y, w[3].y), pack_lo(w[4].y, w[5].y), pack_lo(w[6].y, w[7].y));
+            vt[3] = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y), pack_hi(w[4].y, w[5].y), pack_hi(w[6].y, w[7].y));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb)
                     O[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[j]), as_bf16x8(pf[rb][ks2]), O[rb][j], 0, 0, 0);
         }
-    };
-
-    // ---- main loop: loads of chunk c+1 are in flight while chunk c is computed -------
-    if (c0 < c1) {
-        ChunkRegs ra, rb2;
-        issue(ra, lookup(c0));
-        int tok_next = lookup(c0 + 1);
-        for (int c = c0; c < c1; c += 2) {
-            if (c + 1 < c1) issue(rb2, tok_next);
-            tok_next = lookup(c + 2);
-            compute(ra);
-            if (c + 1 < c1) {
-                if (c + 2 < c1) issue(ra, tok_next);
-                tok_next = lookup(c + 3);
-                compute(rb2);
-            }
-        }
     }
+    STAMP(6);
+    __syncthreads();   // every wavefront is done with its ring: the epilogue reuses that LDS
 
     // ---- merge the four wavefronts ---------------------------------------------------
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-        l_run[rb] += __shfl_xor(l_run[rb], 32);
+        l_run[rb] = sum_xor32(l_run[rb]);
         if (kg == 0) {
-            ms[wave * ROWS + rb * 32 + n] = m_run[rb];
+            ms[wave * ROWS + rb * 32 + n] = m_ref[rb];
             ls[wave * ROWS + rb * 32 + n] = l_run[rb];
         }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        const int row = rb * 32 + n;
-        float mg = fmaxf(fmaxf(ms[row], ms[ROWS + row]), fmaxf(ms[2 * ROWS + row], ms[3 * ROWS + row]));
-        const float m_use = mg == -INFINITY ? 0.f : mg;
-        const float a = __builtin_amdgcn_exp2f(m_run[rb] - m_use);
-        float *dst = obuf + ((size_t)wave * ROWS + row) * kOPitch;
+        float *dst = obuf + ((size_t)wave * ROWS + rb * 32 + n) * kOPitch;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int mi = (i >> 2) * 8 + kg * 4 + (i & 3);
-            *(float4 *)(dst + 4 * mi) = make_float4(O[rb][0][i] * a, O[rb][1][i] * a, O[rb][2][i] * a, O[rb][3][i] * a);
+            *(float4 *)(dst + 4 * mi) = make_float4(O[rb][0][i], O[rb][1][i], O[rb][2][i], O[rb][3][i]);
         }
     }
     __syncthreads();
     constexpr int RPW = ROWS / 4;  // rows each wavefront finishes
-    const int64_t prow0 = (((int64_t)b * s.Hq + h) * part.nsplit + sp) * s.M;
-    for (int rr = 0; rr < RPW; ++rr) {
-        const int row = wave * RPW + rr;
-        const int j = m0 + row;
-        if (j >= s.M) break;
-        float2 acc = make_float2(0.f, 0.f);
+    const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
+    // weights of the four wavefronts for the rows this wavefront finishes (lane -> row)
+    float wgt[4], m_row = -INFINITY, l_row = 0.f;
+    {
+        const int row = wave * RPW + (lane & (RPW - 1));
+        float mw[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { mw[w] = ms[w * ROWS + row]; m_row = fmaxf(m_row, mw[w]); }
+        const float m_use = m_row == -INFINITY ? 0.f : m_row;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float2 x = *(const float2 *)(obuf + ((size_t)w * ROWS + row) * kOPitch + 2 * lane);
-            acc.x += x.x; acc.y += x.y;
+            wgt[w] = __builtin_amdgcn_exp2f(mw[w] - m_use);   // 0 for a wavefront without valid tokens
+            l_row = fmaf(ls[w * ROWS + row], wgt[w], l_row);
         }
-        *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc;
+    }
+#pragma unroll
+    for (int r0 = 0; r0 < RPW; r0 += 8) {
+        float2 acc[8];
+#pragma unroll
+        for (int uu = 0; uu < 8; ++uu) {
+            const int row = wave * RPW + r0 + uu;
+            acc[uu] = make_float2(0.f, 0.f);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float ww = __shfl(wgt[w], r0 + uu);
+                const float2 x = *(const float2 *)(obuf + ((size_t)w * ROWS + row) * kOPitch + 2 * lane);
+                acc[uu].x = fmaf(ww, x.x, acc[uu].x);
+                acc[uu].y = fmaf(ww, x.y, acc[uu].y);
+            }
+        }
+#pragma unroll
+        for (int uu = 0; uu < 8; ++uu) {
+            const int j = m0 + wave * RPW + r0 + uu;
+            if (j < s.M) *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc[uu];
+        }
     }
     if (lane < RPW) {
-        const int row = wave * RPW + lane;
-        const int j = m0 + row;
-        if (j < s.M) {
-            const float mg = fmaxf(fmaxf(ms[row], ms[ROWS + row]), fmaxf(ms[2 * ROWS + row], ms[3 * ROWS + row]));
-            const float m_use = mg == -INFINITY ? 0.f : mg;
-            float lt = 0.f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) lt += ls[w * ROWS + row] * __builtin_amdgcn_exp2f(ms[w * ROWS + row] - m_use);
-            part.ml[(prow0 + j) * 2] = mg;
-            part.ml[(prow0 + j) * 2 + 1] = lt;
-        }
+        const int j = m0 + wave * RPW + lane;
+        if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
     }
+    STAMP(7);
 }
 
 bool attn_ctx_mfma_supported(const Shape &s, int dtype)
 {
-    return dtype == SPECPV_BF16 && s.D == 128 && s.st % 8 == 0;
+    // per-lane byte offsets inside one (sequence, KV head) slab are kept in 32 bits
+    const int64_t span = ((int64_t)s.max_blocks * s.B + 64) * s.st * 2;
+    return dtype == SPECPV_BF16 && s.D == 128 && s.st % 8 == 0 && span < ((int64_t)1 << 31);
 }
 
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
                                 int n_sel, Partials p, hipStream_t st)
 {
-    const int row_tiles = (s.M + 63) / 64;
-    const int GR = s.G * row_tiles;
-    const int n_units = s.batch * s.Hkv * p.nsplit;
-    const int grid = ((n_units + 7) / 8) * 8 * GR;
-    const float scale_log2 = kLog2e / sqrtf(128.f);
+    MfmaArgs a;
+    a.sel_idx = sel_idx;
+    a.sel_count = sel_count;
+    a.n_sel = n_sel;
+    a.scale_log2 = kLog2e / sqrtf(128.f);
+    a.row_tiles = (s.M + 63) / 64;
+    a.n_units = s.batch * s.Hkv * p.nsplit;
+    a.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
+    a.div_hkv = make_fastdiv((uint32_t)s.Hkv);
+    a.div_B = make_fastdiv((uint32_t)s.B);
+    a.div_W = make_fastdiv((uint32_t)p.nsplit * 4u);
+    const int GR = s.G * a.row_tiles;
+    const dim3 grid(8 * GR, (a.n_units + 7) / 8);
+    if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool nrb1 = s.M <= 32;
     const bool aligned = s.B % 32 == 0;
     const int rows = nrb1 ? 32 : 64;
-    const size_t lds = (size_t)(8 * rows + 4 * rows * kOPitch) * sizeof(float);
+    const size_t lds = 2048 + (size_t)max(kRingBytes, 4 * rows * kOPitch * (int)sizeof(float));
 #define SPECPV_LAUNCH(NRB, AL)                                                                         \
     do {                                                                                               \
         static bool attr_set = false;                                                                  \
@@ -308,8 +567,7 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
             if (e != hipSuccess) return e;                                                             \
             attr_set = true;                                                                           \
         }                                                                                              \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, s, sel_idx, sel_count, n_sel, p,      \
-                           scale_log2, n_units, GR);                                                   \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, p, a);                                    \
     } while (0)
     if (nrb1) { if (aligned) SPECPV_LAUNCH(1, true); else SPECPV_LAUNCH(1, false); }
     else      { if (aligned) SPECPV_LAUNCH(2, true); else SPECPV_LAUNCH(2, false); }

@@ -11,67 +11,108 @@ template <typename T, int D>
 __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, void *out, float *lse,
                                                      float scale_log2)
 {
-    constexpr int DPL = D / 64;
-    __shared__ int par[SPECPV_MAX_M];
-    __shared__ int anc[SPECPV_MAX_M];
-    __shared__ int n_anc_sh;
+    constexpr int DPL = D / 64;   // channels per lane: d = lane + 64 * x
     const int lane = threadIdx.x;
     const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z, g = h / s.G;
-    for (int x = lane; x < s.M; x += 64) par[x] = s.parent[(int64_t)b * s.M + x];
-    __syncthreads();
-    if (lane == 0) {
-        // root path of node j; a malformed parent[] (not strictly decreasing) ends the walk
-        int n = 0, a = j;
-        while (a >= 0 && n < s.M) {
-            anc[n++] = a;
-            const int pa = par[a];
-            a = (pa < a) ? pa : -1;
-        }
-        n_anc_sh = n;
-    }
-    __syncthreads();
-    const int n_anc = n_anc_sh;
 
-    float qv[DPL], o[DPL];
+    // ---- every read whose address is known from the arguments goes out first ----------
+    const int32_t *par = s.parent + (int64_t)b * s.M;
+    const int par0 = lane < s.M ? par[lane] : -1;
+    const int par1 = lane + 64 < s.M ? par[lane + 64] : -1;
     const int64_t qrow = (((int64_t)b * s.M + j) * s.Hq + h) * D;
+    float qv[DPL];
 #pragma unroll
-    for (int x = 0; x < DPL; ++x) { qv[x] = Elem<T>::load(s.q, qrow + lane + 64 * x); o[x] = 0.f; }
-    float m = -INFINITY, l = 0.f;
-    for (int n = 0; n < n_anc; ++n) {
-        const int64_t drow = (((int64_t)b * s.M + anc[n]) * s.Hkv + g) * D;
-        float dot = 0.f;
+    for (int x = 0; x < DPL; ++x) qv[x] = Elem<T>::load(s.q, qrow + lane + 64 * x);
+    const int64_t prow0 = (((int64_t)b * s.Hq + h) * part.nsplit) * s.M + j;
+    float2 mlv = make_float2(-INFINITY, 0.f);   // lane sp holds (m, l) of split sp
+    if (lane < part.nsplit) mlv = *(const float2 *)(part.ml + (prow0 + (int64_t)lane * s.M) * 2);
+
+    // ---- root path of node j as a bit set (wave-uniform walk over the parent registers) --
+    unsigned long long anc_lo = 0ull, anc_hi = 0ull;
+    {
+        int a = j;
+        for (int guard = 0; a >= 0 && guard < s.M; ++guard) {
+            if (a < 64) anc_lo |= 1ull << a; else anc_hi |= 1ull << (a - 64);
+            const int pa = a < 64 ? __builtin_amdgcn_readlane(par0, a) : __builtin_amdgcn_readlane(par1, a - 64);
+            a = pa < a ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
+        }
+    }
+
+    // ---- context partials, merged relative to their own maximum ------------------------
+    const float m_ctx = wave_max(mlv.x);
+    const float m_ctx_use = m_ctx == -INFINITY ? 0.f : m_ctx;
+    const float w_mine = mlv.y > 0.f ? exp2f(mlv.x - m_ctx_use) : 0.f;
+    const float l_ctx = wave_sum(mlv.y * w_mine);
+    float o[DPL];
 #pragma unroll
-        for (int x = 0; x < DPL; ++x) dot = fmaf(qv[x], Elem<T>::load(s.kd, drow + lane + 64 * x), dot);
-        const float z = wave_sum(dot) * scale_log2;
-        const float m_new = fmaxf(m, z);
-        const float alpha = exp2f(m - m_new), pe = exp2f(z - m_new);
-        l = l * alpha + pe;
+    for (int x = 0; x < DPL; ++x) o[x] = 0.f;
+    for (int sp0 = 0; sp0 < part.nsplit; sp0 += 8) {
+        float po[8][DPL];
 #pragma unroll
-        for (int x = 0; x < DPL; ++x)
-            o[x] = fmaf(pe, Elem<T>::load(s.vd, drow + lane + 64 * x), o[x] * alpha);
+        for (int u = 0; u < 8; ++u) {
+            const int sp = min(sp0 + u, part.nsplit - 1);
+            const int64_t prow = prow0 + (int64_t)sp * s.M;
+#pragma unroll
+            for (int x = 0; x < DPL; ++x) po[u][x] = part.o[prow * D + lane + 64 * x];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = sp0 + u < part.nsplit ? __shfl(w_mine, sp0 + u) : 0.f;
+#pragma unroll
+            for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, po[u][x], o[x]);
+        }
+    }
+
+    // ---- draft-tree segment: the node itself and its ancestors --------------------------
+    float m = -INFINITY, l = 0.f, od[DPL];
+#pragma unroll
+    for (int x = 0; x < DPL; ++x) od[x] = 0.f;
+    while (anc_lo | anc_hi) {
+        int a[4];
+        float kdv[4][DPL], vdv[4][DPL];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (anc_lo) { a[u] = __builtin_ctzll(anc_lo); anc_lo &= anc_lo - 1; }
+            else if (anc_hi) { a[u] = 64 + __builtin_ctzll(anc_hi); anc_hi &= anc_hi - 1; }
+            else a[u] = -1;
+            const int64_t drow = (((int64_t)b * s.M + max(a[u], 0)) * s.Hkv + g) * D;
+#pragma unroll
+            for (int x = 0; x < DPL; ++x) {
+                kdv[u][x] = Elem<T>::load(s.kd, drow + lane + 64 * x);
+                vdv[u][x] = Elem<T>::load(s.vd, drow + lane + 64 * x);
+            }
+        }
+        float z[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float dot = 0.f;
+#pragma unroll
+            for (int x = 0; x < DPL; ++x) dot = fmaf(qv[x], kdv[u][x], dot);
+            z[u] = a[u] >= 0 ? wave_sum(dot) * scale_log2 : -INFINITY;
+        }
+        const float m_new = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), m);   // z[0] is always finite
+        const float alpha = exp2f(m - m_new);
+        l *= alpha;
+#pragma unroll
+        for (int x = 0; x < DPL; ++x) od[x] *= alpha;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float pe = exp2f(z[u] - m_new);   // 0 for the unused slots
+            l += pe;
+#pragma unroll
+            for (int x = 0; x < DPL; ++x) od[x] = fmaf(pe, vdv[u][x], od[x]);
+        }
         m = m_new;
     }
-    // merge with the context partials
-    const int64_t prow0 = (((int64_t)b * s.Hq + h) * part.nsplit) * s.M + j;
-    float m_all = m;
-    for (int sp = 0; sp < part.nsplit; ++sp)
-        m_all = fmaxf(m_all, part.ml[(prow0 + (int64_t)sp * s.M) * 2]);
+
+    // ---- merge the two and store ---------------------------------------------------------
+    const float m_all = fmaxf(m, m_ctx);
     const float wd = exp2f(m - m_all);
-    float den = l * wd;
-#pragma unroll
-    for (int x = 0; x < DPL; ++x) o[x] *= wd;
-    for (int sp = 0; sp < part.nsplit; ++sp) {
-        const int64_t prow = prow0 + (int64_t)sp * s.M;
-        const float ms = part.ml[prow * 2], ls = part.ml[prow * 2 + 1];
-        if (ls == 0.f) continue;  // split without valid tokens
-        const float w = exp2f(ms - m_all);
-        den = fmaf(ls, w, den);
-#pragma unroll
-        for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, part.o[prow * D + lane + 64 * x], o[x]);
-    }
+    const float wc = m_ctx == -INFINITY ? 0.f : exp2f(m_ctx - m_all);
+    const float den = l * wd + l_ctx * wc;
     const float inv = 1.f / den;
 #pragma unroll
-    for (int x = 0; x < DPL; ++x) Elem<T>::store(out, qrow + lane + 64 * x, o[x] * inv);
+    for (int x = 0; x < DPL; ++x) Elem<T>::store(out, qrow + lane + 64 * x, (od[x] * wd + o[x] * wc) * inv);
     if (lse && lane == 0) lse[((int64_t)b * s.M + j) * s.Hq + h] = (m_all + log2f(den)) * kLn2;
 }
 
