@@ -2,12 +2,13 @@
 // head dim 128 (Section 3.2: the draft tree attends over the kept blocks as one KV
 // segment; with all blocks kept this is the full verification of Section 3.3).
 //
-// Work decomposition.  A workgroup (4 wavefronts, one per SIMD) owns one query head,
-// one tile of up to 64 tree nodes and one KV split; inside it every wavefront owns
-// the whole row tile and a contiguous range of 32-token chunks.  Nothing is
-// gathered: K and V rows go from their place in the cache straight into a small
-// per-wavefront LDS ring by LDS-DMA (global_load_lds), two chunks ahead of the
-// arithmetic, and from there into MFMA operand registers.  The G query heads of a
+// Work decomposition.  A workgroup (8 wavefronts, two per SIMD) owns one query head,
+// one tile of up to 64 tree nodes and one KV split; inside it four pairs of
+// wavefronts each own a contiguous range of 32-token chunks, the two wavefronts of
+// a pair taking 32 rows of the tile each.  Nothing is gathered: K and V rows go
+// from their place in the cache straight into a small per-pair LDS ring by LDS-DMA
+// (global_load_lds), two chunks ahead of the arithmetic, and from there into MFMA
+// operand registers.  The G query heads of a
 // KV head that read the same split are placed on one XCD, next to each other in
 // dispatch order, so that the split's K/V bytes come from HBM once and from that
 // XCD's L2 afterwards.
@@ -25,7 +26,7 @@
 // The reference maximum of a row is only moved when the true maximum runs more than
 // 2^8 ahead of it, so rescaling the accumulators is rare.
 //
-// Epilogue: the four wavefronts merge their (O, m, l) through LDS and write one
+// Epilogue: the four token groups merge their (O, m, l) through LDS and write one
 // split-KV partial per (head, split, node); combine.hip finishes.
 #include "internal.h"
 
@@ -176,16 +177,22 @@ extern "C" void specpv_debug_read(unsigned long long *host) { hipMemcpyFromSymbo
 // with unit = ((b * Hkv + g) * nsplit + split).  Workgroups are handed to the 8 XCDs
 // round-robin in linear order and gridDim.x is a multiple of 8, so a unit (and the G
 // query heads that share its K/V bytes) stays on XCD unit % 8.
-template <int NRB, bool ALIGNED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+//
+// Workgroup = 8 wavefronts = 4 token groups x 2 row blocks.  Wavefronts tg and tg + 4
+// sit on the same SIMD, work on the same chunks (rows 0..31 and 32..63 of the tile)
+// and share one LDS ring; the first of the pair requests the K rows, the second the V
+// rows.  Two workgroup barriers per chunk order "DMA landed -> both read" and "both
+// read -> stage may be refilled".  Every wavefront runs the same number of iterations
+// (the largest chunk count in the workgroup), so the barriers always match up.
+template <bool ALIGNED>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 {
     extern __shared__ char lds_raw[];
-    constexpr int ROWS = NRB * 32;
-    float *ms = (float *)lds_raw;            // [4][ROWS]
-    float *ls = ms + 4 * ROWS;               // [4][ROWS]
-    char *ring = lds_raw + 2048;             // [4 waves][kStages][K 8 KiB | V 8 KiB]
-    float *obuf = (float *)(lds_raw + 2048); // [4][ROWS][kOPitch], reuses the ring after the main loop
+    float *ms = (float *)lds_raw;            // [4 token groups][64 rows]
+    float *ls = ms + 4 * 64;                 // [4][64]
+    char *ring = lds_raw + 2048;             // [4 pairs][kStages][K 8 KiB | V 8 KiB]
+    float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
 
     STAMP(0);
     // ---- which piece of work is this workgroup -------------------------------------
@@ -203,18 +210,19 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tg = wave & 3, rb = wave >> 2;
     const int n = lane & 31, kg = lane >> 5;
 
     // Everything whose address only depends on the kernel arguments is requested up
     // front, so that the cold-miss latencies of these small reads overlap: context
     // length, list length, the kept-block ids this wavefront will most likely need
-    // (assuming a full list), and the query tile.
+    // (assuming a full list), and the query rows.
     const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
-    const int W = part.nsplit * 4, wsid = sp * 4 + wave;
+    const int W = part.nsplit * 4, wsid = sp * 4 + tg;
     const uint32_t Bu = (uint32_t)s.B;
     const int L = s.ctx_len[b];
     const int cnt_raw = sel ? a.sel_count[bg] : 0;
-    // chunks of a list of x blocks that precede this wavefront's share
+    // chunks of a list that precede the share of token group w; shares differ by at most one
     auto first_chunk = [&](uint32_t chunks, int w) -> int {
         const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
         return (int)((uint32_t)w * base + min((uint32_t)w, rem));
@@ -226,13 +234,12 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         const int x = spec_slot + lane;
         spec_vec = x < a.n_sel ? sel[x] : -1;
     }
-    uint4 qraw[NRB][8];
+    uint4 qraw[8];
+    {
+        const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
+        const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8;
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        const int j = m0 + rb * 32 + n;
-        const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + min(j, s.M - 1)) * s.Hq + h) * 128 + kg * 8;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qraw[rb][ks] = *(const uint4 *)(qrow + ks * 16);
+        for (int ks = 0; ks < 8; ++ks) qraw[ks] = *(const uint4 *)(qrow + ks * 16);
     }
 
     int nb = L > 0 ? (int)a.div_B.div((uint32_t)(L + s.B - 1)) : 0;
@@ -243,13 +250,14 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     const uint32_t C = (T + 31u) >> 5;
     const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
     const int nch = c1 - c0;
+    const int nch_max = first_chunk(C, sp * 4 + 1) - first_chunk(C, sp * 4);   // token group 0 has the most
 
     // uniform slab bases; per-lane byte offsets inside a slab fit 32 bits (host-checked)
     const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
     const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
     const uint32_t st2 = (uint32_t)s.st * 2u;   // bytes per token row step
 
-    char *my_ring = ring + wave * (kStages * kStageBytes);
+    char *my_ring = ring + tg * (kStages * kStageBytes);
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)my_ring;
     // K tile in LDS: row-major, 256 B per token, the 16-byte pieces of row t stored at
     // piece index (p ^ (t & 7)) so that the operand reads below (32 lanes, same piece,
@@ -290,12 +298,11 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         return tok < L ? tok : -1;
     };
 
-    // per ring stage: validity bits and this lane's (clamped) token row of the chunk whose
-    // K sits there; issue order number of the youngest K / V group put into the stage
-    uint32_t vmask_st[kStages], tk_st[kStages];
-    int seq_k[kStages], seq_v[kStages], issued = 0;
+    uint32_t vmask_st[kStages];   // validity bits of the chunk this wavefront last requested rows for, per stage
 
-    auto issue_k = [&](int ci) {
+    // Request this wavefront's half of chunk ci (K rows if rb == 0, V rows if rb == 1): 8 DMA
+    // operations, operation i brings rows 4i .. 4i+3, one 256-byte row per 16 lanes.
+    auto issue = [&](int ci) {
         const int stg = ci & (kStages - 1);
         int tok;
         if (ALIGNED) {
@@ -307,15 +314,15 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
         vmask_st[stg] = vm;
-        tk_st[stg] = tk;
-        seq_k[stg] = issued++;
-        char *dst = my_ring + stg * kStageBytes;
-        // DMA operation i brings rows 4i .. 4i+3, one 256-byte row per 16 lanes
         const int r4 = lane >> 4, pos = lane & 15;
-        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u;   // piece pos ^ (row & 7)
+        // K pieces are swizzled (piece pos ^ (row & 7)), V pieces are not
+        const uint32_t sw_even = rb == 0 ? 16u * (uint32_t)(pos ^ r4) : 16u * (uint32_t)pos;
+        const uint32_t sw_odd = rb == 0 ? (sw_even ^ 64u) : sw_even;
+        const char *base = rb == 0 ? kb : vb;
+        char *dst = my_ring + stg * kStageBytes + rb * 8192;
         if (ALIGNED && vm == 0xffffffffu) {
             const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
-            const char *src = kb + (size_t)t0 * st2;
+            const char *src = base + (size_t)t0 * st2;
             const uint32_t lane_row_off = (uint32_t)r4 * st2;
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -324,133 +331,97 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4);
-                dma16(kb + (tv * st2 + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
-            }
-        }
-    };
-    // V of the chunk whose K was issued into the same stage number (rows from tk_st / vmask_st)
-    auto issue_v = [&](int ci) {
-        const int stg = ci & (kStages - 1);
-        const uint32_t tk = tk_st[stg];
-        seq_v[stg] = issued++;
-        char *dst = my_ring + stg * kStageBytes + 8192;
-        const int r4 = lane >> 4, dch = lane & 15;
-        if (ALIGNED && vmask_st[stg] == 0xffffffffu) {
-            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
-            const char *src = vb + (size_t)t0 * st2;
-            const uint32_t lane_off = (uint32_t)r4 * st2 + (uint32_t)dch * 16u;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dma16(src + (size_t)(4 * i) * st2 + lane_off, dst + i * 1024);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4);
-                dma16(vb + (tv * st2 + (uint32_t)dch * 16u), dst + i * 1024);
+                dma16(base + (tv * st2 + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
             }
         }
     };
 
     // ---- Q fragments (B operand of S^T = K . Q^T): row = lane & 31 ------------------
-    bf16x8 qf[NRB][8];
+    bf16x8 qf[8];
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)   // rows past M repeat row M-1; their results are never stored
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = as_bf16x8(qraw[rb][ks]);
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
     if (ALIGNED && nch > 0) {
         const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
         if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }   // the usual case
         else refill(slot0);
     }
     // every load above has been consumed here: from now on the only vector-memory
-    // operations in flight are the LDS-DMA groups counted by the waits below
+    // operations of this wavefront in flight are its own DMA groups (8 operations each)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     STAMP(1);
 
-    f32x16 O[NRB][4];
-    float m_ref[NRB], l_run[NRB];
+    f32x16 O[4];
+    float m_ref = -INFINITY, l_run = 0.f;
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        m_ref[rb] = -INFINITY;
-        l_run[rb] = 0.f;
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[rb][j][i] = 0.f;
-    }
+        for (int i = 0; i < 16; ++i) O[j][i] = 0.f;
 
     // ---- main loop ---------------------------------------------------------------------
-    // The K stages and the V stages are two independent rings of two chunks each:
-    // K(i+2) is requested as soon as K(i) has been read into registers, V(i+2) as soon
-    // as V(i) has been read.
-    if (nch > 0) { issue_k(0); issue_v(0); }
-    if (nch > 1) { issue_k(1); issue_v(1); }
-    for (int i = 0; i < nch; ++i) {
+    if (nch > 0) issue(0);
+    if (nch > 1) issue(1);
+    for (int i = 0; i < nch_max; ++i) {
+        const bool active = i < nch;
         const int stg = i & 1;
-        const uint32_t vmask = vmask_st[stg];
+        // own half of chunk i has landed (the only younger group is chunk i+1's)
+        if (i + 1 < nch) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();          // ... and so has the partner's half
         uint4 kf[8];
-        wait_younger_groups(issued - 1 - seq_k[stg]);
-        if (stg) lds_read_k<kStageBytes>(kread, kf); else lds_read_k<0>(kread, kf);
+        uint2 v[16];
+        const uint32_t vmask = vmask_st[stg];
+        if (active) {
+            if (stg) lds_read_k<kStageBytes>(kread, kf); else lds_read_k<0>(kread, kf);
+            lds_read_v(vread + stg * kStageBytes, v);
+        }
+        __builtin_amdgcn_s_barrier();          // both wavefronts of the pair hold chunk i in registers
         if (i < 4) STAMP(2 + i);
-        const int seqv_keep = seq_v[stg];
-        if (i + 2 < nch) issue_k(i + 2);
+        if (i + 2 < nch) issue(i + 2);
+        if (!active) continue;
 
-        f32x16 S[NRB];
+        f32x16 S;
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) S[rb][x] = 0.f;
+        for (int x = 0; x < 16; ++x) S[x] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb)
-                S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[rb][ks], S[rb], 0, 0, 0);
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[ks], S, 0, 0, 0);
 
-        uint4 pf[NRB][2];
+        if (vmask != 0xffffffffu) {
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            if (vmask != 0xffffffffu) {
-#pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
-                    if (!((vmask >> tt) & 1u)) S[rb][x] = -INFINITY;
-                }
+            for (int x = 0; x < 16; ++x) {
+                const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
+                if (!((vmask >> tt) & 1u)) S[x] = -INFINITY;
             }
-            float mx = fmaxf(S[rb][0], S[rb][1]);
-#pragma unroll
-            for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, S[rb][x]), S[rb][x + 1]);
-            mx = max_xor32(mx) * a.scale_log2;
-            // the reference max only moves when the true max gets more than 2^slack ahead
-            if (__any(mx > m_ref[rb] + kRescaleSlack)) {
-                const float m_new = mx > m_ref[rb] + kRescaleSlack ? mx : m_ref[rb];
-                const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref[rb] - m_new);
-                m_ref[rb] = m_new;
-                l_run[rb] *= alpha;
-                if (__any(alpha != 1.f && l_run[rb] != 0.f)) {   // nothing to rescale while O is still zero
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int x = 0; x < 16; ++x) O[rb][j][x] *= alpha;
-                }
-            }
-            const float m_use = m_ref[rb] == -INFINITY ? 0.f : m_ref[rb];
-            uint32_t pk[8];
-            float lsum = 0.f;
-#pragma unroll
-            for (int x = 0; x < 16; x += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(S[rb][x], a.scale_log2, -m_use));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(S[rb][x + 1], a.scale_log2, -m_use));
-                pk[x >> 1] = pack_bf16x2(p0, p1);
-                lsum = add_bf16x2(pk[x >> 1], lsum);   // the sum runs over the rounded weights the MFMA sees
-            }
-            l_run[rb] += lsum;
-            pf[rb][0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-            pf[rb][1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
         }
-
-        wait_younger_groups(issued - 1 - seqv_keep);
-        uint2 v[16];
-        lds_read_v(vread + stg * kStageBytes, v);
-        if (i + 2 < nch) issue_v(i + 2);
+        float mx = fmaxf(S[0], S[1]);
+#pragma unroll
+        for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, S[x]), S[x + 1]);
+        mx = max_xor32(mx) * a.scale_log2;
+        // the reference max only moves when the true max gets more than 2^slack ahead
+        if (__any(mx > m_ref + kRescaleSlack)) {
+            const float m_new = mx > m_ref + kRescaleSlack ? mx : m_ref;
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            l_run *= alpha;
+            if (__any(alpha != 1.f && l_run != 0.f)) {   // nothing to rescale while O is still zero
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) O[j][x] *= alpha;
+            }
+        }
+        const float m_use = m_ref == -INFINITY ? 0.f : m_ref;
+        uint32_t pk[8];
+        float lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; x += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(S[x], a.scale_log2, -m_use));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(S[x + 1], a.scale_log2, -m_use));
+            pk[x >> 1] = pack_bf16x2(p0, p1);
+            lsum = add_bf16x2(pk[x >> 1], lsum);   // the sum runs over the rounded weights the MFMA sees
+        }
+        l_run += lsum;
+        const uint4 pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]), pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
 #pragma unroll
         for (int ks2 = 0; ks2 < 2; ++ks2) {
             // 8 tokens x 4 channels  ->  4 channels x 8 tokens
@@ -462,64 +433,61 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
             vt[3] = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y), pack_hi(w[4].y, w[5].y), pack_hi(w[6].y, w[7].y));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int rb = 0; rb < NRB; ++rb)
-                    O[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[j]), as_bf16x8(pf[rb][ks2]), O[rb][j], 0, 0, 0);
+                O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[j]), as_bf16x8(ks2 ? pf1 : pf0), O[j], 0, 0, 0);
         }
     }
     STAMP(6);
-    __syncthreads();   // every wavefront is done with its ring: the epilogue reuses that LDS
+    __syncthreads();   // every wavefront is done with the rings: the epilogue reuses that LDS
 
-    // ---- merge the four wavefronts ---------------------------------------------------
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        l_run[rb] = sum_xor32(l_run[rb]);
+    // ---- merge the four token groups ---------------------------------------------------
+    {
+        l_run = sum_xor32(l_run);
+        const int row = rb * 32 + n;
         if (kg == 0) {
-            ms[wave * ROWS + rb * 32 + n] = m_ref[rb];
-            ls[wave * ROWS + rb * 32 + n] = l_run[rb];
+            ms[tg * 64 + row] = m_ref;
+            ls[tg * 64 + row] = l_run;
         }
-        float *dst = obuf + ((size_t)wave * ROWS + rb * 32 + n) * kOPitch;
+        float *dst = obuf + ((size_t)tg * 64 + row) * kOPitch;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int mi = (i >> 2) * 8 + kg * 4 + (i & 3);
-            *(float4 *)(dst + 4 * mi) = make_float4(O[rb][0][i], O[rb][1][i], O[rb][2][i], O[rb][3][i]);
+            *(float4 *)(dst + 4 * mi) = make_float4(O[0][i], O[1][i], O[2][i], O[3][i]);
         }
     }
     __syncthreads();
-    constexpr int RPW = ROWS / 4;  // rows each wavefront finishes
+    constexpr int RPW = 8;  // rows each wavefront finishes
     const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
-    // weights of the four wavefronts for the rows this wavefront finishes (lane -> row)
+    // weights of the four token groups for the rows this wavefront finishes (lane -> row)
     float wgt[4], m_row = -INFINITY, l_row = 0.f;
     {
         const int row = wave * RPW + (lane & (RPW - 1));
         float mw[4];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) { mw[w] = ms[w * ROWS + row]; m_row = fmaxf(m_row, mw[w]); }
+        for (int w = 0; w < 4; ++w) { mw[w] = ms[w * 64 + row]; m_row = fmaxf(m_row, mw[w]); }
         const float m_use = m_row == -INFINITY ? 0.f : m_row;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            wgt[w] = __builtin_amdgcn_exp2f(mw[w] - m_use);   // 0 for a wavefront without valid tokens
-            l_row = fmaf(ls[w * ROWS + row], wgt[w], l_row);
+            wgt[w] = __builtin_amdgcn_exp2f(mw[w] - m_use);   // 0 for a token group without valid tokens
+            l_row = fmaf(ls[w * 64 + row], wgt[w], l_row);
         }
     }
+    {
+        float2 acc[RPW];
 #pragma unroll
-    for (int r0 = 0; r0 < RPW; r0 += 8) {
-        float2 acc[8];
-#pragma unroll
-        for (int uu = 0; uu < 8; ++uu) {
-            const int row = wave * RPW + r0 + uu;
+        for (int uu = 0; uu < RPW; ++uu) {
+            const int row = wave * RPW + uu;
             acc[uu] = make_float2(0.f, 0.f);
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float ww = __shfl(wgt[w], r0 + uu);
-                const float2 x = *(const float2 *)(obuf + ((size_t)w * ROWS + row) * kOPitch + 2 * lane);
+                const float ww = __shfl(wgt[w], uu);
+                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + 2 * lane);
                 acc[uu].x = fmaf(ww, x.x, acc[uu].x);
                 acc[uu].y = fmaf(ww, x.y, acc[uu].y);
             }
         }
 #pragma unroll
-        for (int uu = 0; uu < 8; ++uu) {
-            const int j = m0 + wave * RPW + r0 + uu;
+        for (int uu = 0; uu < RPW; ++uu) {
+            const int j = m0 + wave * RPW + uu;
             if (j < s.M) *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc[uu];
         }
     }
@@ -554,23 +522,20 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     const int GR = s.G * a.row_tiles;
     const dim3 grid(8 * GR, (a.n_units + 7) / 8);
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
-    const bool nrb1 = s.M <= 32;
     const bool aligned = s.B % 32 == 0;
-    const int rows = nrb1 ? 32 : 64;
-    const size_t lds = 2048 + (size_t)max(kRingBytes, 4 * rows * kOPitch * (int)sizeof(float));
-#define SPECPV_LAUNCH(NRB, AL)                                                                         \
+    const size_t lds = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
+#define SPECPV_LAUNCH(AL)                                                                              \
     do {                                                                                               \
         static bool attr_set = false;                                                                  \
-        auto kern = attn_ctx_mfma_kernel<NRB, AL>;                                                     \
+        auto kern = attn_ctx_mfma_kernel<AL>;                                                          \
         if (!attr_set) {                                                                               \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
             if (e != hipSuccess) return e;                                                             \
             attr_set = true;                                                                           \
         }                                                                                              \
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, p, a);                                    \
+        hipLaunchKernelGGL(kern, grid, dim3(512), lds, st, s, p, a);                                    \
     } while (0)
-    if (nrb1) { if (aligned) SPECPV_LAUNCH(1, true); else SPECPV_LAUNCH(1, false); }
-    else      { if (aligned) SPECPV_LAUNCH(2, true); else SPECPV_LAUNCH(2, false); }
+    if (aligned) SPECPV_LAUNCH(true); else SPECPV_LAUNCH(false);
 #undef SPECPV_LAUNCH
     return hipGetLastError();
 }
