@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run 4 plain device copies of 256 MiB (read 256 MiB + write 256 MiB each) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -133,6 +136,14 @@ def main():
             e1.record(stream)
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / steps
+
+    if args.copy_calib:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     use_graph = not args.no_graph
     ms = timed(partial_step, args.steps, args.warmup, use_graph)
