@@ -23,6 +23,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per specpv_partial_verify_attn call at the default workload, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE scaled by a plain device copy (profiles/pmc_traffic_llama8b_128k.md); not measurable live.
+MEASURED_TRAFFIC_BYTES = {"llama8b_128k": int((19.9 + 9.9 + 7.6 + 0.47) * 2**20)}
 
 
 def parse():
@@ -187,8 +190,9 @@ def main():
                    "launch": "hip_graph" if use_graph else "eager"},
         "achieved_hbm_GBs": round(achieved, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "specpv_partial_verify_attn (context attention + combine), per layer",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if n_layers == cfg["layers"] else None,
+                     "kernel": "attn_ctx_mfma_kernel + combine_kernel = one specpv_partial_verify_attn call (one layer)",
                      "algorithmic_bytes_per_launch": bytes_layer, "us_per_launch": round(us_layer, 3)},
         "cpu_baseline": cpu,
         "extras": extras,
