@@ -277,6 +277,9 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         slot_base = slot;
         const int x = slot + lane;
         blkvec = (sel && x < cnt) ? sel[x] : x;
+        // wait for the list entries here, inside the rare branch, so that the common path
+        // that joins behind it carries no pending load (and no wait on the DMA prefetch)
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     };
     // first token row of chunk ci (relative to c0), or -1 if the block is not valid
     auto chunk_row0 = [&](int ci) -> int {
@@ -347,7 +350,11 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     }
     // every load above has been consumed here: from now on the only vector-memory
     // operations of this wavefront in flight are its own DMA groups (8 operations each)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // (as an instruction the compiler knows, not inline assembly: otherwise it assumes that the
+    // loads of the prologue may still be in flight at the loop header and waits for vmcnt(0),
+    // i.e. for the prefetch just issued, at the first use of Q in every iteration)
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt untouched
+    asm volatile("" ::: "memory");
     STAMP(1);
 
     f32x16 O[4];
