@@ -35,6 +35,8 @@ namespace specpv {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 
@@ -93,6 +95,17 @@ __device__ __forceinline__ float add_bf16x2(uint32_t p, float acc)
 __device__ __forceinline__ void dma16(const char *gsrc, char *lds_dst)
 {
     __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_dst, 16, 0, 0);
+}
+
+// Four such operations 1 KiB apart on both sides: gbase is wavefront-uniform, the per-lane
+// byte offsets alternate between off_even (operations 0, 2) and off_odd (1, 3).  The
+// immediate offset of the instruction is added to the global and to the LDS address.
+__device__ __forceinline__ void dma16x4(const char *gbase, uint32_t off_even, uint32_t off_odd, char *lds_dst)
+{
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 1024, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 2048, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 3072, 0);
 }
 
 // Wait until at most 8*groups vector-memory operations of this wavefront are outstanding
@@ -327,9 +340,17 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
             const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
             const char *src = base + (size_t)t0 * st2;
             const uint32_t lane_row_off = (uint32_t)r4 * st2;
+            if (st2 == 256u) {
+                // rows are 256 bytes apart (the usual head-major cache): four consecutive
+                // operations differ by 1 KiB on both sides, which the instruction's immediate
+                // offset covers, so they share one base address and one LDS base
+                dma16x4(src, lane_row_off + sw_even, lane_row_off + sw_odd, dst);
+                dma16x4(src + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                dma16(src + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+                for (int i = 0; i < 8; ++i)
+                    dma16(src + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -505,6 +526,393 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     STAMP(7);
 }
 
+// acc *= alpha for a 32x32 accumulator tile that lives in accumulation registers, without
+// giving the compiler a reason to keep a copy of the tile in vector registers (it would do
+// that on every iteration, for this rarely taken path).  The waits cover the distance that
+// the hardware needs between an MFMA writing the tile and these reads, and between these
+// writes and the next MFMA reading it; the compiler cannot see into the block.
+__device__ __forceinline__ void scale_acc_tile(f32x16 &acc, float alpha)
+{
+    float e[16];
+#pragma unroll
+    for (int x = 0; x < 16; ++x) e[x] = acc[x];
+    float t;
+    asm volatile(
+        "s_nop 15\n\ts_nop 15\n\t"
+        "v_accvgpr_read_b32 %16, %0\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %0, %16\n\t"
+        "v_accvgpr_read_b32 %16, %1\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %1, %16\n\t"
+        "v_accvgpr_read_b32 %16, %2\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %2, %16\n\t"
+        "v_accvgpr_read_b32 %16, %3\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %3, %16\n\t"
+        "v_accvgpr_read_b32 %16, %4\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %4, %16\n\t"
+        "v_accvgpr_read_b32 %16, %5\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %5, %16\n\t"
+        "v_accvgpr_read_b32 %16, %6\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %6, %16\n\t"
+        "v_accvgpr_read_b32 %16, %7\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %7, %16\n\t"
+        "v_accvgpr_read_b32 %16, %8\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %8, %16\n\t"
+        "v_accvgpr_read_b32 %16, %9\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %9, %16\n\t"
+        "v_accvgpr_read_b32 %16, %10\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %10, %16\n\t"
+        "v_accvgpr_read_b32 %16, %11\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %11, %16\n\t"
+        "v_accvgpr_read_b32 %16, %12\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %12, %16\n\t"
+        "v_accvgpr_read_b32 %16, %13\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %13, %16\n\t"
+        "v_accvgpr_read_b32 %16, %14\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %14, %16\n\t"
+        "v_accvgpr_read_b32 %16, %15\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %15, %16\n\t"
+        "s_nop 4"
+        : "+a"(e[0]), "+a"(e[1]), "+a"(e[2]), "+a"(e[3]), "+a"(e[4]), "+a"(e[5]), "+a"(e[6]), "+a"(e[7]),
+          "+a"(e[8]), "+a"(e[9]), "+a"(e[10]), "+a"(e[11]), "+a"(e[12]), "+a"(e[13]), "+a"(e[14]), "+a"(e[15]),
+          "=&v"(t)
+        : "v"(alpha));
+#pragma unroll
+    for (int x = 0; x < 16; ++x) acc[x] = e[x];
+}
+
+// ---- wide variant: one wavefront per SIMD, 64 rows per wavefront ---------------------------
+// Same decomposition over workgroups and the same partials as attn_ctx_mfma_kernel, but a
+// workgroup is 4 wavefronts (one per SIMD, up to 512 registers each) and every wavefront
+// owns its chunks alone: it requests K and V of a chunk into its private LDS ring (16 DMA
+// operations), reads the fragments once and uses them for both 32-row blocks of the tile.
+// No wavefront ever touches another one's ring, so the main loop has no barrier at all,
+// the LDS traffic per MFMA halves, and the two row blocks give the scheduler independent
+// MFMA and softmax work to overlap inside one wavefront.
+template <bool ALIGNED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
+{
+    extern __shared__ char lds_raw[];
+    float *ms = (float *)lds_raw;            // [4 token groups][64 rows]
+    float *ls = ms + 4 * 64;                 // [4][64]
+    char *ring = lds_raw + 2048;             // [4 wavefronts][kStages][K 8 KiB | V 8 KiB]
+    float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
+
+    const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
+    const int u = blockIdx.y * 8 + xcd;
+    if (u >= a.n_units) return;
+    const int bg = (int)a.div_nsplit.div((uint32_t)u);
+    const int sp = u - bg * part.nsplit;
+    const int b = (int)a.div_hkv.div((uint32_t)bg);
+    const int g = bg - b * s.Hkv;
+    const int rt = r >= s.G ? 1 : 0;
+    const int hh = r - rt * s.G;
+    const int h = g * s.G + hh;
+    const int m0 = rt * 64;
+
+    const int lane = threadIdx.x & 63;
+    const int tg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // token group = wavefront
+    const int n = lane & 31, kg = lane >> 5;
+
+    const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
+    const int W = part.nsplit * 4, wsid = sp * 4 + tg;
+    const uint32_t Bu = (uint32_t)s.B;
+    const int L = s.ctx_len[b];
+    const int cnt_raw = sel ? a.sel_count[bg] : 0;
+    auto first_chunk = [&](uint32_t chunks, int w) -> int {
+        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
+        return (int)((uint32_t)w * base + min((uint32_t)w, rem));
+    };
+    int spec_slot = 0, spec_vec = 0;
+    if (ALIGNED && sel) {
+        const uint32_t Cspec = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
+        spec_slot = (int)a.div_B.div((uint32_t)first_chunk(Cspec, wsid) * 32u);
+        const int x = spec_slot + lane;
+        spec_vec = x < a.n_sel ? sel[x] : -1;
+    }
+    uint4 qraw[2][8];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
+        const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qraw[rb][ks] = *(const uint4 *)(qrow + ks * 16);
+    }
+
+    int nb = L > 0 ? (int)a.div_B.div((uint32_t)(L + s.B - 1)) : 0;
+    if (nb > s.max_blocks) nb = s.max_blocks;
+    int cnt = nb;
+    if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
+    const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;
+    const uint32_t C = (T + 31u) >> 5;
+    const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
+    const int nch = c1 - c0;
+
+    const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
+    const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
+    const uint32_t st2 = (uint32_t)s.st * 2u;
+
+    char *my_ring = ring + tg * (kStages * kStageBytes);
+    int slot_base = 0, blkvec = 0;
+    auto refill = [&](int slot) {
+        slot_base = slot;
+        const int x = slot + lane;
+        blkvec = (sel && x < cnt) ? sel[x] : x;
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): inside the rare branch, see attn_ctx_mfma_kernel
+    };
+    auto chunk_row0 = [&](int ci) -> int {
+        const uint32_t p0 = (uint32_t)(c0 + ci) * 32u;
+        const uint32_t slot = a.div_B.div(p0);
+        if ((int)slot - slot_base >= 64) refill((int)slot);
+        const int blk = __builtin_amdgcn_readlane(blkvec, (int)slot - slot_base);
+        if (blk < 0 || blk >= nb) return -1;
+        return blk * s.B + (int)(p0 - slot * Bu);
+    };
+    auto lane_row = [&](int ci) -> int {
+        const uint32_t p = (uint32_t)(c0 + ci) * 32u + (uint32_t)n;
+        if (p >= T) return -1;
+        const uint32_t slot = a.div_B.div(p);
+        const int blk = sel ? sel[slot] : (int)slot;
+        if (blk < 0 || blk >= nb) return -1;
+        const int tok = blk * s.B + (int)(p - slot * Bu);
+        return tok < L ? tok : -1;
+    };
+
+    uint32_t vmask_st[kStages];
+
+    // Request chunk ci: 16 DMA operations, 8 for the K rows (pieces swizzled by row & 7) and
+    // 8 for the V rows; operation i of each brings rows 4i .. 4i+3, one 256-byte row per 16 lanes.
+    auto issue = [&](int ci) {
+        const int stg = ci & (kStages - 1);
+        int tok;
+        if (ALIGNED) {
+            const int r0 = chunk_row0(ci);
+            tok = (r0 >= 0 && r0 + n < L) ? r0 + n : -1;
+        } else {
+            tok = lane_row(ci);
+        }
+        const uint32_t vm = (uint32_t)__ballot(tok >= 0);
+        const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
+        vmask_st[stg] = vm;
+        const int r4 = lane >> 4, pos = lane & 15;
+        const uint32_t ksw_even = 16u * (uint32_t)(pos ^ r4), ksw_odd = ksw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+        char *dst = my_ring + stg * kStageBytes;
+        if (ALIGNED && vm == 0xffffffffu) {
+            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
+            const size_t row0 = (size_t)t0 * st2;
+            const uint32_t lane_row_off = (uint32_t)r4 * st2;
+            if (st2 == 256u) {
+                // rows are 256 bytes apart (the usual head-major cache): four consecutive
+                // operations differ by 1 KiB on both sides, which the instruction's immediate
+                // offset covers, so they share one base address and one LDS base
+                dma16x4(kb + row0, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst);
+                dma16x4(kb + row0 + 4096, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst + 4096);
+                dma16x4(vb + row0, lane_row_off + vsw, lane_row_off + vsw, dst + 8192);
+                dma16x4(vb + row0 + 4096, lane_row_off + vsw, lane_row_off + vsw, dst + 8192 + 4096);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    dma16(vb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + vsw), dst + 8192 + i * 1024);
+            }
+        } else {
+            uint32_t tv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) tv[i] = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dma16(kb + (tv[i] + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dma16(vb + (tv[i] + vsw), dst + 8192 + i * 1024);
+        }
+    };
+
+    if (ALIGNED && nch > 0) {
+        const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
+        if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }
+        else refill(slot0);
+    }
+    // every load above is complete from here on (an instruction the compiler knows, see
+    // attn_ctx_mfma_kernel): only this wavefront's DMA groups (16 operations each) are in flight
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+
+    f32x16 O[2][4];
+    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[rb][j][i] = 0.f;
+
+    // K / V fragments of one chunk, as the MFMAs want them (see attn_ctx_mfma_kernel)
+    struct Frags { uint4 k[8]; uint2 v[16]; uint32_t vmask; };
+    const char *kptr = my_ring + n * 256;
+    uint32_t koff[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) koff[ks] = ((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u));
+    const char *vptr = my_ring + 8192 + kg * 1024 + n * 8;
+    // Plain LDS loads: the compiler tracks when they arrive, so they can stay in flight
+    // behind the arithmetic of the previous chunk.
+    auto read_frags = [&](int ci, Frags &f) {
+        const int stg = ci & 1;
+        f.vmask = vmask_st[stg];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) f.k[ks] = *(const uint4 *)(kptr + stg * kStageBytes + koff[ks]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            f.v[e] = *(const uint2 *)(vptr + stg * kStageBytes + (e >> 2) * 2048 + (e & 3) * 256);
+    };
+    // The arithmetic of one chunk for both 32-row blocks.
+    auto compute = [&](const Frags &f) {
+        // V: 8 tokens x 4 channels  ->  4 channels x 8 tokens, once for both row blocks
+        uint4 vt[2][4];
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+            const uint2 *w = f.v + 8 * ks2;
+            vt[ks2][0] = make_uint4(pack_lo(w[0].x, w[1].x), pack_lo(w[2].x, w[3].x), pack_lo(w[4].x, w[5].x), pack_lo(w[6].x, w[7].x));
+            vt[ks2][1] = make_uint4(pack_hi(w[0].x, w[1].x), pack_hi(w[2].x, w[3].x), pack_hi(w[4].x, w[5].x), pack_hi(w[6].x, w[7].x));
+            vt[ks2][2] = make_uint4(pack_lo(w[0].y, w[1].y), pack_lo(w[2].y, w[3].y), pack_lo(w[4].y, w[5].y), pack_lo(w[6].y, w[7].y));
+            vt[ks2][3] = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y), pack_hi(w[4].y, w[5].y), pack_hi(w[6].y, w[7].y));
+        }
+        const uint32_t vmask = f.vmask;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            f32x16 S;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) S[x] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f.k[ks]), as_bf16x8(qraw[rb][ks]), S, 0, 0, 0);
+            float sv[16];
+#pragma unroll
+            for (int x = 0; x < 16; ++x) sv[x] = S[x];
+            if (vmask != 0xffffffffu) {
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
+                    const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
+                    if (!((vmask >> tt) & 1u)) sv[x] = -INFINITY;
+                }
+            }
+            float mx = fmaxf(sv[0], sv[1]);
+#pragma unroll
+            for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, sv[x]), sv[x + 1]);
+            mx = max_xor32(mx) * a.scale_log2;
+            if (__any(mx > m_ref[rb] + kRescaleSlack)) {
+                const float m_new = mx > m_ref[rb] + kRescaleSlack ? mx : m_ref[rb];
+                const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref[rb] - m_new);
+                m_ref[rb] = m_new;
+                l_run[rb] *= alpha;
+                if (__any(alpha != 1.f && l_run[rb] != 0.f)) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) scale_acc_tile(O[rb][j], alpha);
+                }
+            }
+            const float m_use = m_ref[rb] == -INFINITY ? 0.f : m_ref[rb];
+            uint32_t pk[8];
+            float lsum = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; x += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[x], a.scale_log2, -m_use));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[x + 1], a.scale_log2, -m_use));
+                pk[x >> 1] = pack_bf16x2(p0, p1);
+                lsum = add_bf16x2(pk[x >> 1], lsum);
+            }
+            l_run[rb] += lsum;
+            const uint4 pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]), pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+#pragma unroll
+            for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    O[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[ks2][j]), as_bf16x8(ks2 ? pf1 : pf0), O[rb][j], 0, 0, 0);
+        }
+    };
+    // every register of f has arrived (the compiler places the wait); nothing is emitted
+    auto settle = [&](const Frags &f) {
+#define SPECPV_K(i) "v"(__builtin_bit_cast(u32x4, f.k[i]))
+#define SPECPV_V(i) "v"(__builtin_bit_cast(u32x2, f.v[i]))
+        asm volatile("" ::SPECPV_K(0), SPECPV_K(1), SPECPV_K(2), SPECPV_K(3), SPECPV_K(4), SPECPV_K(5), SPECPV_K(6), SPECPV_K(7));
+        asm volatile("" ::SPECPV_V(0), SPECPV_V(1), SPECPV_V(2), SPECPV_V(3), SPECPV_V(4), SPECPV_V(5), SPECPV_V(6), SPECPV_V(7),
+                     SPECPV_V(8), SPECPV_V(9), SPECPV_V(10), SPECPV_V(11), SPECPV_V(12), SPECPV_V(13), SPECPV_V(14), SPECPV_V(15));
+#undef SPECPV_K
+#undef SPECPV_V
+    };
+    // One pipeline step: `cur` holds chunk i.  The fragments of chunk i + 1 are requested from
+    // LDS first and arrive while chunk i is being computed; chunk i + 2 is requested from
+    // memory into the stage that chunk i has left.
+    auto step = [&](int i, Frags &cur, Frags &nxt) {
+        if (i + 1 < nch) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // chunk i + 1 has landed (nothing younger is in flight)
+            read_frags(i + 1, nxt);
+        }
+        if (i + 2 < nch) {
+            settle(cur);      // the LDS reads of chunk i are complete: its stage may be overwritten
+            issue(i + 2);
+        }
+        compute(cur);
+    };
+
+    if (nch > 0) issue(0);
+    if (nch > 1) issue(1);
+    {
+        Frags fa, fb;
+        if (nch > 0) {
+            if (nch > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            read_frags(0, fa);
+        }
+        for (int i = 0; i < nch; i += 2) {
+            step(i, fa, fb);
+            if (i + 1 < nch) step(i + 1, fb, fa);
+        }
+    }
+    __syncthreads();   // every wavefront is done with its ring: the epilogue reuses that LDS
+
+    // ---- merge the four token groups ---------------------------------------------------
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const float lr = sum_xor32(l_run[rb]);
+        const int row = rb * 32 + n;
+        if (kg == 0) {
+            ms[tg * 64 + row] = m_ref[rb];
+            ls[tg * 64 + row] = lr;
+        }
+        float *dst = obuf + ((size_t)tg * 64 + row) * kOPitch;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int mi = (i >> 2) * 8 + kg * 4 + (i & 3);
+            *(float4 *)(dst + 4 * mi) = make_float4(O[rb][0][i], O[rb][1][i], O[rb][2][i], O[rb][3][i]);
+        }
+    }
+    __syncthreads();
+    constexpr int RPW = 16;  // rows each wavefront finishes
+    const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
+    float wgt[4], m_row = -INFINITY, l_row = 0.f;
+    {
+        const int row = tg * RPW + (lane & (RPW - 1));
+        float mw[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { mw[w] = ms[w * 64 + row]; m_row = fmaxf(m_row, mw[w]); }
+        const float m_use = m_row == -INFINITY ? 0.f : m_row;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            wgt[w] = __builtin_amdgcn_exp2f(mw[w] - m_use);
+            l_row = fmaf(ls[w * 64 + row], wgt[w], l_row);
+        }
+    }
+#pragma unroll
+    for (int u0 = 0; u0 < RPW; u0 += 8) {
+        float2 acc[8];
+#pragma unroll
+        for (int uu = 0; uu < 8; ++uu) {
+            const int row = tg * RPW + u0 + uu;
+            acc[uu] = make_float2(0.f, 0.f);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float ww = __shfl(wgt[w], u0 + uu);
+                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + 2 * lane);
+                acc[uu].x = fmaf(ww, x.x, acc[uu].x);
+                acc[uu].y = fmaf(ww, x.y, acc[uu].y);
+            }
+        }
+#pragma unroll
+        for (int uu = 0; uu < 8; ++uu) {
+            const int j = m0 + tg * RPW + u0 + uu;
+            if (j < s.M) *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc[uu];
+        }
+    }
+    if (lane < RPW) {
+        const int j = m0 + tg * RPW + lane;
+        if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
+    }
+}
+
 bool attn_ctx_mfma_supported(const Shape &s, int dtype)
 {
     // per-lane byte offsets inside one (sequence, KV head) slab are kept in 32 bits
@@ -542,7 +950,27 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
         }                                                                                              \
         hipLaunchKernelGGL(kern, grid, dim3(512), lds, st, s, p, a);                                    \
     } while (0)
-    if (aligned) SPECPV_LAUNCH(true); else SPECPV_LAUNCH(false);
+#define SPECPV_LAUNCH_WIDE(AL)                                                                         \
+    do {                                                                                               \
+        static bool attr_set = false;                                                                  \
+        auto kern = attn_ctx_mfma_wide_kernel<AL>;                                                     \
+        if (!attr_set) {                                                                               \
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            if (e != hipSuccess) return e;                                                             \
+            attr_set = true;                                                                           \
+        }                                                                                              \
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, p, a);                                    \
+    } while (0)
+    // Long token ranges per wavefront amortise the wide variant's longer prologue and epilogue;
+    // at a handful of chunks the eight-wavefront kernel hides latency better.
+    const int64_t chunks = (((int64_t)(sel_idx ? n_sel : s.max_blocks)) * s.B + 31) / 32;
+    const bool wide = chunks >= (int64_t)8 * 4 * p.nsplit;
+    if (wide) {
+        if (aligned) SPECPV_LAUNCH_WIDE(true); else SPECPV_LAUNCH_WIDE(false);
+    } else {
+        if (aligned) SPECPV_LAUNCH(true); else SPECPV_LAUNCH(false);
+    }
+#undef SPECPV_LAUNCH_WIDE
 #undef SPECPV_LAUNCH
     return hipGetLastError();
 }

@@ -27,6 +27,16 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
     float2 mlv = make_float2(-INFINITY, 0.f);   // lane sp holds (m, l) of split sp
     if (lane < part.nsplit) mlv = *(const float2 *)(part.ml + (prow0 + (int64_t)lane * s.M) * 2);
 
+    // ... including the first 8 context partials (all of them in the usual case)
+    float po[8][DPL];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int sp = min(u, part.nsplit - 1);
+        const int64_t prow = prow0 + (int64_t)sp * s.M;
+#pragma unroll
+        for (int x = 0; x < DPL; ++x) po[u][x] = part.o[prow * D + lane + 64 * x];
+    }
+
     // ---- root path of node j as a bit set (wave-uniform walk over the parent registers) --
     unsigned long long anc_lo = 0ull, anc_hi = 0ull;
     {
@@ -37,8 +47,27 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
             a = pa < a ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
         }
     }
+    // ---- second (and last) round of reads: draft K / V of the first 8 nodes of the path ----
+    auto pop = [&]() -> int {
+        int a = -1;
+        if (anc_lo) { a = __builtin_ctzll(anc_lo); anc_lo &= anc_lo - 1; }
+        else if (anc_hi) { a = 64 + __builtin_ctzll(anc_hi); anc_hi &= anc_hi - 1; }
+        return a;
+    };
+    int a8[8];
+    float kd8[8][DPL], vd8[8][DPL];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        a8[u] = pop();
+        const int64_t drow = (((int64_t)b * s.M + max(a8[u], 0)) * s.Hkv + g) * D;
+#pragma unroll
+        for (int x = 0; x < DPL; ++x) {
+            kd8[u][x] = Elem<T>::load(s.kd, drow + lane + 64 * x);
+            vd8[u][x] = Elem<T>::load(s.vd, drow + lane + 64 * x);
+        }
+    }
 
-    // ---- context partials, merged relative to their own maximum ------------------------
+    // ---- context partials, merged relative to their own maximum (first-round data) -------
     const float m_ctx = wave_max(mlv.x);
     const float m_ctx_use = m_ctx == -INFINITY ? 0.f : m_ctx;
     const float w_mine = mlv.y > 0.f ? exp2f(mlv.x - m_ctx_use) : 0.f;
@@ -46,8 +75,13 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
     float o[DPL];
 #pragma unroll
     for (int x = 0; x < DPL; ++x) o[x] = 0.f;
-    for (int sp0 = 0; sp0 < part.nsplit; sp0 += 8) {
-        float po[8][DPL];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const float w = u < part.nsplit ? __shfl(w_mine, u) : 0.f;
+#pragma unroll
+        for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, po[u][x], o[x]);
+    }
+    for (int sp0 = 8; sp0 < part.nsplit; sp0 += 8) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int sp = min(sp0 + u, part.nsplit - 1);
@@ -67,21 +101,8 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
     float m = -INFINITY, l = 0.f, od[DPL];
 #pragma unroll
     for (int x = 0; x < DPL; ++x) od[x] = 0.f;
-    while (anc_lo | anc_hi) {
-        int a[4];
-        float kdv[4][DPL], vdv[4][DPL];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (anc_lo) { a[u] = __builtin_ctzll(anc_lo); anc_lo &= anc_lo - 1; }
-            else if (anc_hi) { a[u] = 64 + __builtin_ctzll(anc_hi); anc_hi &= anc_hi - 1; }
-            else a[u] = -1;
-            const int64_t drow = (((int64_t)b * s.M + max(a[u], 0)) * s.Hkv + g) * D;
-#pragma unroll
-            for (int x = 0; x < DPL; ++x) {
-                kdv[u][x] = Elem<T>::load(s.kd, drow + lane + 64 * x);
-                vdv[u][x] = Elem<T>::load(s.vd, drow + lane + 64 * x);
-            }
-        }
+    // online softmax over four nodes (slots without a node have a[u] < 0 and weigh nothing)
+    auto four = [&](const int *a, float (*kdv)[DPL], float (*vdv)[DPL]) {
         float z[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -90,19 +111,37 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
             for (int x = 0; x < DPL; ++x) dot = fmaf(qv[x], kdv[u][x], dot);
             z[u] = a[u] >= 0 ? wave_sum(dot) * scale_log2 : -INFINITY;
         }
-        const float m_new = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), m);   // z[0] is always finite
-        const float alpha = exp2f(m - m_new);
+        const float m_new = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), m);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = exp2f(m - m_use);
         l *= alpha;
 #pragma unroll
         for (int x = 0; x < DPL; ++x) od[x] *= alpha;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float pe = exp2f(z[u] - m_new);   // 0 for the unused slots
+            const float pe = exp2f(z[u] - m_use);   // 0 for the unused slots
             l += pe;
 #pragma unroll
             for (int x = 0; x < DPL; ++x) od[x] = fmaf(pe, vdv[u][x], od[x]);
         }
         m = m_new;
+    };
+    four(a8, kd8, vd8);
+    if (a8[4] >= 0) four(a8 + 4, kd8 + 4, vd8 + 4);
+    while (anc_lo | anc_hi) {   // paths longer than 8 nodes
+        int a[4];
+        float kdv[4][DPL], vdv[4][DPL];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a[u] = pop();
+            const int64_t drow = (((int64_t)b * s.M + max(a[u], 0)) * s.Hkv + g) * D;
+#pragma unroll
+            for (int x = 0; x < DPL; ++x) {
+                kdv[u][x] = Elem<T>::load(s.kd, drow + lane + 64 * x);
+                vdv[u][x] = Elem<T>::load(s.vd, drow + lane + 64 * x);
+            }
+        }
+        four(a, kdv, vdv);
     }
 
     // ---- merge the two and store ---------------------------------------------------------
