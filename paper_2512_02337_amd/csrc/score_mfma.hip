@@ -1,13 +1,14 @@
 // Block scoring (Section 3.2, eq. 2 and eq. 3) on the matrix cores for bf16, head dim 128.
 //
 // Per KV head the scores are max(Q . Kmax^T, Q . Kmin^T) reduced over the M*G query rows:
-// two [rows x 128] x [128 x blocks] products.  One wavefront owns a tile of 32 blocks: it
-// keeps the two 32 x 128 summary tiles in registers as MFMA B operands (lane = block) and
-// walks over the query rows 32 at a time (MFMA A operand, lane = row), so each lane ends up
-// with 16 rows of ONE block; the element-wise max of the two accumulators and the reduction
-// over rows (mean / max / rows of one node) are lane-local, with a single exchange between
-// lane and lane ^ 32 at the end.  The sum order is the same for every block, so identical
-// blocks get bit-identical scores wherever they sit.
+// two [rows x 128] x [128 x blocks] products.  A workgroup owns a tile of 32 blocks and
+// spreads the query rows over its wavefronts, 32 rows at a time: a wavefront holds the two
+// 32 x 128 summary tiles as MFMA B operands (lane = block) and its query rows as A operand
+// (lane = row), so each lane ends up with 16 rows of ONE block; the element-wise max of the
+// two accumulators and the reduction over rows (mean / max / rows of one node) are
+// lane-local.  All reads of a wavefront are issued at once (one round trip); the
+// wavefronts' partial results meet in LDS.  The sum order is the same for every block, so
+// identical blocks get bit-identical scores wherever they sit.
 #include "internal.h"
 
 namespace specpv {
@@ -15,43 +16,68 @@ namespace specpv {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-__global__ __launch_bounds__(256) void score_mfma_kernel(Shape s, const uint16_t *__restrict__ kmax,
-                                                         const uint16_t *__restrict__ kmin, int reduce,
-                                                         int last_node, float *__restrict__ scores)
+constexpr int kScoreMaxWaves = 16;
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *glb_void_ptr;
+
+__global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s, const uint16_t *__restrict__ kmax,
+                                                                         const uint16_t *__restrict__ kmin, int reduce,
+                                                                         int last_node, float *__restrict__ scores)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the two summary tiles of this workgroup's 32 blocks: row-major, 256 B per block, the
+    // 16-byte pieces of row t stored at piece index p ^ (t & 7) so that the operand reads
+    // below (32 lanes, same piece, different rows) spread over all banks
+    __shared__ __attribute__((aligned(1024))) char tile[2][8192];
+    __shared__ float red[kScoreMaxWaves][64];
+    const int lane = threadIdx.x & 63, W = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, kg = lane >> 5;
     const int g = blockIdx.y, b = blockIdx.z;
-    const int L = s.ctx_len[b];
-    int nb = L > 0 ? (L + s.B - 1) / s.B : 0;
-    if (nb > s.max_blocks) nb = s.max_blocks;
-    const int tile = blockIdx.x * 4 + wave;
-    const int i0 = tile * 32;
-    if (i0 >= nb) return;
-    const int blk = min(i0 + n, nb - 1);   // lanes past the end repeat the last block; not stored
+    const int i0 = blockIdx.x * 32;
     const int R = s.M * s.G;
+    const int L = s.ctx_len[b];   // only needed at the very end: its latency overlaps with everything else
 
-    // summary tiles as B operands: lane = block, channels 16*ks + 8*kg .. +8
-    const int64_t srow = (((int64_t)b * s.Hkv + g) * s.max_blocks + blk) * 128 + kg * 8;
-    bf16x8 bx[8], bn[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        bx[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(kmax + srow + ks * 16));
-        bn[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(kmin + srow + ks * 16));
+    // Summary rows go from memory straight into LDS (16 DMA operations of 1 KiB shared by the
+    // wavefronts; operation d brings rows 4*(d&7) .. +3 of Kmax (d < 8) or Kmin, one 256-byte
+    // row per 16 lanes).  Rows past the end of the arrays repeat the last row; their scores
+    // are never stored.
+    {
+        const int r4 = lane >> 4, pos = lane & 15;
+        const int64_t arr_row0 = ((int64_t)b * s.Hkv + g) * s.max_blocks;
+        for (int d = wave; d < 16; d += W) {
+            const int i = d & 7, row = 4 * i + r4;
+            const int blk = min(i0 + row, s.max_blocks - 1);
+            const char *src = (const char *)(d < 8 ? kmax : kmin) + ((arr_row0 + blk) * 128) * 2 + 16 * (pos ^ (row & 7));
+            __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile[d >> 3] + i * 1024), 16, 0, 0);
+        }
     }
 
     float acc = reduce == SPECPV_REDUCE_MAX ? -INFINITY : 0.f;
     const uint16_t *q = (const uint16_t *)s.q;
-    // query rows r0 .. r0+31 as A operand: lane = row; the next tile's rows are requested
-    // while the current tile is multiplied
-    auto load_rows = [&](int r0, uint4 (&dst)[8]) {
+    const char *bxp = tile[0] + n * 256, *bnp = tile[1] + n * 256;
+    bool have_tiles = false;
+    bf16x8 bx[8], bn[8];
+    // query rows r0 .. r0+31 as A operand: lane = row
+    for (int r0 = wave * 32; r0 < R; r0 += W * 32) {
         const int r = min(r0 + n, R - 1);
         const int j = r / s.G, hh = r - j * s.G;
         const uint16_t *qrow = q + (((int64_t)b * s.M + j) * s.Hq + g * s.G + hh) * 128 + kg * 8;
+        uint4 qa[8];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) dst[ks] = *(const uint4 *)(qrow + ks * 16);
-    };
-    auto row_tile = [&](int r0, const uint4 (&qa)[8]) {
+        for (int ks = 0; ks < 8; ++ks) qa[ks] = *(const uint4 *)(qrow + ks * 16);
+        if (!have_tiles) {
+            // summary tiles as B operands: lane = block, channels 16*ks + 8*kg .. +8
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's DMA operations (and query rows) are in
+            __syncthreads();                      // ... and so are everybody else's
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const int off = (32 * ks + 16 * kg) ^ (16 * (n & 7));
+                bx[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(bxp + off));
+                bn[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(bnp + off));
+            }
+            have_tiles = true;
+        }
         f32x16 sx, sn;
 #pragma unroll
         for (int x = 0; x < 16; ++x) { sx[x] = 0.f; sn[x] = 0.f; }
@@ -74,22 +100,21 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(Shape s, const uint16_t
                 if (row < R && row / s.G == last_node) acc += sv;
             }
         }
-    };
-    uint4 qa[8], qb[8];
-    load_rows(0, qa);
-    for (int r0 = 0; r0 < R; r0 += 64) {
-        if (r0 + 32 < R) load_rows(r0 + 32, qb);
-        row_tile(r0, qa);
-        if (r0 + 32 < R) {
-            if (r0 + 64 < R) load_rows(r0 + 64, qa);
-            row_tile(r0 + 32, qb);
-        }
+    }
+    red[wave][lane] = acc;
+    __syncthreads();
+    if (wave != 0) return;
+    for (int w = 1; w < W; ++w) {
+        const float o = red[w][lane];
+        acc = reduce == SPECPV_REDUCE_MAX ? fmaxf(acc, o) : acc + o;
     }
     const float other = __shfl_xor(acc, 32);
     float out;
     if (reduce == SPECPV_REDUCE_MAX) out = fmaxf(acc, other);
     else if (reduce == SPECPV_REDUCE_MEAN) out = (acc + other) / (float)R;
     else out = (acc + other) / (float)s.G;
+    int nb = L > 0 ? (L + s.B - 1) / s.B : 0;
+    if (nb > s.max_blocks) nb = s.max_blocks;
     if (kg == 0 && i0 + n < nb) scores[((int64_t)b * s.Hkv + g) * s.max_blocks + i0 + n] = out;
 }
 
@@ -98,8 +123,8 @@ bool score_mfma_supported(const Shape &s, int dtype) { return dtype == SPECPV_BF
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
                               int last_node, float *scores, hipStream_t st)
 {
-    const int tiles = (s.max_blocks + 31) / 32;
-    dim3 grid((tiles + 3) / 4, s.Hkv, s.batch), block(256);
+    const int tiles = (s.max_blocks + 31) / 32, row_tiles = (s.M * s.G + 31) / 32;
+    dim3 grid(tiles, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
     hipLaunchKernelGGL(score_mfma_kernel, grid, block, 0, st, s, (const uint16_t *)kmax, (const uint16_t *)kmin,
                        reduce, last_node, scores);
     return hipGetLastError();

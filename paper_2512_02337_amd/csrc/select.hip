@@ -192,6 +192,144 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *scores, const in
     if (tid == 0) sel_count[(int64_t)b * Hkv + g] = base;
 }
 
+// Faster selection for lists of up to 256 * P blocks (P <= 16): thread t owns the P
+// consecutive blocks t*P .. t*P+P-1 and keeps their scores in registers, so that
+//   - the radix select reads memory once and only runs over the 32 score bits (4 passes of 8
+//     bits; the histogram's suffix sums are one wavefront's work, without workgroup barriers);
+//   - ties at the threshold score are broken towards the lower index by ranking the tied
+//     blocks in index order (one workgroup-wide prefix sum) instead of four more radix passes;
+//   - the ascending output comes from one more prefix sum over the per-thread keep counts.
+__device__ __forceinline__ uint32_t score_bits(float score)
+{
+    if (score == 0.f) score = 0.f;  // -0 and +0 compare equal: give them one key
+    const uint32_t u = __float_as_uint(score);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// exclusive prefix sum of v over the 256 threads (and the total), two barriers
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wave_tot, int &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(inc, o);
+        if (lane >= o) inc += up;
+    }
+    __syncthreads();   // wave_tot may still be read from a previous call
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int off = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) off += wave_tot[w];
+        total += wave_tot[w];
+    }
+    return off + inc - v;
+}
+
+template <int P>
+__global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, const int32_t *ctx_len, int B,
+                                                        int max_blocks, int Hkv, int ns, int nr, int k,
+                                                        int32_t *sel_idx, int32_t *sel_count)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh_digit, sh_above;
+    __shared__ int wave_tot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int n_sel = ns + k + nr;
+    const int L = ctx_len[b];
+    int nb = L > 0 ? (L + B - 1) / B : 0;
+    if (nb > max_blocks) nb = max_blocks;
+    const float *sc = scores + ((int64_t)b * Hkv + g) * max_blocks;
+    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_sel;
+    const bool all = nb <= n_sel;
+    const int lo = ns, hi = nb - nr;          // candidates of the top-k: blocks lo .. hi-1
+    const bool any_topk = !all && k > 0;      // then hi - lo > k
+
+    const int i0 = tid * P;
+    uint32_t key[P];
+    uint32_t cand = 0;                        // bit j: block i0 + j is a top-k candidate
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const int i = i0 + j;
+        const bool c = any_topk && i >= lo && i < hi;
+        key[j] = c ? score_bits(sc[i]) : 0u;
+        cand |= (c ? 1u : 0u) << j;
+    }
+
+    uint32_t prefix = 0;                      // threshold bits decided so far
+    int krem = k;                             // how many of the keys that match prefix still belong to the top k
+    if (any_topk) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            hist[tid] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < P; ++j)
+                if (((cand >> j) & 1u) && (pass == 0 || (key[j] >> (shift + 8)) == (prefix >> (shift + 8))))
+                    atomicAdd(&hist[(key[j] >> shift) & 255u], 1u);
+            __syncthreads();
+            if (wave == 0) {
+                // lane l owns digits 4l .. 4l+3; suf[x] = number of matching keys with digit >= 4l + x
+                const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+                uint32_t inc = h0 + h1 + h2 + h3;         // becomes the sum over lanes >= l
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t dn = __shfl_down(inc, o);
+                    if (lane + o < 64) inc += dn;
+                }
+                const uint32_t higher = inc - (h0 + h1 + h2 + h3);   // keys with digit >= 4l + 4
+                const uint32_t suf[5] = {higher + h3 + h2 + h1 + h0, higher + h3 + h2 + h1, higher + h3 + h2, higher + h3, higher};
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if (suf[x] >= (uint32_t)krem && suf[x + 1] < (uint32_t)krem) {   // true for exactly one digit
+                        sh_digit = (uint32_t)(4 * lane + x);
+                        sh_above = suf[x + 1];
+                    }
+            }
+            __syncthreads();
+            prefix |= sh_digit << shift;
+            krem -= (int)sh_above;
+        }
+    }
+    // prefix is the k-th largest score key; krem (>= 1) of the blocks that tie with it are kept,
+    // lowest indices first
+    uint32_t tie = 0;
+#pragma unroll
+    for (int j = 0; j < P; ++j)
+        if (((cand >> j) & 1u) && key[j] == prefix) tie |= 1u << j;
+    int tie_rank = 0, tie_total = 0;
+    if (any_topk) tie_rank = block_exclusive_scan(__popc(tie), wave_tot, tie_total);
+    uint32_t keep = 0;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const int i = i0 + j;
+        bool kp = false;
+        if (i < nb) {
+            kp = all || i < lo || i >= hi;
+            if (!kp && ((cand >> j) & 1u)) {
+                if (key[j] > prefix) kp = true;
+                else if ((tie >> j) & 1u) { kp = tie_rank < krem; ++tie_rank; }
+            }
+        }
+        keep |= (kp ? 1u : 0u) << j;
+    }
+    int total = 0;
+    int pos = block_exclusive_scan(__popc(keep), wave_tot, total);
+#pragma unroll
+    for (int j = 0; j < P; ++j)
+        if ((keep >> j) & 1u) {
+            if (pos < n_sel) out[pos] = i0 + j;
+            ++pos;
+        }
+    if (total > n_sel) total = n_sel;
+    for (int c = total + tid; c < n_sel; c += 256) out[c] = -1;
+    if (tid == 0) sel_count[(int64_t)b * Hkv + g] = total;
+}
+
 bool score_mfma_supported(const Shape &s, int dtype);
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
                               int last_node, float *scores, hipStream_t st);
@@ -208,8 +346,14 @@ hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int 
                        int32_t *sel_idx, int32_t *sel_count, hipStream_t st)
 {
     dim3 grid(s.Hkv, s.batch), block(256);
-    hipLaunchKernelGGL(topk_kernel, grid, block, 0, st, scores, s.ctx_len, s.B, s.max_blocks, s.Hkv,
-                       ns, nr, k, sel_idx, sel_count);
+#define SPECPV_TOPK(KERN)                                                                        \
+    hipLaunchKernelGGL(KERN, grid, block, 0, st, scores, s.ctx_len, s.B, s.max_blocks, s.Hkv, ns, nr, k, \
+                       sel_idx, sel_count)
+    if (s.max_blocks <= 256 * 4) SPECPV_TOPK(topk_fast_kernel<4>);
+    else if (s.max_blocks <= 256 * 8) SPECPV_TOPK(topk_fast_kernel<8>);
+    else if (s.max_blocks <= 256 * 16) SPECPV_TOPK(topk_fast_kernel<16>);
+    else SPECPV_TOPK(topk_kernel);
+#undef SPECPV_TOPK
     return hipGetLastError();
 }
 

@@ -156,6 +156,31 @@ def test_selection_ties_and_extremes(gpu_lib):
             check_selection(got_idx, got_cnt, idx, cnt, sc, ns, nr, kb, "extremes")
 
 
+def test_selection_over_long_lists(gpu_lib):
+    """More than 4096 blocks per head takes the general radix-select kernel (the lists up to
+    4096 blocks that the other tests use take the register-resident one): same rule, same
+    answer, including an exact tie at the threshold."""
+    cfg = dict(SMALL); cfg.update(ctx=[4 * 4300], B=4, M=8, rho=[0.0], name="long_list")
+    case = workloads.to_device(workloads.make_case(cfg, seed=5), "cuda")
+    B = case["B"]
+    k = case["k"]
+    src = k[0, :, 7 * B:8 * B].clone() + 1.0
+    for i in (7, 1000, 2500, 4200):
+        k[0, :, i * B:(i + 1) * B] = src
+    for (ns, nr, kb) in [(1, 2, 3), (4, 4, 300), (0, 0, 1)]:
+        run = GpuRun(gpu_lib, case, cfg=(ns, nr, kb))
+        run.summarize(); run.select()
+        torch.cuda.synchronize()
+        o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0, cfg=(ns, nr, kb))
+        got_idx, got_cnt = run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0]
+        say("   4300 blocks, ns,nr,k =", (ns, nr, kb), "kept", got_idx[0, :got_cnt[0]].tolist()[:8])
+        assert np.array_equal(got_cnt, cnt)
+        if kb in (3, 1):   # the tie group decides: must match the oracle exactly
+            assert np.array_equal(got_idx, idx), (got_idx, idx)
+        else:
+            check_selection(got_idx, got_cnt, idx, cnt, sc, ns, nr, kb, "long list")
+
+
 def test_attention_list_semantics(gpu_lib):
     """Order of the list is irrelevant, entries past sel_count / negative / out of
     range are ignored, an empty list leaves only the draft segment."""
