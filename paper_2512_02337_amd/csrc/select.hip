@@ -236,41 +236,66 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh_digit, sh_above;
+    __shared__ uint32_t wave_min[4], wave_max_[4];
     __shared__ int wave_tot[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x, b = blockIdx.y;
     const int n_sel = ns + k + nr;
+    const float *sc = scores + ((int64_t)b * Hkv + g) * max_blocks;
+    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_sel;
+
+    const int i0 = tid * P;
+    // the scores are requested before the context length is known (any block below max_blocks
+    // is readable), so the two cold reads overlap
+    float raw[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) raw[j] = sc[min(i0 + j, max_blocks - 1)];
     const int L = ctx_len[b];
     int nb = L > 0 ? (L + B - 1) / B : 0;
     if (nb > max_blocks) nb = max_blocks;
-    const float *sc = scores + ((int64_t)b * Hkv + g) * max_blocks;
-    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_sel;
     const bool all = nb <= n_sel;
     const int lo = ns, hi = nb - nr;          // candidates of the top-k: blocks lo .. hi-1
     const bool any_topk = !all && k > 0;      // then hi - lo > k
-
-    const int i0 = tid * P;
     uint32_t key[P];
     uint32_t cand = 0;                        // bit j: block i0 + j is a top-k candidate
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         const int i = i0 + j;
         const bool c = any_topk && i >= lo && i < hi;
-        key[j] = c ? score_bits(sc[i]) : 0u;
+        key[j] = c ? score_bits(raw[j]) : 0u;
         cand |= (c ? 1u : 0u) << j;
+        if (c) { kmin = min(kmin, key[j]); kmax = max(kmax, key[j]); }
     }
 
     uint32_t prefix = 0;                      // threshold bits decided so far
     int krem = k;                             // how many of the keys that match prefix still belong to the top k
     if (any_topk) {
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
+        // Smallest and largest key of the workgroup: the bits above the highest bit in which
+        // they differ are common to all keys and need no pass.  Starting the digits right
+        // there also spreads the first histogram over its bins (the leading bits of scores
+        // of similar magnitude are all alike, and LDS atomics on one address serialise).
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+        }
+        if (lane == 0) { wave_min[wave] = kmin; wave_max_[wave] = kmax; }
+        __syncthreads();
+        kmin = min(min(wave_min[0], wave_min[1]), min(wave_min[2], wave_min[3]));
+        kmax = max(max(wave_max_[0], wave_max_[1]), max(wave_max_[2], wave_max_[3]));
+        const uint32_t diff = kmin ^ kmax;
+        int top = diff ? 32 - __builtin_clz(diff) : 0;   // number of low bits that are not common to all keys
+        prefix = top < 32 ? (kmax >> top) << top : 0u;
+        while (top > 0) {
+            const int width = top < 8 ? top : 8, shift = top - width;
+            const uint32_t mask = (1u << width) - 1u;
             hist[tid] = 0;
             __syncthreads();
 #pragma unroll
             for (int j = 0; j < P; ++j)
-                if (((cand >> j) & 1u) && (pass == 0 || (key[j] >> (shift + 8)) == (prefix >> (shift + 8))))
-                    atomicAdd(&hist[(key[j] >> shift) & 255u], 1u);
+                if (((cand >> j) & 1u) && (top >= 32 || (key[j] >> top) == (prefix >> top)))
+                    atomicAdd(&hist[(key[j] >> shift) & mask], 1u);
             __syncthreads();
             if (wave == 0) {
                 // lane l owns digits 4l .. 4l+3; suf[x] = number of matching keys with digit >= 4l + x
@@ -293,6 +318,7 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
             __syncthreads();
             prefix |= sh_digit << shift;
             krem -= (int)sh_above;
+            top = shift;
         }
     }
     // prefix is the k-th largest score key; krem (>= 1) of the blocks that tie with it are kept,
