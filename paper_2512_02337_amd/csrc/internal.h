@@ -40,6 +40,9 @@ template <> struct Elem<float> {
         f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
         f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
     }
+    static __device__ __forceinline__ uint4 pack(const float *f) {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
     static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
     static __device__ __forceinline__ void store(void *p, int64_t i, float x) { ((float *)p)[i] = x; }
 };
@@ -58,6 +61,12 @@ template <> struct Elem<bf16_t> {
         f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
         f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
         f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ uint4 pack(const float *f) {   // values that are exactly representable
+        return make_uint4(float_to_bf16_bits(f[0]) | ((uint32_t)float_to_bf16_bits(f[1]) << 16),
+                          float_to_bf16_bits(f[2]) | ((uint32_t)float_to_bf16_bits(f[3]) << 16),
+                          float_to_bf16_bits(f[4]) | ((uint32_t)float_to_bf16_bits(f[5]) << 16),
+                          float_to_bf16_bits(f[6]) | ((uint32_t)float_to_bf16_bits(f[7]) << 16));
     }
     static __device__ __forceinline__ float load(const void *p, int64_t i) {
         return bf16_bits_to_float(((const uint16_t *)p)[i]);

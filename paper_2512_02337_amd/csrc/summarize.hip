@@ -2,8 +2,19 @@
 // of each block.  Pure HBM streaming: one wavefront per (block, KV head), 16-byte
 // loads, the lanes that share a channel group are folded with cross-lane shuffles.
 #include "internal.h"
+#ifndef SPECPV_SUM_UNR
+#define SPECPV_SUM_UNR 16
+#endif
 
 namespace specpv {
+
+// 16-byte read of data that is used once: keep it from displacing what the caches hold
+__device__ __forceinline__ uint4 load_stream(const uint4 *p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void summarize_kernel(Shape s, int blk_begin, int blk_end,
@@ -29,7 +40,23 @@ __global__ __launch_bounds__(256) void summarize_kernel(Shape s, int blk_begin, 
     float mx[E], mn[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; }
-    for (int t = t0 + rsub; t < t1; t += RPP) {
+    // UNR independent 16-byte loads per lane in flight: the kernel is bound by the bytes it
+    // keeps in flight against the memory latency
+    constexpr int UNR = SPECPV_SUM_UNR;
+    int t = t0 + rsub;
+    for (; t + (UNR - 1) * RPP < t1; t += UNR * RPP) {
+        uint4 u[UNR];
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) u[x] = load_stream((const uint4 *)(base + (int64_t)(t + x * RPP) * s.st));
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            float f[E];
+            Elem<T>::unpack(u[x], f);
+#pragma unroll
+            for (int e = 0; e < E; ++e) { mx[e] = fmaxf(mx[e], f[e]); mn[e] = fminf(mn[e], f[e]); }
+        }
+    }
+    for (; t < t1; t += RPP) {
         const uint4 u = *(const uint4 *)(base + (int64_t)t * s.st);
         float f[E];
         Elem<T>::unpack(u, f);
@@ -46,11 +73,9 @@ __global__ __launch_bounds__(256) void summarize_kernel(Shape s, int blk_begin, 
     }
     if (rsub == 0) {
         const int64_t o = (((int64_t)b * s.Hkv + g) * s.max_blocks + i) * D + c * E;
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            Elem<T>::store(kmax, o + e, mx[e]);
-            Elem<T>::store(kmin, o + e, mn[e]);
-        }
+        // one 16-byte store per array (o is a multiple of E elements)
+        *(uint4 *)((T *)kmax + o) = Elem<T>::pack(mx);
+        *(uint4 *)((T *)kmin + o) = Elem<T>::pack(mn);
     }
 }
 
