@@ -44,6 +44,10 @@ constexpr int kOPitch = 132;         // floats per staged output row (128 + 4: c
 constexpr int kStageBytes = 16384;   // one 32-token chunk: 8 KiB of K + 8 KiB of V
 constexpr int kStages = 2;           // ring depth per wavefront
 constexpr int kRingBytes = 4 * kStages * kStageBytes;
+// The wide kernel stores the V rows of a chunk in 8 pieces of 4 rows (tokens i, i+8, i+16,
+// i+24 in piece i), 1088 bytes apart, for its transposing LDS reads (see there).
+constexpr int kVPiecePitch = 1088;
+constexpr int kWideStageBytes = 8192 + 8 * kVPiecePitch;
 constexpr float kRescaleSlack = 8.f; // the reference max may lag the true max by 2^8
 
 // Exact n / d for 0 <= n < 2^31 with a host-prepared multiplier (no integer divide
@@ -579,7 +583,7 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
     extern __shared__ char lds_raw[];
     float *ms = (float *)lds_raw;            // [4 token groups][64 rows]
     float *ls = ms + 4 * 64;                 // [4][64]
-    char *ring = lds_raw + 2048;             // [4 wavefronts][kStages][K 8 KiB | V 8 KiB]
+    char *ring = lds_raw + 2048;             // [4 wavefronts][kStages][K 8 KiB | V 8 pieces of 1088 B]
     float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
 
     const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
@@ -636,7 +640,7 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
     const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
     const uint32_t st2 = (uint32_t)s.st * 2u;
 
-    char *my_ring = ring + tg * (kStages * kStageBytes);
+    char *my_ring = ring + tg * (kStages * kWideStageBytes);
     int slot_base = 0, blkvec = 0;
     auto refill = [&](int slot) {
         slot_base = slot;
@@ -664,8 +668,9 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
 
     uint32_t vmask_st[kStages];
 
-    // Request chunk ci: 16 DMA operations, 8 for the K rows (pieces swizzled by row & 7) and
-    // 8 for the V rows; operation i of each brings rows 4i .. 4i+3, one 256-byte row per 16 lanes.
+    // Request chunk ci: 16 DMA operations of 1 KiB (one 256-byte row per 16 lanes).  K: operation
+    // i brings rows 4i .. 4i+3, pieces swizzled by row & 7.  V: operation i brings rows i, i+8,
+    // i+16, i+24 into piece i.
     auto issue = [&](int ci) {
         const int stg = ci & (kStages - 1);
         int tok;
@@ -680,35 +685,43 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
         vmask_st[stg] = vm;
         const int r4 = lane >> 4, pos = lane & 15;
         const uint32_t ksw_even = 16u * (uint32_t)(pos ^ r4), ksw_odd = ksw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-        char *dst = my_ring + stg * kStageBytes;
+        char *dst = my_ring + stg * kWideStageBytes;
+        char *dstv = dst + 8192;
         if (ALIGNED && vm == 0xffffffffu) {
             const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
             const size_t row0 = (size_t)t0 * st2;
             const uint32_t lane_row_off = (uint32_t)r4 * st2;
             if (st2 == 256u) {
-                // rows are 256 bytes apart (the usual head-major cache): four consecutive
-                // operations differ by 1 KiB on both sides, which the instruction's immediate
-                // offset covers, so they share one base address and one LDS base
+                // rows are 256 bytes apart (the usual head-major cache): the instruction's
+                // immediate offset, added to the global and to the LDS address, covers the step
+                // between consecutive operations (K: 1 KiB on both sides; V: 256 bytes, with the
+                // LDS base adjusted for the rest of the piece pitch)
                 dma16x4(kb + row0, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst);
                 dma16x4(kb + row0 + 4096, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst + 4096);
-                dma16x4(vb + row0, lane_row_off + vsw, lane_row_off + vsw, dst + 8192);
-                dma16x4(vb + row0 + 4096, lane_row_off + vsw, lane_row_off + vsw, dst + 8192 + 4096);
+                const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
+#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, 0)
+                SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
+                SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
+#undef SPECPV_VOP
             } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    dma16(vb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + vsw), dst + 8192 + i * 1024);
+                    dma16(vb + row0 + (size_t)(8 * r4 + i) * st2 + vsw, dstv + i * kVPiecePitch);
             }
         } else {
-            uint32_t tv[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) tv[i] = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
+                dma16(kb + (tv + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
+            }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dma16(kb + (tv[i] + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dma16(vb + (tv[i] + vsw), dst + 8192 + i * 1024);
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * st2;
+                dma16(vb + (tv + vsw), dstv + i * kVPiecePitch);
+            }
         }
     };
 
@@ -731,36 +744,54 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[rb][j][i] = 0.f;
 
-    // K / V fragments of one chunk, as the MFMAs want them (see attn_ctx_mfma_kernel)
+    // K / V fragments of one chunk, as the MFMAs want them.  V (the A operand of O^T += V^T . P^T)
+    // needs, per lane, 8 tokens of ONE channel, while memory and LDS hold 128 channels of one
+    // token contiguously: the transposing LDS read (ds_read_b64_tr_b16) does that exchange
+    // inside groups of 16 lanes.  Lane s of a group reads 8 bytes (4 channels) and receives,
+    // as lane 4a + c of the group, element c of what lanes a, a+4, a+8, a+12 read.  With lane
+    // s reading token (s >> 2) of a token quad and channels 4 * (s & 3) .. +3 of a 16-channel
+    // group, every lane ends up with the four tokens of the quad for channel (lane & 15) of
+    // the group: lane m = lane & 31 holds channel 32j + m of tile j, its k-group the tokens
+    // 16*ks2 + 8*hf + 4*kg + 0..3.  The four token rows of a quad sit in four different V
+    // pieces, 1088 bytes apart, i.e. 64 bytes apart modulo the bank cycle: no bank conflicts.
     struct Frags { uint4 k[8]; uint2 v[16]; uint32_t vmask; };
     const char *kptr = my_ring + n * 256;
     uint32_t koff[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) koff[ks] = ((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u));
-    const char *vptr = my_ring + 8192 + kg * 1024 + n * 8;
+    const char *vptr;
+    {
+        const int s16 = lane & 15, grp = lane >> 4;
+        vptr = my_ring + 8192 + (4 * kg + (s16 >> 2)) * kVPiecePitch + 32 * (grp & 1) + 8 * (s16 & 3);
+    }
     // Plain LDS loads: the compiler tracks when they arrive, so they can stay in flight
     // behind the arithmetic of the previous chunk.
     auto read_frags = [&](int ci, Frags &f) {
         const int stg = ci & 1;
         f.vmask = vmask_st[stg];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) f.k[ks] = *(const uint4 *)(kptr + stg * kStageBytes + koff[ks]);
+        for (int ks = 0; ks < 8; ++ks) f.k[ks] = *(const uint4 *)(kptr + stg * kWideStageBytes + koff[ks]);
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            f.v[e] = *(const uint2 *)(vptr + stg * kStageBytes + (e >> 2) * 2048 + (e & 3) * 256);
+        for (int e = 0; e < 16; ++e) {
+            // e = (ks2 * 4 + j) * 2 + hf: token quad 16*ks2 + 8*hf (+ 4*kg) is rows 2*ks2 + hf of the pieces
+            const int hf = e & 1, j = (e >> 1) & 3, ks2 = e >> 3;
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            const v4s t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4s *)(vptr + stg * kWideStageBytes + (2 * ks2 + hf) * 256 + 64 * j));
+            f.v[e] = __builtin_bit_cast(uint2, t);
+        }
     };
     // The arithmetic of one chunk for both 32-row blocks.
     auto compute = [&](const Frags &f) {
-        // V: 8 tokens x 4 channels  ->  4 channels x 8 tokens, once for both row blocks
+        // V^T operands: channels 32j + (lane & 31), tokens as above
         uint4 vt[2][4];
 #pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-            const uint2 *w = f.v + 8 * ks2;
-            vt[ks2][0] = make_uint4(pack_lo(w[0].x, w[1].x), pack_lo(w[2].x, w[3].x), pack_lo(w[4].x, w[5].x), pack_lo(w[6].x, w[7].x));
-            vt[ks2][1] = make_uint4(pack_hi(w[0].x, w[1].x), pack_hi(w[2].x, w[3].x), pack_hi(w[4].x, w[5].x), pack_hi(w[6].x, w[7].x));
-            vt[ks2][2] = make_uint4(pack_lo(w[0].y, w[1].y), pack_lo(w[2].y, w[3].y), pack_lo(w[4].y, w[5].y), pack_lo(w[6].y, w[7].y));
-            vt[ks2][3] = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y), pack_hi(w[4].y, w[5].y), pack_hi(w[6].y, w[7].y));
-        }
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint2 lo = f.v[(ks2 * 4 + j) * 2], hi = f.v[(ks2 * 4 + j) * 2 + 1];
+                vt[ks2][j] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
         const uint32_t vmask = f.vmask;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
@@ -863,12 +894,14 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
             ms[tg * 64 + row] = m_ref[rb];
             ls[tg * 64 + row] = lr;
         }
+        // accumulator element 4q + x of tile j is channel 32j + 8q + 4kg + x of this lane's row
         float *dst = obuf + ((size_t)tg * 64 + row) * kOPitch;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int mi = (i >> 2) * 8 + kg * 4 + (i & 3);
-            *(float4 *)(dst + 4 * mi) = make_float4(O[rb][0][i], O[rb][1][i], O[rb][2][i], O[rb][3][i]);
-        }
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) =
+                    make_float4(O[rb][j][4 * q], O[rb][j][4 * q + 1], O[rb][j][4 * q + 2], O[rb][j][4 * q + 3]);
     }
     __syncthreads();
     constexpr int RPW = 16;  // rows each wavefront finishes
