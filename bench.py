@@ -169,7 +169,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(layers[0], n_layers)
+        cpu = cpu_baseline(layers)
 
     line = {
         "metric": "partial_verify_attention_us_per_step",
@@ -200,32 +200,35 @@ def main():
     print(json.dumps(line))
 
 
-def cpu_baseline(layer, n_layers):
-    """The fp64 oracle, as it stands, on the host's cores: one layer of the same
-    workload (layer 0), attention-only partial step; scaled to the whole step."""
+def cpu_baseline(layers):
+    """The fp64 oracle, as it stands, on the host's cores: the attention-only partial step over
+    every layer of the same workload (one whole step, about ten seconds of CPU work)."""
     import numpy as np
     import torch
     import oracle
-    case = layer["case"]
-    B, Hkv = case["B"], case["Hkv"]
-    idx = layer["sel_idx"][0].cpu().numpy()
-    cnt = layer["sel_count"][0].cpu().numpy()
-    n = int(cnt.max())
-    # hand the oracle only the kept blocks (per KV head, renumbered 0..n-1): attention
-    # does not depend on where a block sits, so this is the same computation
-    blocks = torch.from_numpy(idx[:, :n].astype(np.int64)).to(case["k"].device)          # [Hkv, n]
-    tok = (blocks[:, :, None] * B + torch.arange(B, device=blocks.device)[None, None]).reshape(Hkv, n * B)
-    K = torch.gather(case["k"][0], 1, tok[:, :, None].expand(-1, -1, case["D"])).permute(1, 0, 2).contiguous().cpu()
-    V = torch.gather(case["v"][0], 1, tok[:, :, None].expand(-1, -1, case["D"])).permute(1, 0, 2).contiguous().cpu()
-    Q, Kd, Vd = case["q"][0].cpu(), case["kd"][0].cpu(), case["vd"][0].cpu()
-    parent = case["parent"][0].cpu().numpy()
-    t0 = time.time()
-    O, _, _ = oracle.tree_attention(Q, K, V, Kd, Vd, parent, B)
-    dt = time.time() - t0
-    err = float(np.abs(layer["out"][0].float().cpu().numpy() - O).max())
-    return {"value": round(dt * 1e6 * n_layers, 1), "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "layer 0 of %d (partial-verify attention, fp64, %.3f s), scaled x%d" % (n_layers, dt, n_layers),
-            "gpu_vs_oracle_max_abs_err_layer0": round(err, 6)}
+    total, err0 = 0.0, None
+    for li, layer in enumerate(layers):
+        case = layer["case"]
+        B, Hkv = case["B"], case["Hkv"]
+        idx = layer["sel_idx"][0].cpu().numpy()
+        cnt = layer["sel_count"][0].cpu().numpy()
+        n = int(cnt.max())
+        # hand the oracle only the kept blocks (per KV head, renumbered 0..n-1): attention
+        # does not depend on where a block sits, so this is the same computation
+        blocks = torch.from_numpy(idx[:, :n].astype(np.int64)).to(case["k"].device)          # [Hkv, n]
+        tok = (blocks[:, :, None] * B + torch.arange(B, device=blocks.device)[None, None]).reshape(Hkv, n * B)
+        K = torch.gather(case["k"][0], 1, tok[:, :, None].expand(-1, -1, case["D"])).permute(1, 0, 2).contiguous().cpu()
+        V = torch.gather(case["v"][0], 1, tok[:, :, None].expand(-1, -1, case["D"])).permute(1, 0, 2).contiguous().cpu()
+        Q, Kd, Vd = case["q"][0].cpu(), case["kd"][0].cpu(), case["vd"][0].cpu()
+        parent = case["parent"][0].cpu().numpy()
+        t0 = time.time()
+        O, _, _ = oracle.tree_attention(Q, K, V, Kd, Vd, parent, B)
+        total += time.time() - t0
+        if li == 0:
+            err0 = float(np.abs(layer["out"][0].float().cpu().numpy() - O).max())
+    return {"value": round(total * 1e6, 1), "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "one whole step: partial-verify attention of all %d layers, fp64, %.2f s" % (len(layers), total),
+            "gpu_vs_oracle_max_abs_err_layer0": round(err0, 6)}
 
 
 if __name__ == "__main__":

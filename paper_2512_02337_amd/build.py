@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecpv.so")
 SOURCES = ["api.hip", "summarize.hip", "select.hip", "score_mfma.hip", "attn_generic.hip",
            "attn_mfma.hip", "combine.hip"]
-FLAGS = (["-DSPECPV_TIMING"] if os.environ.get("SPECPV_TIMING") else []) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

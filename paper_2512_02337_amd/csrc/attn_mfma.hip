@@ -28,6 +28,11 @@
 //
 // Epilogue: the four token groups merge their (O, m, l) through LDS and write one
 // split-KV partial per (head, split, node); combine.hip finishes.
+//
+// Two kernels share this decomposition.  attn_ctx_mfma_kernel (above description) is
+// used when a wavefront has only a few chunks to go through (the partial verification
+// over a 4K-token cache); attn_ctx_mfma_wide_kernel, further down, when it has many
+// (full verification of a long context).
 #include "internal.h"
 
 namespace specpv {
@@ -112,16 +117,6 @@ __device__ __forceinline__ void dma16x4(const char *gbase, uint32_t off_even, ui
     __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 3072, 0);
 }
 
-// Wait until at most 8*groups vector-memory operations of this wavefront are outstanding
-// (every DMA group below is 8 operations).
-__device__ __forceinline__ void wait_younger_groups(int groups)
-{
-    if (groups <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (groups == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else if (groups == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-}
-
 // The LDS reads of staged K / V are written in assembly so that the compiler does not
 // put a full vector-memory wait in front of them (it cannot tell which in-flight
 // LDS-DMA a read depends on); the waits are placed by hand instead.
@@ -182,13 +177,6 @@ __device__ __forceinline__ float sum_xor32(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-#ifdef SPECPV_TIMING
-__device__ unsigned long long g_dbg[512 * 8];
-#define STAMP(k) do { if (threadIdx.x == 0) g_dbg[(blockIdx.x + gridDim.x * blockIdx.y) * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-extern "C" void specpv_debug_read(unsigned long long *host) { hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg), sizeof(g_dbg)); }
-#else
-#define STAMP(k)
-#endif
 
 // grid: x = r * 8 + xcd   (r = query head within the group + G * row tile),  y = unit / 8
 // with unit = ((b * Hkv + g) * nsplit + split).  Workgroups are handed to the 8 XCDs
@@ -211,7 +199,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     char *ring = lds_raw + 2048;             // [4 pairs][kStages][K 8 KiB | V 8 KiB]
     float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
 
-    STAMP(0);
     // ---- which piece of work is this workgroup -------------------------------------
     const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
     const int u = blockIdx.y * 8 + xcd;
@@ -380,7 +367,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     // i.e. for the prefetch just issued, at the first use of Q in every iteration)
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt untouched
     asm volatile("" ::: "memory");
-    STAMP(1);
 
     f32x16 O[4];
     float m_ref = -INFINITY, l_run = 0.f;
@@ -407,7 +393,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
             lds_read_v(vread + stg * kStageBytes, v);
         }
         __builtin_amdgcn_s_barrier();          // both wavefronts of the pair hold chunk i in registers
-        if (i < 4) STAMP(2 + i);
         if (i + 2 < nch) issue(i + 2);
         if (!active) continue;
 
@@ -468,7 +453,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
                 O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[j]), as_bf16x8(ks2 ? pf1 : pf0), O[j], 0, 0, 0);
         }
     }
-    STAMP(6);
     __syncthreads();   // every wavefront is done with the rings: the epilogue reuses that LDS
 
     // ---- merge the four token groups ---------------------------------------------------
@@ -527,7 +511,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         const int j = m0 + wave * RPW + lane;
         if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
     }
-    STAMP(7);
 }
 
 // acc *= alpha for a 32x32 accumulator tile that lives in accumulation registers, without
