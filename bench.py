@@ -165,6 +165,21 @@ def main():
         c0 = layers[0]["case"]
         full_bytes = sum(int(x) for x in c0["ctx_len"]) * c0["Hkv"] * c0["D"] * 2 * 2
         extras["full_verify_refresh_kv_GBs"] = round(full_bytes * n_layers / (rf * 1e-6) / 1e9, 1)
+        # buffer commit after a partial step (Section 3.2: accepted candidates stay pending, the rest
+        # is dropped): 4 accepted tokens per layer into a 28-token buffer
+        c0 = layers[0]["case"]
+        P, Mt = 28, c0["M"]
+        cb = {"k": torch.zeros((c0["batch"], P + Mt, c0["Hkv"], c0["D"]), dtype=c0["q"].dtype, device=dev),
+              "n_pending": torch.zeros((c0["batch"],), dtype=torch.int32, device=dev),
+              "accepted": torch.tensor([[0, 1, 2, 3]] * c0["batch"], dtype=torch.int32, device=dev),
+              "n_accepted": torch.full((c0["batch"],), 4, dtype=torch.int32, device=dev)}
+        cb["v"] = torch.zeros_like(cb["k"])
+
+        def commit_step():
+            for l in layers:
+                specpv.specpv_commit_accepted(l["kv"], cb["k"], cb["v"], P, Mt, cb["n_pending"], cb["accepted"],
+                                              cb["n_accepted"], specpv.MODE_PARTIAL, None, None, ws)
+        extras["commit_partial_us_per_step"] = round(timed(commit_step, k2, 3, use_graph) * 1e3, 2)
         extras["setup_s"] = round(setup_s, 1)
 
     cpu = None

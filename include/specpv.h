@@ -148,6 +148,58 @@ int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree,
                                int32_t *sel_idx, int32_t *sel_count, float *scores,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- verification modes and the buffer (Section 3.3, Algorithm 1: SelectMode and the
+ * KV side of PostEvaluate) ------------------------------------------------------------
+ *
+ * State of one sequence between verify steps: L committed tokens in the cache (all
+ * fully verified) and n_pending partially verified tokens whose K/V wait in the
+ * buffer for the next full verification.  The buffer is the K/V storage of the
+ * (extended) draft tree: [batch, pending_cap + M_tree, Hkv, D], rows
+ * pending_cap - n_pending .. pending_cap - 1 hold the pending tokens (oldest first),
+ * rows pending_cap .. pending_cap + M_tree - 1 this step's candidates.  A verify step
+ * then passes the rows from pending_cap - n_pending on as kd / vd of a tree with
+ * n_pending + M_tree nodes whose parent array is a chain over the pending tokens with the
+ * candidates' tree hanging off its end (specpv_extend_parents); in a refresh step the
+ * pending tokens are queries as well and their K/V rows have been recomputed by the caller. */
+typedef enum { SPECPV_MODE_FULL = 0, SPECPV_MODE_PARTIAL = 1, SPECPV_MODE_REFRESH = 2 } specpv_mode;
+
+typedef struct specpv_policy {
+    int32_t partial_budget_tokens; /* size of the partial cache without the buffer: (ns + k + nr) * B */
+    int32_t pending_margin_tokens; /* the buffer holds one step's candidates plus this many pending
+                                      tokens (Section 4.2 and Appendix D: 20)                        */
+} specpv_policy;
+
+/* Section 3.3, last paragraph but one; SelectMode of Algorithm 1.  Host only, no GPU work.
+ *   seq_len <= partial_budget_tokens           -> FULL    (partial verification disabled)
+ *   partial cache not initialised yet           -> FULL    (the caller refreshes the selection with it)
+ *   n_pending > pending_margin_tokens           -> REFRESH (pending + candidates exceed the buffer)
+ *   otherwise                                   -> PARTIAL
+ * seq_len counts committed and pending tokens.  Returns the mode, or SPECPV_EINVAL. */
+int specpv_select_mode(const specpv_policy *policy, int64_t seq_len, int32_t partial_ready, int32_t n_pending);
+
+/* Parent array (host memory, n_pending + M_tree entries) of the extended tree described
+ * above: out[i] = i - 1 for the pending chain, the candidates' roots get n_pending - 1. */
+int specpv_extend_parents(const int32_t *tree_parent, int32_t M_tree, int32_t n_pending, int32_t *out);
+
+/* Section 3.2 (the buffer: "invalid tokens can be removed once verification is completed")
+ * and Section 3.3 ("we remove the invalid tokens from both the partial and the full KV
+ * cache").  accepted [batch, max_accept] int32 (device): the candidates on the accepted
+ * path as indices 0 .. M_tree-1 in increasing order; n_accepted [batch] (device).
+ *   mode PARTIAL: the accepted candidates' K/V rows join the pending tokens (the buffer is
+ *     compacted: everything else of this step's candidates is dropped);
+ *     n_pending_b += n_accepted_b (clamped to pending_cap).
+ *   mode FULL / REFRESH: the pending tokens' rows, then the accepted candidates' rows, are
+ *     appended to the cache at tokens L_b, L_b + 1, ...; L_b grows by their number (clamped to
+ *     max_blocks * B), n_pending_b = 0, and the summaries (eq. 1) of every block that
+ *     received a token are recomputed (kmax == NULL: skipped).
+ * Writes through kv->k, kv->v (rows from L_b on; the allocation must cover max_blocks * B
+ * tokens) and kv->ctx_len, n_pending [batch] (device), in stream order.  Workspace: 4 bytes
+ * per sequence (specpv_workspace_bytes covers it). */
+int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_t pending_cap, int32_t M_tree,
+                           int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
+                           int32_t max_accept, specpv_mode mode, void *kmax, void *kmin,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 const char *specpv_strerror(int status);
 /* Text of the HIP error behind the calling thread's last SPECPV_EHIP. */
 const char *specpv_last_hip_error(void);

@@ -153,3 +153,52 @@ def full_verify_refresh(Q, K, V, Kd, Vd, parent, B, ns, nr, k, reduce="mean", la
     scores = block_scores(Q, kmax, kmin, reduce, last_node)
     sel_idx, sel_count = select_blocks(scores, ns, nr, k)
     return O, lse, sel_idx, sel_count, scores
+
+
+# ---- verification modes and the buffer (Section 3.3; Algorithm 1: SelectMode, PostEvaluate) ----
+# Plain Python on one sequence's state; nothing here is shared with the HIP path.
+MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
+
+
+def select_mode(seq_len, partial_ready, n_pending, partial_budget_tokens, pending_margin_tokens):
+    """Section 3.3: no partial verification while the sequence fits the partial budget; one
+    full verification initialises the partial cache once it no longer does; after that
+    partial verification, until the partially verified tokens together with one step's
+    candidates exceed the buffer (candidates + margin), which triggers a refresh."""
+    if seq_len <= partial_budget_tokens:
+        return MODE_FULL
+    if not partial_ready:
+        return MODE_FULL
+    if n_pending > pending_margin_tokens:
+        return MODE_REFRESH
+    return MODE_PARTIAL
+
+
+def extend_parents(tree_parent, n_pending):
+    """Section 3.3: on a refresh the partially verified tokens are prepended to the candidates;
+    as a tree they are a chain, and every root of the candidates' tree hangs off its end."""
+    out = [i - 1 for i in range(n_pending)]
+    for p in tree_parent:
+        out.append(n_pending - 1 if p < 0 else int(p) + n_pending)
+    return out
+
+
+def commit_accepted(K, V, L, pend_k, pend_v, cand_k, cand_v, accepted, mode, capacity):
+    """Sections 3.2 / 3.3, KV side of PostEvaluate for one sequence.
+    K, V [capacity, Hkv, D] cache with L committed tokens; pend_k / pend_v: lists of the
+    pending tokens' rows [Hkv, D] (oldest first); cand_k / cand_v [M, Hkv, D] this step's
+    candidates; accepted: the candidates on the accepted path.  Returns (L, pend_k, pend_v):
+    partial verification keeps the accepted candidates as pending tokens; full verification
+    and refresh append the pending tokens and then the accepted candidates to the cache.
+    Everything else of this step's candidates is dropped."""
+    rows_k = list(pend_k) + [cand_k[a] for a in accepted]
+    rows_v = list(pend_v) + [cand_v[a] for a in accepted]
+    if mode == MODE_PARTIAL:
+        return L, rows_k, rows_v
+    for rk, rv in zip(rows_k, rows_v):
+        if L >= capacity:
+            break
+        K[L] = rk
+        V[L] = rv
+        L += 1
+    return L, [], []

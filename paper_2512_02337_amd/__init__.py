@@ -8,8 +8,11 @@ raises.
 from .binding import (REDUCE_LAST, REDUCE_MAX, REDUCE_MEAN, SpecPVError, KV, Tree, SelectCfg, load,
                       lib_path, specpv_block_summarize, specpv_full_verify_refresh,
                       specpv_partial_verify_attn, specpv_select_blocks, specpv_workspace_bytes,
-                      specpv_strerror, specpv_version, EXPORTS)
+                      specpv_strerror, specpv_version, EXPORTS, MODE_FULL, MODE_PARTIAL, MODE_REFRESH,
+                      specpv_select_mode, specpv_extend_parents, specpv_commit_accepted)
 
 __all__ = ["REDUCE_LAST", "REDUCE_MAX", "REDUCE_MEAN", "SpecPVError", "KV", "Tree", "SelectCfg", "load",
            "lib_path", "specpv_block_summarize", "specpv_full_verify_refresh", "specpv_partial_verify_attn",
-           "specpv_select_blocks", "specpv_workspace_bytes", "specpv_strerror", "specpv_version", "EXPORTS"]
+           "specpv_select_blocks", "specpv_workspace_bytes", "specpv_strerror", "specpv_version", "EXPORTS",
+           "MODE_FULL", "MODE_PARTIAL", "MODE_REFRESH", "specpv_select_mode", "specpv_extend_parents",
+           "specpv_commit_accepted"]

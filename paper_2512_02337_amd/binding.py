@@ -16,8 +16,11 @@ REDUCE_MEAN, REDUCE_MAX, REDUCE_LAST = 0, 1, 2
 _REDUCE = {"mean": 0, "max": 1, "last": 2, 0: 0, 1: 1, 2: 2}
 _DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
+MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
+
 EXPORTS = ["specpv_workspace_bytes", "specpv_block_summarize", "specpv_select_blocks",
-           "specpv_partial_verify_attn", "specpv_full_verify_refresh", "specpv_strerror",
+           "specpv_partial_verify_attn", "specpv_full_verify_refresh", "specpv_select_mode",
+           "specpv_extend_parents", "specpv_commit_accepted", "specpv_strerror",
            "specpv_last_hip_error", "specpv_version"]
 
 
@@ -39,6 +42,10 @@ class _Tree(ctypes.Structure):
     _fields_ = [("q", ctypes.c_void_p), ("kd", ctypes.c_void_p), ("vd", ctypes.c_void_p),
                 ("parent", ctypes.c_void_p), ("M", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("last_node", ctypes.c_int32)]
+
+
+class _Policy(ctypes.Structure):
+    _fields_ = [("partial_budget_tokens", ctypes.c_int32), ("pending_margin_tokens", ctypes.c_int32)]
 
 
 class _Cfg(ctypes.Structure):
@@ -74,6 +81,12 @@ def load():
     lib.specpv_partial_verify_attn.argtypes = [P(_KV), P(_Tree), vp, vp, i32, vp, vp, vp, sz, vp]
     lib.specpv_full_verify_refresh.restype = ctypes.c_int
     lib.specpv_full_verify_refresh.argtypes = [P(_KV), P(_Tree), vp, vp, i32, P(_Cfg), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.specpv_select_mode.restype = ctypes.c_int
+    lib.specpv_select_mode.argtypes = [P(_Policy), ctypes.c_int64, i32, i32]
+    lib.specpv_extend_parents.restype = ctypes.c_int
+    lib.specpv_extend_parents.argtypes = [P(i32), i32, i32, P(i32)]
+    lib.specpv_commit_accepted.restype = ctypes.c_int
+    lib.specpv_commit_accepted.argtypes = [P(_KV), vp, vp, i32, i32, vp, vp, vp, i32, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.specpv_strerror.restype = ctypes.c_char_p
     lib.specpv_strerror.argtypes = [ctypes.c_int]
     lib.specpv_last_hip_error.restype = ctypes.c_char_p
@@ -255,6 +268,44 @@ def specpv_full_verify_refresh(kv, tree, kmax, kmin, stale_blk_begin, cfg, out, 
                                              _ptr(sel_idx, torch.int32, "sel_idx"),
                                              _ptr(sel_count, torch.int32, "sel_count"),
                                              _ptr(scores, torch.float32, "scores"), wp, wb, _stream()))
+
+
+def specpv_select_mode(partial_budget_tokens, pending_margin_tokens, seq_len, partial_ready, n_pending):
+    pol = _Policy(int(partial_budget_tokens), int(pending_margin_tokens))
+    rc = load().specpv_select_mode(ctypes.byref(pol), int(seq_len), 1 if partial_ready else 0, int(n_pending))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def specpv_extend_parents(tree_parent, n_pending):
+    """tree_parent: sequence of M_tree ints (host).  Returns the n_pending + M_tree parents as a list."""
+    m = len(tree_parent)
+    src = (ctypes.c_int32 * m)(*[int(x) for x in tree_parent])
+    dst = (ctypes.c_int32 * (m + int(n_pending)))()
+    _check(load().specpv_extend_parents(src, m, int(n_pending), dst))
+    return list(dst)
+
+
+def specpv_commit_accepted(kv, buf_k, buf_v, pending_cap, M_tree, n_pending, accepted, n_accepted, mode,
+                           kmax=None, kmin=None, workspace=None):
+    """buf_k / buf_v [batch, pending_cap + M_tree, Hkv, D]; n_pending, n_accepted int32 [batch];
+    accepted int32 [batch, max_accept] -- all on the GPU."""
+    for name, t in (("buf_k", buf_k), ("buf_v", buf_v)):
+        if tuple(t.shape) != (kv.batch, pending_cap + M_tree, kv.Hkv, kv.D):
+            raise ValueError("%s: [batch, pending_cap + M_tree, Hkv, D]" % name)
+    if tuple(n_pending.shape) != (kv.batch,) or tuple(n_accepted.shape) != (kv.batch,) or accepted.dim() != 2 \
+            or accepted.shape[0] != kv.batch:
+        raise ValueError("n_pending, n_accepted: int32 [batch]; accepted: int32 [batch, max_accept]")
+    for name, t in (("kmax", kmax), ("kmin", kmin)):
+        if t is not None and tuple(t.shape) != kv.summary_shape():
+            raise ValueError("%s: [batch, Hkv, max_blocks, D]" % name)
+    wp, wb = _ws(workspace)
+    _check(load().specpv_commit_accepted(ctypes.byref(kv.c), _ptr(buf_k, kv.dtype, "buf_k"), _ptr(buf_v, kv.dtype, "buf_v"),
+                                         int(pending_cap), int(M_tree), _ptr(n_pending, torch.int32, "n_pending"),
+                                         _ptr(accepted, torch.int32, "accepted"), _ptr(n_accepted, torch.int32, "n_accepted"),
+                                         int(accepted.shape[1]), int(mode), _ptr(kmax, kv.dtype, "kmax"),
+                                         _ptr(kmin, kv.dtype, "kmin"), wp, wb, _stream()))
 
 
 def specpv_strerror(status):

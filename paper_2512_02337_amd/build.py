@@ -7,7 +7,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecpv.so")
 SOURCES = ["api.hip", "summarize.hip", "select.hip", "score_mfma.hip", "attn_generic.hip",
-           "attn_mfma.hip", "combine.hip"]
+           "attn_mfma.hip", "combine.hip", "commit.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

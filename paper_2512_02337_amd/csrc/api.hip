@@ -178,7 +178,7 @@ extern "C" {
 size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, const specpv_select_cfg *cfg)
 {
     if (check_kv(kv) != SPECPV_OK) return 0;
-    if (!tree) return 256;
+    if (!tree) { const size_t n = align_up((size_t)kv->batch * sizeof(int32_t)); return n > 256 ? n : 256; }
     if (check_tree(kv, tree, false) != SPECPV_OK) return 0;
     const Shape s = make_shape(kv, tree);
     int nsplit = plan_splits(s, kv->dtype, s.max_blocks);
@@ -259,6 +259,49 @@ int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree, voi
     rc = run_attention(s, kv->dtype, nullptr, nullptr, 0, out, lse, workspace, workspace_bytes, st);
     if (rc != SPECPV_OK) return rc;
     return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores ? scores : w.scores, st);
+}
+
+int specpv_select_mode(const specpv_policy *policy, int64_t seq_len, int32_t partial_ready, int32_t n_pending)
+{
+    if (!policy || policy->partial_budget_tokens < 0 || policy->pending_margin_tokens < 0 || seq_len < 0 || n_pending < 0)
+        return SPECPV_EINVAL;
+    if (seq_len <= policy->partial_budget_tokens) return SPECPV_MODE_FULL;
+    if (!partial_ready) return SPECPV_MODE_FULL;
+    if (n_pending > policy->pending_margin_tokens) return SPECPV_MODE_REFRESH;
+    return SPECPV_MODE_PARTIAL;
+}
+
+int specpv_extend_parents(const int32_t *tree_parent, int32_t M_tree, int32_t n_pending, int32_t *out)
+{
+    if (!tree_parent || !out || M_tree < 1 || n_pending < 0) return SPECPV_EINVAL;
+    if ((int64_t)M_tree + n_pending > SPECPV_MAX_M) return SPECPV_ELIMIT;
+    for (int32_t i = 0; i < n_pending; ++i) out[i] = i - 1;
+    for (int32_t j = 0; j < M_tree; ++j) {
+        if (tree_parent[j] >= j) return SPECPV_EINVAL;
+        out[n_pending + j] = tree_parent[j] < 0 ? n_pending - 1 : tree_parent[j] + n_pending;
+    }
+    return SPECPV_OK;
+}
+
+int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_t pending_cap, int32_t M_tree,
+                           int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
+                           int32_t max_accept, specpv_mode mode, void *kmax, void *kmin,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if (!buf_k || !buf_v || !n_pending || !accepted || !n_accepted) return SPECPV_EINVAL;
+    if (pending_cap < 0 || M_tree < 1 || max_accept < 1) return SPECPV_EINVAL;
+    if (mode != SPECPV_MODE_FULL && mode != SPECPV_MODE_PARTIAL && mode != SPECPV_MODE_REFRESH) return SPECPV_EINVAL;
+    if (((uintptr_t)buf_k | (uintptr_t)buf_v) & 15) return SPECPV_EINVAL;
+    if ((kmax || kmin) && (!kmax || !kmin || (((uintptr_t)kmax | (uintptr_t)kmin) & 15))) return SPECPV_EINVAL;
+    if ((int64_t)pending_cap + max_accept > 128 || (int64_t)pending_cap + M_tree > SPECPV_MAX_M) return SPECPV_ELIMIT;
+    if (!workspace || workspace_bytes < (size_t)kv->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
+    const Shape s = make_shape(kv, nullptr);
+    const hipError_t e = launch_commit(s, kv->dtype, buf_k, buf_v, pending_cap, M_tree, n_pending, accepted, n_accepted,
+                                       max_accept, mode != SPECPV_MODE_PARTIAL, kmax, kmin, (int32_t *)workspace,
+                                       (hipStream_t)stream);
+    return e == hipSuccess ? SPECPV_OK : fail_hip(e);
 }
 
 const char *specpv_strerror(int status)

@@ -1,0 +1,158 @@
+// KV side of what follows a verify step (Section 3.2: the buffer keeps the candidates' K/V
+// so that invalid tokens can be removed once verification is completed; Section 3.3: a
+// full verification moves the partially verified tokens into the cache).  Pure data
+// movement of at most a few dozen rows per (sequence, KV head), then the block summaries
+// (eq. 1) of the blocks that received tokens.
+#include "internal.h"
+
+namespace specpv {
+
+constexpr int kCommitMaxRows = 128;   // pending + accepted rows one call moves per sequence (host-checked)
+
+// One workgroup per (KV head, sequence); a row of D elements is D * sizeof(T) / 16 lanes.
+// Every source row is read into registers before anything is written (the compaction of
+// the buffer moves rows within one array).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void commit_copy_kernel(Shape s, T *buf_k, T *buf_v, int P, int Mt,
+                                                          const int32_t *n_pending, const int32_t *accepted,
+                                                          const int32_t *n_accepted, int max_accept, int to_cache)
+{
+    constexpr int LPR = D * (int)sizeof(T) / 16;   // lanes per row
+    constexpr int RPP = 256 / LPR;                 // rows per pass
+    constexpr int PASSES = (kCommitMaxRows + RPP - 1) / RPP;
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int c = threadIdx.x % LPR, r0 = threadIdx.x / LPR;
+    const int L = s.ctx_len[b];
+    const int n = min(max(n_pending[b], 0), P);
+    int a = min(max(n_accepted[b], 0), max_accept);
+    int total = n + a;
+    if (to_cache) total = min(total, max(0, s.max_blocks * s.B - L));   // the cache is full: the rest is dropped
+    else total = min(total, P);
+    const int64_t buf_rows = (int64_t)P + Mt;
+    auto buf_row = [&](T *base, int row) -> uint4 * {
+        return (uint4 *)(base + (((int64_t)b * buf_rows + row) * s.Hkv + g) * D) + c;
+    };
+    uint4 kr[PASSES], vr[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int i = p * RPP + r0;
+        if (i < total) {
+            int src;
+            if (i < n) src = P - n + i;                             // pending token i (oldest first)
+            else src = P + min(max(accepted[(int64_t)b * max_accept + (i - n)], 0), Mt - 1);   // accepted candidate
+            kr[p] = *buf_row(buf_k, src);
+            vr[p] = *buf_row(buf_v, src);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int i = p * RPP + r0;
+        if (i < total) {
+            if (to_cache) {
+                const int64_t off = (int64_t)b * s.sb + (int64_t)g * s.sh + (int64_t)(L + i) * s.st;
+                *((uint4 *)((T *)s.k + off) + c) = kr[p];
+                *((uint4 *)((T *)s.v + off) + c) = vr[p];
+            } else {
+                *buf_row(buf_k, P - total + i) = kr[p];
+                *buf_row(buf_v, P - total + i) = vr[p];
+            }
+        }
+    }
+}
+
+// One thread per sequence, after the copies: the new lengths (the old committed length goes to
+// old_len for the summary update).
+__global__ void commit_update_kernel(Shape s, int P, int32_t *ctx_len, int32_t *n_pending,
+                                     const int32_t *n_accepted, int max_accept, int to_cache, int32_t *old_len)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= s.batch) return;
+    const int L = ctx_len[b];
+    const int n = min(max(n_pending[b], 0), P);
+    const int a = min(max(n_accepted[b], 0), max_accept);
+    old_len[b] = L;
+    if (to_cache) {
+        ctx_len[b] = L + min(n + a, max(0, s.max_blocks * s.B - L));
+        n_pending[b] = 0;
+    } else {
+        n_pending[b] = min(n + a, P);
+    }
+}
+
+// eq. 1 for the blocks old_len / B .. (new length - 1) / B of every sequence: one wavefront per
+// (block, KV head), lanes over 16-byte pieces of a row, rows strided over the lane groups.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void summarize_tail_kernel(Shape s, const int32_t *old_len, void *kmax, void *kmin)
+{
+    constexpr int E = Elem<T>::kPerVec;
+    constexpr int LPR = D / E;
+    constexpr int RPP = 64 / LPR;
+    const int lane = threadIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int L = s.ctx_len[b], L0 = old_len[b];
+    if (L <= L0) return;
+    const int i = L0 / s.B + blockIdx.x;
+    if (i >= s.max_blocks || (int64_t)i * s.B >= L) return;
+    const int t0 = i * s.B, t1 = min(t0 + s.B, L);
+    const int c = lane % LPR, rsub = lane / LPR;
+    const T *base = (const T *)s.k + (int64_t)b * s.sb + (int64_t)g * s.sh + c * E;
+    float mx[E], mn[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; }
+    for (int t = t0 + rsub; t < t1; t += RPP) {
+        const uint4 u = *(const uint4 *)(base + (int64_t)t * s.st);
+        float f[E];
+        Elem<T>::unpack(u, f);
+#pragma unroll
+        for (int e = 0; e < E; ++e) { mx[e] = fmaxf(mx[e], f[e]); mn[e] = fminf(mn[e], f[e]); }
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], off));
+            mn[e] = fminf(mn[e], __shfl_xor(mn[e], off));
+        }
+    }
+    if (rsub == 0) {
+        const int64_t o = (((int64_t)b * s.Hkv + g) * s.max_blocks + i) * D + c * E;
+        *(uint4 *)((T *)kmax + o) = Elem<T>::pack(mx);
+        *(uint4 *)((T *)kmin + o) = Elem<T>::pack(mn);
+    }
+}
+
+hipError_t launch_commit(const Shape &s, int dtype, void *buf_k, void *buf_v, int P, int Mt,
+                         int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
+                         int max_accept, int to_cache, void *kmax, void *kmin, int32_t *old_len, hipStream_t st)
+{
+    if (P + max_accept > kCommitMaxRows) return hipErrorInvalidValue;
+    const dim3 grid(s.Hkv, s.batch);
+#define SPECPV_COPY(T, DD)                                                                             \
+    hipLaunchKernelGGL((commit_copy_kernel<T, DD>), grid, dim3(256), 0, st, s, (T *)buf_k, (T *)buf_v, P, Mt, \
+                       n_pending, accepted, n_accepted, max_accept, to_cache)
+    if (dtype == SPECPV_BF16) {
+        if (s.D == 128) SPECPV_COPY(bf16_t, 128); else SPECPV_COPY(bf16_t, 64);
+    } else {
+        if (s.D == 128) SPECPV_COPY(float, 128); else SPECPV_COPY(float, 64);
+    }
+#undef SPECPV_COPY
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(commit_update_kernel, dim3((s.batch + 63) / 64), dim3(64), 0, st, s, P,
+                       (int32_t *)s.ctx_len, n_pending, n_accepted, max_accept, to_cache, old_len);
+    e = hipGetLastError();
+    if (e != hipSuccess || !to_cache || !kmax || !kmin) return e;
+    // blocks that can have received one of at most P + max_accept tokens
+    const int touched = (P + max_accept + s.B - 1) / s.B + 1;
+    const dim3 g2(touched, s.Hkv, s.batch);
+#define SPECPV_SUM(T, DD) hipLaunchKernelGGL((summarize_tail_kernel<T, DD>), g2, dim3(64), 0, st, s, old_len, kmax, kmin)
+    if (dtype == SPECPV_BF16) {
+        if (s.D == 128) SPECPV_SUM(bf16_t, 128); else SPECPV_SUM(bf16_t, 64);
+    } else {
+        if (s.D == 128) SPECPV_SUM(float, 128); else SPECPV_SUM(float, 64);
+    }
+#undef SPECPV_SUM
+    return hipGetLastError();
+}
+
+}  // namespace specpv

@@ -100,6 +100,11 @@ bool attn_ctx_mfma_supported(const Shape &s, int dtype);
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
                                 int n_sel, Partials p, hipStream_t st);
 hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st);
+// to_cache != 0: pending + accepted rows go to the cache tail (lengths, summaries updated);
+// otherwise the accepted rows join the pending rows of the buffer.  old_len: [batch] scratch.
+hipError_t launch_commit(const Shape &s, int dtype, void *buf_k, void *buf_v, int P, int Mt,
+                         int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
+                         int max_accept, int to_cache, void *kmax, void *kmin, int32_t *old_len, hipStream_t st);
 
 int device_cu_count();
 

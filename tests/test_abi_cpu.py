@@ -98,3 +98,51 @@ def test_binding_refuses_cpu_tensors():
     k = torch.zeros((1, 1, 64, 64))
     with pytest.raises(ValueError):
         specpv.KV(k, k, torch.zeros((1,), dtype=torch.int32), 16)
+
+
+def test_mode_policy_and_extended_parents_on_the_host():
+    """Host-only entry points: the library's SelectMode and extended-tree parents against the
+    hand-worked example and the oracle's own version (no GPU involved)."""
+    import json
+    import numpy as np
+    import oracle
+    import workloads
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "mode_policy_hand_example.json")))
+    names = {"FULL": specpv.MODE_FULL, "PARTIAL": specpv.MODE_PARTIAL, "REFRESH": specpv.MODE_REFRESH}
+    for st in g["steps"]:
+        got = specpv.specpv_select_mode(g["partial_budget_tokens"], g["pending_margin_tokens"], st["seq_len"],
+                                        st["partial_ready"], st["n_pending"])
+        assert got == names[st["mode"]], st
+    for budget in (0, 7, 100):
+        for margin in (0, 3):
+            for seq_len in (0, 6, 7, 8, 100, 101, 5000):
+                for ready in (False, True):
+                    for pending in (0, 3, 4, 50):
+                        assert specpv.specpv_select_mode(budget, margin, seq_len, ready, pending) == \
+                            oracle.select_mode(seq_len, ready, pending, budget, margin)
+    rng = np.random.default_rng(0)
+    for n_pending in (0, 1, 20):
+        for kind in ("uniform", "bounded", "chain", "star"):
+            tree = workloads.make_tree(17, kind, rng).tolist()
+            assert specpv.specpv_extend_parents(tree, n_pending) == oracle.extend_parents(tree, n_pending)
+    lib = specpv.load()
+    pol = binding._Policy(-1, 0)
+    assert lib.specpv_select_mode(ctypes.byref(pol), 5, 0, 0) == -1
+    assert lib.specpv_select_mode(None, 5, 0, 0) == -1
+    bad = (ctypes.c_int32 * 3)(-1, 1, 0)     # parent[1] = 1 is not an earlier node
+    out = (ctypes.c_int32 * 8)()
+    assert lib.specpv_extend_parents(bad, 3, 2, out) == -1
+    assert lib.specpv_extend_parents(bad, 3, 126, out) == -3
+    # commit: fake pointers, never dereferenced
+    vp = ctypes.c_void_p
+    B = ctypes.byref
+    ok_args = (vp(0x100), vp(0x200), 28, 60, vp(0x300), vp(0x400), vp(0x500), 8, 1, None, None, vp(0x8000), 4096, None)
+    assert lib.specpv_commit_accepted(None, *ok_args) == -1
+    a = list(ok_args); a[0] = None
+    assert lib.specpv_commit_accepted(B(_kv()), *a) == -1
+    a = list(ok_args); a[8] = 7
+    assert lib.specpv_commit_accepted(B(_kv()), *a) == -1          # unknown mode
+    a = list(ok_args); a[2] = 125
+    assert lib.specpv_commit_accepted(B(_kv()), *a) == -3          # buffer beyond the limits
+    a = list(ok_args); a[12] = 2
+    assert lib.specpv_commit_accepted(B(_kv()), *a) == -2          # workspace too small

@@ -1,0 +1,134 @@
+"""GPU parity of the verification modes and the buffer (Section 3.3, Algorithm 1): a
+synthetic multi-step decode.  Every step picks the mode with the library's SelectMode, runs
+the attention the mode prescribes on the device state (partial over the kept blocks, or
+full + refresh, with the partially verified tokens as the chain prefix of the tree), accepts a
+seeded random root path, and commits it.  The fp64 oracle runs the same steps on its own
+copy of the state.  Bars: modes, lengths, cache rows, buffer rows, summaries and kept
+lists bit-exact (lists under the near-tie margin rule); attention outputs max-abs <= 2e-2
+(bf16) / 1e-5 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from helpers import ATOL, check_selection, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype,D,B,Hq,Hkv,M,L0", [("bf16", 128, 16, 8, 2, 12, 215),
+                                                  ("f32", 64, 8, 4, 2, 9, 130)])
+def test_multi_step_decode(gpu_lib, dtype, D, B, Hq, Hkv, M, L0):
+    sp = gpu_lib
+    dev = torch.device("cuda")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rng = np.random.default_rng(1234 + D)
+    gen = torch.Generator().manual_seed(99 + D)
+    ns, nr, kb = 2, 3, 9
+    budget = (ns + nr + kb) * B                # the partial cache without the buffer
+    margin, max_accept = 6, 5
+    P = margin + max_accept + 1                # room for the pending tokens
+    nbm = 64                                   # capacity in blocks
+    T = nbm * B
+
+    def rnd(*shape):
+        return torch.randn(shape, generator=gen).to(tdt)
+
+    # device state
+    k, v = torch.zeros((1, Hkv, T, D), dtype=tdt), torch.zeros((1, Hkv, T, D), dtype=tdt)
+    k[0, :, :L0], v[0, :, :L0] = rnd(Hkv, L0, D), rnd(Hkv, L0, D)
+    k, v = k.to(dev), v.to(dev)
+    ctx_len = torch.tensor([L0], dtype=torch.int32, device=dev)
+    kv = sp.KV(k, v, ctx_len, B, nbm)
+    buf_k = torch.zeros((1, P + M, Hkv, D), dtype=tdt, device=dev)
+    buf_v = torch.zeros_like(buf_k)
+    n_pending = torch.zeros((1,), dtype=torch.int32, device=dev)
+    kmax = torch.zeros((1, Hkv, nbm, D), dtype=tdt, device=dev)
+    kmin = torch.zeros_like(kmax)
+    cfg = sp.SelectCfg(ns, nr, kb, "mean")
+    sel_idx = torch.full((1, Hkv, cfg.n_sel), -1, dtype=torch.int32, device=dev)
+    sel_count = torch.zeros((1, Hkv), dtype=torch.int32, device=dev)
+    sp.specpv_block_summarize(kv, 0, -1, kmax, kmin)
+    # oracle state: K / V [T, Hkv, D] float64 copies of the same numbers
+    Ko, Vo = _f64(k[0]).transpose(1, 0, 2).copy(), _f64(v[0]).transpose(1, 0, 2).copy()
+    L, pend_k, pend_v, ready = L0, [], [], False
+    o_idx = o_cnt = None
+    modes = []
+    for step in range(16):
+        n = len(pend_k)
+        mode = sp.specpv_select_mode(budget, margin, L + n, ready, n)
+        assert mode == oracle.select_mode(L + n, ready, n, budget, margin)
+        modes.append(mode)
+        # this step's candidates (and, on a refresh, recomputed K/V of the pending tokens)
+        tree = workloads.make_tree(M, "bounded", rng, max_depth=max_accept - 1)
+        q, kd, vd = rnd(1, n + M, Hq, D).to(dev), rnd(1, M, Hkv, D).to(dev), rnd(1, M, Hkv, D).to(dev)
+        buf_k[:, P:], buf_v[:, P:] = kd, vd
+        if mode != sp.MODE_PARTIAL and n > 0:
+            nk, nv = rnd(1, n, Hkv, D).to(dev), rnd(1, n, Hkv, D).to(dev)
+            buf_k[:, P - n:P], buf_v[:, P - n:P] = nk, nv
+            pend_k, pend_v = list(_f64(nk[0])), list(_f64(nv[0]))
+        ext = sp.specpv_extend_parents(tree.tolist(), n)
+        assert ext == oracle.extend_parents(tree.tolist(), n)
+        parent = torch.tensor([ext], dtype=torch.int32, device=dev)
+        tr = sp.Tree(q, buf_k[:, P - n:], buf_v[:, P - n:], parent)
+        out = torch.zeros_like(q)
+        lse = torch.zeros((1, n + M, Hq), dtype=torch.float32, device=dev)
+        ws = torch.empty((sp.specpv_workspace_bytes(kv, tr, cfg),), dtype=torch.uint8, device=dev)
+        Qo = _f64(q[0])
+        Kd_o = np.stack(pend_k + list(_f64(kd[0])))
+        Vd_o = np.stack(pend_v + list(_f64(vd[0])))
+        if mode == sp.MODE_PARTIAL:
+            sp.specpv_partial_verify_attn(kv, tr, sel_idx, sel_count, out, lse, ws)
+            O, LSE, _ = oracle.tree_attention(Qo, Ko[:L], Vo[:L], Kd_o, Vd_o, np.array(ext, np.int32), B, o_idx, o_cnt)
+        elif L + n <= budget:
+            sp.specpv_partial_verify_attn(kv, tr, None, None, out, lse, ws)      # plain full verification
+            O, LSE, _ = oracle.tree_attention(Qo, Ko[:L], Vo[:L], Kd_o, Vd_o, np.array(ext, np.int32), B)
+        else:
+            # full verification that (re)builds the partial cache with this pass's queries
+            sp.specpv_full_verify_refresh(kv, tr, kmax, kmin, -1, cfg, out, lse, sel_idx, sel_count, None, ws)
+            O, LSE, o_idx, o_cnt, sc = oracle.full_verify_refresh(Qo, Ko[:L], Vo[:L], Kd_o, Vd_o,
+                                                                  np.array(ext, np.int32), B, ns, nr, kb)
+            torch.cuda.synchronize()
+            check_selection(sel_idx.cpu().numpy()[0], sel_count.cpu().numpy()[0], o_idx, o_cnt, sc, ns, nr, kb,
+                            "step %d" % step)
+            o_idx, o_cnt = sel_idx.cpu().numpy()[0].copy(), sel_count.cpu().numpy()[0].copy()   # continue on the device's lists
+            ready = True
+        torch.cuda.synchronize()
+        err = np.abs(_f64(out[0]) - O).max()
+        assert err <= ATOL[dtype], (step, mode, err)
+        # a seeded random accepted root path
+        path, node = [0], 0
+        want = int(rng.integers(1, max_accept + 1))
+        while len(path) < want:
+            kids = [j for j in range(M) if tree[j] == node]
+            if not kids:
+                break
+            node = kids[int(rng.integers(0, len(kids)))]
+            path.append(node)
+        acc = torch.full((1, max_accept), -1, dtype=torch.int32)
+        acc[0, :len(path)] = torch.tensor(path, dtype=torch.int32)
+        n_acc = torch.tensor([len(path)], dtype=torch.int32, device=dev)
+        L_before = L
+        sp.specpv_commit_accepted(kv, buf_k, buf_v, P, M, n_pending, acc.to(dev), n_acc, mode, kmax, kmin, ws)
+        L, pend_k, pend_v = oracle.commit_accepted(Ko, Vo, L, pend_k, pend_v, _f64(kd[0]), _f64(vd[0]), path, mode, T)
+        torch.cuda.synchronize()
+        assert int(ctx_len[0]) == L and int(n_pending[0]) == len(pend_k), (step, mode)
+        kd_all, vd_all = _f64(k[0]).transpose(1, 0, 2), _f64(v[0]).transpose(1, 0, 2)
+        assert np.array_equal(kd_all[:L], Ko[:L]) and np.array_equal(vd_all[:L], Vo[:L]), (step, "cache rows")
+        assert not kd_all[L:].any() and not vd_all[L:].any(), (step, "rows beyond the committed length")
+        if pend_k:
+            m = len(pend_k)
+            assert np.array_equal(_f64(buf_k[0, P - m:P]), np.stack(pend_k)), (step, "pending K rows")
+            assert np.array_equal(_f64(buf_v[0, P - m:P]), np.stack(pend_v)), (step, "pending V rows")
+        nb = (L + B - 1) // B
+        omax, omin = oracle.block_summarize(Ko[:L], B)
+        assert np.array_equal(_f64(kmax[0, :, :nb]), omax.transpose(1, 0, 2)), (step, "kmax")
+        assert np.array_equal(_f64(kmin[0, :, :nb]), omin.transpose(1, 0, 2)), (step, "kmin")
+        say("   step %2d mode %s: %d pending before, accepted %d, L %d -> %d, attention err %.3g"
+            % (step, ["FULL", "PARTIAL", "REFRESH"][mode], n, len(path), L_before, L, err))
+    assert sp.MODE_PARTIAL in modes and sp.MODE_REFRESH in modes and modes[0] == sp.MODE_FULL

@@ -368,3 +368,94 @@ def test_full_verify_refresh_is_the_composition():
     idx_ref, cnt_ref = oracle.select_blocks(oracle.block_scores(Q, kmax, kmin), 1, 2, 4)
     assert np.array_equal(O, O_ref) and np.array_equal(idx, idx_ref) and np.array_equal(cnt, cnt_ref)
     assert idx.shape == (2, 7) and (cnt == 7).all()
+
+
+# ---- verification modes and the buffer (Section 3.3, Algorithm 1) ---------------------------
+
+def test_mode_policy_matches_the_hand_worked_example():
+    """tests/golden/mode_policy_hand_example.json: the mode sequence written out by hand from
+    Section 3.3; also replays the state transitions it implies."""
+    g = json.load(open(os.path.join(GOLD, "mode_policy_hand_example.json")))
+    names = {"FULL": oracle.MODE_FULL, "PARTIAL": oracle.MODE_PARTIAL, "REFRESH": oracle.MODE_REFRESH}
+    budget, margin = g["partial_budget_tokens"], g["pending_margin_tokens"]
+    seq_len, ready, pending = g["steps"][0]["seq_len"], False, 0
+    for st in g["steps"]:
+        assert (seq_len, ready, pending) == (st["seq_len"], st["partial_ready"], st["n_pending"]), st
+        mode = oracle.select_mode(seq_len, ready, pending, budget, margin)
+        assert mode == names[st["mode"]], (st, mode)
+        if mode == oracle.MODE_PARTIAL:
+            pending += st["accepted"]
+        else:
+            pending = 0
+            if seq_len > budget:
+                ready = True
+        seq_len += st["accepted"]
+
+
+def _ancestor_set(parent, j):
+    out = set()
+    while j >= 0:
+        out.add(j)
+        j = parent[j]
+    return out
+
+
+def test_extended_tree_is_a_chain_plus_the_shifted_tree():
+    rng = np.random.default_rng(3)
+    for n_pending in (0, 1, 7):
+        tree = workloads.make_tree(13, "uniform", rng)
+        ext = oracle.extend_parents(tree, n_pending)
+        assert len(ext) == n_pending + 13 and all(p < i for i, p in enumerate(ext))
+        for j in range(13):
+            want = set(range(n_pending)) | {a + n_pending for a in _ancestor_set(tree, j)}
+            assert _ancestor_set(ext, n_pending + j) == want
+        for i in range(n_pending):
+            assert _ancestor_set(ext, i) == set(range(i + 1))
+
+
+def test_pending_tokens_as_chain_prefix_equal_pending_tokens_in_the_cache():
+    """The reading behind the buffer (Section 3.2: the four components are handled as one
+    continuous KV segment): attending over `cache + pending chain + tree` gives the candidates
+    exactly what attending over `cache extended by the pending tokens + tree` gives them."""
+    rng = np.random.default_rng(11)
+    Hq, Hkv, D, B, L, n_pending, M = 4, 2, 16, 4, 37, 5, 9
+    K, V = rng.standard_normal((L, Hkv, D)), rng.standard_normal((L, Hkv, D))
+    pk, pv = rng.standard_normal((n_pending, Hkv, D)), rng.standard_normal((n_pending, Hkv, D))
+    Q, Kd, Vd = rng.standard_normal((M, Hq, D)), rng.standard_normal((M, Hkv, D)), rng.standard_normal((M, Hkv, D))
+    tree = workloads.make_tree(M, "bounded", rng)
+    ext = np.array(oracle.extend_parents(tree, n_pending), dtype=np.int32)
+    Qe = np.concatenate([rng.standard_normal((n_pending, Hq, D)), Q])   # the pending tokens' queries do not matter
+    O1, lse1, _ = oracle.tree_attention(Qe, K, V, np.concatenate([pk, Kd]), np.concatenate([pv, Vd]), ext, B)
+    O2, lse2, _ = oracle.tree_attention(Q, np.concatenate([K, pk]), np.concatenate([V, pv]), Kd, Vd,
+                                        np.array(tree, dtype=np.int32), B)
+    np.testing.assert_allclose(O1[n_pending:], O2, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(lse1[n_pending:], lse2, rtol=1e-11, atol=1e-12)
+
+
+def test_commit_keeps_exactly_the_accepted_tokens_in_order():
+    rng = np.random.default_rng(5)
+    Hkv, D, cap, L0, M = 2, 8, 64, 20, 10
+    K, V = np.zeros((cap, Hkv, D)), np.zeros((cap, Hkv, D))
+    K[:L0], V[:L0] = rng.standard_normal((L0, Hkv, D)), rng.standard_normal((L0, Hkv, D))
+    K0, V0 = K.copy(), V.copy()
+    L, pk, pv = L0, [], []
+    log_k = []          # what the cache must hold behind L0 in the end, written down independently
+    pend_log = []
+    for step, mode in enumerate([oracle.MODE_PARTIAL, oracle.MODE_PARTIAL, oracle.MODE_REFRESH, oracle.MODE_FULL,
+                                 oracle.MODE_PARTIAL]):
+        ck, cv = rng.standard_normal((M, Hkv, D)), rng.standard_normal((M, Hkv, D))
+        acc = sorted(rng.choice(M, size=int(rng.integers(1, 5)), replace=False).tolist())
+        L_before = L
+        L, pk, pv = oracle.commit_accepted(K, V, L, pk, pv, ck, cv, acc, mode, cap)
+        pend_log += [ck[a] for a in acc]
+        if mode == oracle.MODE_PARTIAL:
+            assert L == L_before and len(pk) == len(pend_log)
+            assert np.array_equal(K, K0) or L_before > L0   # a partial step never writes the cache
+        else:
+            log_k += pend_log
+            pend_log = []
+            assert len(pk) == 0 and L == L0 + len(log_k)
+    assert np.array_equal(K[:L0], K0[:L0]) and np.array_equal(V[:L0], V0[:L0])
+    assert np.array_equal(K[L0:L], np.stack(log_k))
+    assert not K[L:].any()                                   # nothing beyond the committed length
+    assert len(pk) == len(pend_log) and all(np.array_equal(a, b) for a, b in zip(pk, pend_log))
