@@ -180,6 +180,26 @@ def main():
                 specpv.specpv_commit_accepted(l["kv"], cb["k"], cb["v"], P, Mt, cb["n_pending"], cb["accepted"],
                                               cb["n_accepted"], specpv.MODE_PARTIAL, None, None, ws)
         extras["commit_partial_us_per_step"] = round(timed(commit_step, k2, 3, use_graph) * 1e3, 2)
+        # the paper's physically gathered partial cache (Section 3.2) against reading the blocks in
+        # place: one gather per layer, and the partial step over the gathered segments
+        g = []
+        for l in layers:
+            c = l["case"]
+            gk = torch.empty((c["batch"], c["Hkv"], c["n_sel"] * c["B"], c["D"]), dtype=c["q"].dtype, device=dev)
+            gv = torch.empty_like(gk)
+            glen = torch.zeros((c["batch"],), dtype=torch.int32, device=dev)
+            specpv.specpv_gather_blocks(l["kv"], l["sel_idx"], l["sel_count"], gk, gv, glen)
+            g.append({"k": gk, "v": gv, "len": glen, "kv": specpv.KV(gk, gv, glen, c["B"], c["n_sel"])})
+
+        def gather_step():
+            for l, x in zip(layers, g):
+                specpv.specpv_gather_blocks(l["kv"], l["sel_idx"], l["sel_count"], x["k"], x["v"], x["len"])
+
+        def gathered_partial_step():
+            for l, x in zip(layers, g):
+                specpv.specpv_partial_verify_attn(x["kv"], l["tree"], None, None, l["out"], None, ws)
+        extras["gather_us_per_step"] = round(timed(gather_step, k2, 3, use_graph) * 1e3, 2)
+        extras["partial_on_gathered_us_per_step"] = round(timed(gathered_partial_step, k2, 3, use_graph) * 1e3, 2)
         extras["setup_s"] = round(setup_s, 1)
 
     cpu = None

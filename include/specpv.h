@@ -148,6 +148,17 @@ int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree,
                                int32_t *sel_idx, int32_t *sel_count, float *scores,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* Section 3.2: the paper keeps the partial cache as a physically contiguous segment; this call
+ * builds that variant from the kept-block lists (the attention calls above read the blocks in
+ * place and do not need it).  For every sequence b and KV head g the tokens of the blocks
+ * sel_idx[b, g, 0 .. sel_count[b, g]) are copied, in list order, to out_k / out_v
+ * [batch, Hkv, n_sel * B, D] (same dtype; rows of list entries that are invalid or lie beyond
+ * L_b are zero), and out_len[b] = the largest number of token rows any of its heads produced
+ * (device, [batch]).  Attention over this gathered cache with sel_idx == NULL gives the same
+ * result as attention over the lists when every head keeps the same number of full blocks. */
+int specpv_gather_blocks(const specpv_kv *kv, const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
+                         void *out_k, void *out_v, int32_t *out_len, void *stream);
+
 /* ---- verification modes and the buffer (Section 3.3, Algorithm 1: SelectMode and the
  * KV side of PostEvaluate) ------------------------------------------------------------
  *

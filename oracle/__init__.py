@@ -202,3 +202,27 @@ def commit_accepted(K, V, L, pend_k, pend_v, cand_k, cand_v, accepted, mode, cap
         V[L] = rv
         L += 1
     return L, [], []
+
+
+def gather_blocks(K, V, B, sel_idx, sel_count):
+    """Section 3.2: the partial cache as a physically contiguous segment.  K, V [L, Hkv, D];
+    sel_idx [Hkv, n_sel], sel_count [Hkv].  Returns (Kg, Vg) [n_sel * B, Hkv, D] (rows that no
+    kept token fills are zero) and the number of rows filled per head."""
+    K, V = _f64(K), _f64(V)
+    L, Hkv, D = K.shape
+    n_sel = len(sel_idx[0])
+    Kg, Vg = np.zeros((n_sel * B, Hkv, D)), np.zeros((n_sel * B, Hkv, D))
+    rows = np.zeros(Hkv, dtype=np.int64)
+    nb = (L + B - 1) // B
+    for g in range(Hkv):
+        for slot in range(int(sel_count[g])):
+            blk = int(sel_idx[g][slot])
+            if blk < 0 or blk >= nb:
+                continue
+            for r in range(B):
+                t = blk * B + r
+                if t < L:
+                    Kg[slot * B + r, g] = K[t, g]
+                    Vg[slot * B + r, g] = V[t, g]
+                    rows[g] = max(rows[g], slot * B + r + 1)
+    return Kg, Vg, rows

@@ -19,7 +19,7 @@ _DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
 
 EXPORTS = ["specpv_workspace_bytes", "specpv_block_summarize", "specpv_select_blocks",
-           "specpv_partial_verify_attn", "specpv_full_verify_refresh", "specpv_select_mode",
+           "specpv_partial_verify_attn", "specpv_full_verify_refresh", "specpv_gather_blocks", "specpv_select_mode",
            "specpv_extend_parents", "specpv_commit_accepted", "specpv_strerror",
            "specpv_last_hip_error", "specpv_version"]
 
@@ -81,6 +81,8 @@ def load():
     lib.specpv_partial_verify_attn.argtypes = [P(_KV), P(_Tree), vp, vp, i32, vp, vp, vp, sz, vp]
     lib.specpv_full_verify_refresh.restype = ctypes.c_int
     lib.specpv_full_verify_refresh.argtypes = [P(_KV), P(_Tree), vp, vp, i32, P(_Cfg), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.specpv_gather_blocks.restype = ctypes.c_int
+    lib.specpv_gather_blocks.argtypes = [P(_KV), vp, vp, i32, vp, vp, vp, vp]
     lib.specpv_select_mode.restype = ctypes.c_int
     lib.specpv_select_mode.argtypes = [P(_Policy), ctypes.c_int64, i32, i32]
     lib.specpv_extend_parents.restype = ctypes.c_int
@@ -268,6 +270,18 @@ def specpv_full_verify_refresh(kv, tree, kmax, kmin, stale_blk_begin, cfg, out, 
                                              _ptr(sel_idx, torch.int32, "sel_idx"),
                                              _ptr(sel_count, torch.int32, "sel_count"),
                                              _ptr(scores, torch.float32, "scores"), wp, wb, _stream()))
+
+
+def specpv_gather_blocks(kv, sel_idx, sel_count, out_k, out_v, out_len=None):
+    """out_k / out_v [batch, Hkv, n_sel * B, D]; out_len int32 [batch] (optional)."""
+    n_sel = sel_idx.shape[-1]
+    _check_sel(kv, sel_idx, sel_count, n_sel)
+    for name, t in (("out_k", out_k), ("out_v", out_v)):
+        if tuple(t.shape) != (kv.batch, kv.Hkv, n_sel * kv.B, kv.D):
+            raise ValueError("%s: [batch, Hkv, n_sel * B, D]" % name)
+    _check(load().specpv_gather_blocks(ctypes.byref(kv.c), _ptr(sel_idx, torch.int32, "sel_idx"),
+                                       _ptr(sel_count, torch.int32, "sel_count"), n_sel, _ptr(out_k, kv.dtype, "out_k"),
+                                       _ptr(out_v, kv.dtype, "out_v"), _ptr(out_len, torch.int32, "out_len"), _stream()))
 
 
 def specpv_select_mode(partial_budget_tokens, pending_margin_tokens, seq_len, partial_ready, n_pending):

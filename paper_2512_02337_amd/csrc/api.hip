@@ -261,6 +261,19 @@ int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree, voi
     return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores ? scores : w.scores, st);
 }
 
+int specpv_gather_blocks(const specpv_kv *kv, const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
+                         void *out_k, void *out_v, int32_t *out_len, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if (!sel_idx || !sel_count || !out_k || !out_v || n_sel < 1) return SPECPV_EINVAL;
+    if (((uintptr_t)out_k | (uintptr_t)out_v) & 15) return SPECPV_EINVAL;
+    if (n_sel > (1 << 24) || (int64_t)n_sel * kv->block_size > ((int64_t)1 << 30)) return SPECPV_ELIMIT;
+    const Shape s = make_shape(kv, nullptr);
+    const hipError_t e = launch_gather(s, kv->dtype, sel_idx, sel_count, n_sel, out_k, out_v, out_len, (hipStream_t)stream);
+    return e == hipSuccess ? SPECPV_OK : fail_hip(e);
+}
+
 int specpv_select_mode(const specpv_policy *policy, int64_t seq_len, int32_t partial_ready, int32_t n_pending)
 {
     if (!policy || policy->partial_budget_tokens < 0 || policy->pending_margin_tokens < 0 || seq_len < 0 || n_pending < 0)

@@ -156,3 +156,77 @@ hipError_t launch_commit(const Shape &s, int dtype, void *buf_k, void *buf_v, in
 }
 
 }  // namespace specpv
+
+namespace specpv {
+
+// Gathered (physically contiguous) partial cache, Section 3.2: one workgroup per (list slot,
+// KV head, sequence) copies one block of K and of V with 16-byte accesses, all of a thread's
+// reads issued before its writes.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_blocks_kernel(Shape s, const int32_t *sel_idx, const int32_t *sel_count,
+                                                            int n_sel, T *out_k, T *out_v, int32_t *out_len)
+{
+    constexpr int E = Elem<T>::kPerVec;
+    constexpr int LPR = D / E;
+    constexpr int RPP = 256 / LPR;
+    const int slot = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int L = s.ctx_len[b];
+    int nb = L > 0 ? (L + s.B - 1) / s.B : 0;
+    if (nb > s.max_blocks) nb = s.max_blocks;
+    const int cnt = max(0, min(sel_count[(int64_t)b * s.Hkv + g], n_sel));
+    const int blk = slot < cnt ? sel_idx[((int64_t)b * s.Hkv + g) * n_sel + slot] : -1;
+    const bool valid = blk >= 0 && blk < nb;
+    const int c = threadIdx.x % LPR, rsub = threadIdx.x / LPR;
+    const int64_t src0 = (int64_t)b * s.sb + (int64_t)g * s.sh + c * E;
+    const int64_t dst0 = (((int64_t)b * s.Hkv + g) * n_sel + slot) * s.B * D + c * E;
+    for (int r0 = 0; r0 < s.B; r0 += 4 * RPP) {
+        uint4 kk[4], vv[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int r = r0 + x * RPP + rsub, t = blk * s.B + r;
+            kk[x] = make_uint4(0, 0, 0, 0);
+            vv[x] = kk[x];
+            if (valid && r < s.B && t < L) {
+                kk[x] = *(const uint4 *)((const T *)s.k + src0 + (int64_t)t * s.st);
+                vv[x] = *(const uint4 *)((const T *)s.v + src0 + (int64_t)t * s.st);
+            }
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int r = r0 + x * RPP + rsub;
+            if (r < s.B) {
+                *(uint4 *)(out_k + dst0 + (int64_t)r * D) = kk[x];
+                *(uint4 *)(out_v + dst0 + (int64_t)r * D) = vv[x];
+            }
+        }
+    }
+    if (out_len && threadIdx.x == 0 && valid) {
+        const int rows = slot * s.B + min(s.B, L - blk * s.B);   // token rows up to and including this block
+        atomicMax(&out_len[b], rows);
+    }
+}
+
+__global__ void zero_i32_kernel(int32_t *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_gather(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count, int n_sel,
+                         void *out_k, void *out_v, int32_t *out_len, hipStream_t st)
+{
+    if (out_len) hipLaunchKernelGGL(zero_i32_kernel, dim3((s.batch + 63) / 64), dim3(64), 0, st, out_len, s.batch);
+    const dim3 grid(n_sel, s.Hkv, s.batch);
+    if (grid.z > 65535u || grid.y > 65535u) return hipErrorInvalidConfiguration;
+#define SPECPV_GATHER(T, DD) \
+    hipLaunchKernelGGL((gather_blocks_kernel<T, DD>), grid, dim3(256), 0, st, s, sel_idx, sel_count, n_sel, (T *)out_k, (T *)out_v, out_len)
+    if (dtype == SPECPV_BF16) {
+        if (s.D == 128) SPECPV_GATHER(bf16_t, 128); else SPECPV_GATHER(bf16_t, 64);
+    } else {
+        if (s.D == 128) SPECPV_GATHER(float, 128); else SPECPV_GATHER(float, 64);
+    }
+#undef SPECPV_GATHER
+    return hipGetLastError();
+}
+
+}  // namespace specpv

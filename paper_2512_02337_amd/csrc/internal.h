@@ -106,6 +106,9 @@ hipError_t launch_commit(const Shape &s, int dtype, void *buf_k, void *buf_v, in
                          int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
                          int max_accept, int to_cache, void *kmax, void *kmin, int32_t *old_len, hipStream_t st);
 
+hipError_t launch_gather(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count, int n_sel,
+                         void *out_k, void *out_v, int32_t *out_len, hipStream_t st);
+
 int device_cu_count();
 
 }  // namespace specpv

@@ -459,3 +459,26 @@ def test_commit_keeps_exactly_the_accepted_tokens_in_order():
     assert np.array_equal(K[L0:L], np.stack(log_k))
     assert not K[L:].any()                                   # nothing beyond the committed length
     assert len(pk) == len(pend_log) and all(np.array_equal(a, b) for a, b in zip(pk, pend_log))
+
+
+def test_gathered_cache_gives_the_same_attention_as_the_lists():
+    """Section 3.2: the kept tokens form one contiguous KV segment.  Attention over the
+    gathered segment (all of it) equals attention over the block lists; the gather itself is
+    checked against numpy fancy indexing."""
+    rng = np.random.default_rng(21)
+    Hq, Hkv, D, B, L, M, n_sel = 4, 2, 8, 4, 46, 7, 5     # 12 blocks, the last one ragged (2 tokens)
+    K, V = rng.standard_normal((L, Hkv, D)), rng.standard_normal((L, Hkv, D))
+    Q, Kd, Vd = rng.standard_normal((M, Hq, D)), rng.standard_normal((M, Hkv, D)), rng.standard_normal((M, Hkv, D))
+    parent = np.array(workloads.make_tree(M, "bounded", rng), dtype=np.int32)
+    sel = np.stack([np.array([0, 3, 4, 9, 11]), np.array([1, 2, 7, 10, 11])]).astype(np.int32)
+    cnt = np.full(Hkv, n_sel, np.int32)
+    Kg, Vg, rows = oracle.gather_blocks(K, V, B, sel, cnt)
+    assert rows.tolist() == [4 * B + 2, 4 * B + 2]
+    for g in range(Hkv):
+        toks = np.concatenate([np.arange(i * B, min((i + 1) * B, L)) for i in sel[g]])
+        assert np.array_equal(Kg[:len(toks), g], K[toks, g]) and np.array_equal(Vg[:len(toks), g], V[toks, g])
+        assert not Kg[len(toks):, g].any()
+    O1, lse1, _ = oracle.tree_attention(Q, K, V, Kd, Vd, parent, B, sel, cnt)
+    O2, lse2, _ = oracle.tree_attention(Q, Kg[:rows[0]], Vg[:rows[0]], Kd, Vd, parent, B)
+    np.testing.assert_allclose(O1, O2, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse1, lse2, rtol=1e-12, atol=1e-13)
