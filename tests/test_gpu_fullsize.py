@@ -142,3 +142,28 @@ def test_paper_default_geometry(gpu_lib):
     torch.cuda.synchronize()
     qh, O, lse = _oracle_attention_on_heads(case, 0, [1, 6], (got_idx, got_cnt))
     _compare(run, case, 0, qh, O, lse, "partial, block 16")
+
+
+@pytest.mark.parametrize("budget", [512, 2048, 8192])
+def test_paper_budgets(gpu_lib, budget):
+    """The partial-cache budgets of Table 1 / Figure 5 (512, 2K, 8K tokens) in the paper's geometry
+    (Appendix D: 16-token blocks, 32 sink and 128 local tokens) at 60K context: the retrieval
+    part is k = (budget - 32 - 128) / 16 blocks."""
+    case = workloads.make_case("paper_default_4k", seed=1, device="cuda")
+    ns, nr = 2, 8
+    kb = (budget - ns * 16 - nr * 16) // 16
+    run = GpuRun(gpu_lib, case, cfg=(ns, nr, kb))
+    run.summarize(); run.select()
+    torch.cuda.synchronize()
+    L = int(case["ctx_len"][0])
+    K = case["k"][0, :, :L].permute(1, 0, 2).contiguous().cpu()
+    kmax, kmin = oracle.block_summarize(K, case["B"])
+    sc = oracle.block_scores(case["q"][0].cpu(), kmax, kmin, "mean")
+    idx, cnt = oracle.select_blocks(sc, ns, nr, kb)
+    got_idx, got_cnt = run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy()
+    exact = check_selection(got_idx, got_cnt, idx, cnt, sc, ns, nr, kb, "budget %d" % budget)
+    assert (got_cnt == ns + nr + kb).all()
+    run.attend()
+    torch.cuda.synchronize()
+    qh, O, lse = _oracle_attention_on_heads(case, 0, [2, 5], (got_idx, got_cnt))
+    _compare(run, case, 0, qh, O, lse, "budget %d (k = %d blocks, lists bit-exact: %s)" % (budget, kb, exact))
