@@ -115,6 +115,31 @@ def test_shapes_and_edges(gpu_lib, over, tag):
         _check_attn(run, case, None, tag + " full " + layout)
 
 
+@pytest.mark.parametrize("over,tag", [
+    (dict(ctx=[36000], B=64, M=100, tree="uniform"), "two row tiles, ragged tail"),
+    (dict(ctx=[33333, 40000], B=16, M=24, rho=[0.1, 0.1]), "block 16 (chunks cross blocks), batch of 2"),
+    (dict(ctx=[34816], B=64, M=30, Hq=10, Hkv=2), "G=5"),
+    (dict(ctx=[40000], B=64, M=9, Hq=2, Hkv=2), "G=1"),
+])
+def test_long_ranges_take_the_wide_kernel(gpu_lib, over, tag):
+    """Full verification over tens of thousands of tokens at small head counts: each wavefront
+    gets eight or more chunks, which selects the one-wavefront-per-SIMD kernel; head-major
+    (256-byte row stride: grouped DMA path) and token-major (general path) layouts."""
+    say("case", tag)
+    cfg = dict(SMALL); cfg.update(over)
+    case = workloads.to_device(workloads.make_case(cfg, seed=17), "cuda")
+    for layout in ("bhtd", "bthd"):
+        run = GpuRun(gpu_lib, case, layout=layout)
+        run.refresh(stale=0)
+        torch.cuda.synchronize()
+        _check_attn(run, case, None, tag + " full " + layout)
+        sel = [(run.sel_idx.cpu().numpy()[b], run.sel_count.cpu().numpy()[b]) for b in range(case["batch"])]
+        run.out.zero_()
+        run.attend()
+        torch.cuda.synchronize()
+        _check_attn(run, case, sel, tag + " partial " + layout)
+
+
 @pytest.mark.parametrize("reduce,last_node", [("max", 0), ("last", 0), ("last", 5), ("mean", 0)])
 def test_reducers(gpu_lib, reduce, last_node):
     say("reducer", reduce, last_node)
