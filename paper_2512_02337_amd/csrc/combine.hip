@@ -7,6 +7,37 @@
 
 namespace specpv {
 
+// Whole-wavefront sum / max through DPP (no LDS round trips: this kernel is a chain of
+// dependent reductions): lane ^ 1, lane ^ 2, then the mirrors inside 8 and 16 lanes leave
+// every lane of a row of 16 with the row's result; row_bcast:15 adds the end of rows 0 and 2
+// into rows 1 and 3, row_bcast:31 the end of row 1 into rows 2 and 3; lane 63 holds the
+// total, which readlane hands back as a wavefront-uniform value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_get(float v, float fill)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_u(float x)
+{
+    x += dpp_get<0xB1, 0xf>(x, 0.f);
+    x += dpp_get<0x4E, 0xf>(x, 0.f);
+    x += dpp_get<0x141, 0xf>(x, 0.f);
+    x += dpp_get<0x140, 0xf>(x, 0.f);
+    x += dpp_get<0x142, 0xa>(x, 0.f);
+    x += dpp_get<0x143, 0xc>(x, 0.f);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+__device__ __forceinline__ float wave_max_u(float x)
+{
+    x = fmaxf(x, dpp_get<0xB1, 0xf>(x, -INFINITY));
+    x = fmaxf(x, dpp_get<0x4E, 0xf>(x, -INFINITY));
+    x = fmaxf(x, dpp_get<0x141, 0xf>(x, -INFINITY));
+    x = fmaxf(x, dpp_get<0x140, 0xf>(x, -INFINITY));
+    x = fmaxf(x, dpp_get<0x142, 0xa>(x, -INFINITY));
+    x = fmaxf(x, dpp_get<0x143, 0xc>(x, -INFINITY));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, void *out, float *lse,
                                                      float scale_log2)
@@ -68,16 +99,16 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
     }
 
     // ---- context partials, merged relative to their own maximum (first-round data) -------
-    const float m_ctx = wave_max(mlv.x);
+    const float m_ctx = wave_max_u(mlv.x);
     const float m_ctx_use = m_ctx == -INFINITY ? 0.f : m_ctx;
     const float w_mine = mlv.y > 0.f ? exp2f(mlv.x - m_ctx_use) : 0.f;
-    const float l_ctx = wave_sum(mlv.y * w_mine);
+    const float l_ctx = wave_sum_u(mlv.y * w_mine);
     float o[DPL];
 #pragma unroll
     for (int x = 0; x < DPL; ++x) o[x] = 0.f;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-        const float w = u < part.nsplit ? __shfl(w_mine, u) : 0.f;
+        const float w = u < part.nsplit ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_mine), u)) : 0.f;
 #pragma unroll
         for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, po[u][x], o[x]);
     }
@@ -91,7 +122,7 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const float w = sp0 + u < part.nsplit ? __shfl(w_mine, sp0 + u) : 0.f;
+            const float w = sp0 + u < part.nsplit ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_mine), sp0 + u)) : 0.f;
 #pragma unroll
             for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, po[u][x], o[x]);
         }
@@ -109,7 +140,7 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
             float dot = 0.f;
 #pragma unroll
             for (int x = 0; x < DPL; ++x) dot = fmaf(qv[x], kdv[u][x], dot);
-            z[u] = a[u] >= 0 ? wave_sum(dot) * scale_log2 : -INFINITY;
+            z[u] = a[u] >= 0 ? wave_sum_u(dot) * scale_log2 : -INFINITY;
         }
         const float m_new = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), m);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
