@@ -495,7 +495,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
             acc[uu] = make_float2(0.f, 0.f);
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float ww = __shfl(wgt[w], uu);
+                const float ww = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt[w]), uu));   // uniform: no LDS shuffle
                 const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + 2 * lane);
                 acc[uu].x = fmaf(ww, x.x, acc[uu].x);
                 acc[uu].y = fmaf(ww, x.y, acc[uu].y);
@@ -911,7 +911,7 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
             acc[uu] = make_float2(0.f, 0.f);
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float ww = __shfl(wgt[w], u0 + uu);
+                const float ww = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt[w]), u0 + uu));
                 const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + 2 * lane);
                 acc[uu].x = fmaf(ww, x.x, acc[uu].x);
                 acc[uu].y = fmaf(ww, x.y, acc[uu].y);
