@@ -206,16 +206,49 @@ __device__ __forceinline__ uint32_t score_bits(float score)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Wavefront scans and reductions through DPP (no LDS round trips).  row_shr:n shifts inside rows
+// of 16 lanes (zeros come in), row_bcast:15 / row_bcast:31 carry the row totals on.
+template <int CTRL, int ROW_MASK, bool ZERO_FILL>
+__device__ __forceinline__ int dpp_i32(int v, int fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, CTRL, ROW_MASK, 0xf, ZERO_FILL);
+}
+__device__ __forceinline__ int wave_inclusive_scan(int x)
+{
+    x += dpp_i32<0x111, 0xf, true>(x, 0);   // row_shr:1
+    x += dpp_i32<0x112, 0xf, true>(x, 0);   // row_shr:2
+    x += dpp_i32<0x114, 0xf, true>(x, 0);   // row_shr:4
+    x += dpp_i32<0x118, 0xf, true>(x, 0);   // row_shr:8
+    x += dpp_i32<0x142, 0xa, false>(x, 0);  // row_bcast:15 into rows 1 and 3
+    x += dpp_i32<0x143, 0xc, false>(x, 0);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x)
+{
+    x = min(x, (uint32_t)dpp_i32<0xB1, 0xf, false>((int)x, -1));
+    x = min(x, (uint32_t)dpp_i32<0x4E, 0xf, false>((int)x, -1));
+    x = min(x, (uint32_t)dpp_i32<0x141, 0xf, false>((int)x, -1));
+    x = min(x, (uint32_t)dpp_i32<0x140, 0xf, false>((int)x, -1));
+    x = min(x, (uint32_t)dpp_i32<0x142, 0xa, false>((int)x, -1));
+    x = min(x, (uint32_t)dpp_i32<0x143, 0xc, false>((int)x, -1));
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
+{
+    x = max(x, (uint32_t)dpp_i32<0xB1, 0xf, false>((int)x, 0));
+    x = max(x, (uint32_t)dpp_i32<0x4E, 0xf, false>((int)x, 0));
+    x = max(x, (uint32_t)dpp_i32<0x141, 0xf, false>((int)x, 0));
+    x = max(x, (uint32_t)dpp_i32<0x140, 0xf, false>((int)x, 0));
+    x = max(x, (uint32_t)dpp_i32<0x142, 0xa, false>((int)x, 0));
+    x = max(x, (uint32_t)dpp_i32<0x143, 0xc, false>((int)x, 0));
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
 // exclusive prefix sum of v over the 256 threads (and the total), two barriers
 __device__ __forceinline__ int block_exclusive_scan(int v, int *wave_tot, int &total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int up = __shfl_up(inc, o);
-        if (lane >= o) inc += up;
-    }
+    const int inc = wave_inclusive_scan(v);
     __syncthreads();   // wave_tot may still be read from a previous call
     if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
@@ -275,11 +308,8 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
         // they differ are common to all keys and need no pass.  Starting the digits right
         // there also spreads the first histogram over its bins (the leading bits of scores
         // of similar magnitude are all alike, and LDS atomics on one address serialise).
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
-            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
-        }
+        kmin = wave_min_u32(kmin);
+        kmax = wave_max_u32(kmax);
         if (lane == 0) { wave_min[wave] = kmin; wave_max_[wave] = kmax; }
         __syncthreads();
         kmin = min(min(wave_min[0], wave_min[1]), min(wave_min[2], wave_min[3]));
@@ -300,13 +330,11 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
             if (wave == 0) {
                 // lane l owns digits 4l .. 4l+3; suf[x] = number of matching keys with digit >= 4l + x
                 const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-                uint32_t inc = h0 + h1 + h2 + h3;         // becomes the sum over lanes >= l
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const uint32_t dn = __shfl_down(inc, o);
-                    if (lane + o < 64) inc += dn;
-                }
-                const uint32_t higher = inc - (h0 + h1 + h2 + h3);   // keys with digit >= 4l + 4
+                // sum over the lanes above l = total - inclusive prefix of l
+                const uint32_t mine = h0 + h1 + h2 + h3;
+                const uint32_t pre = (uint32_t)wave_inclusive_scan((int)mine);
+                const uint32_t all_keys = (uint32_t)__builtin_amdgcn_readlane((int)pre, 63);
+                const uint32_t higher = all_keys - pre;              // keys with digit >= 4l + 4
                 const uint32_t suf[5] = {higher + h3 + h2 + h1 + h0, higher + h3 + h2 + h1, higher + h3 + h2, higher + h3, higher};
 #pragma unroll
                 for (int x = 0; x < 4; ++x)
