@@ -18,8 +18,8 @@
 //                     lane holds 16 tokens of ONE query row: max, sum and rescale
 //                     are lane-local (one exchange with lane ^ 32);
 //   O^T += V^T . P^T  the S^T accumulator, converted to bf16, already has the
-//                     B-operand layout; V is read as 4 channels x 8 tokens per
-//                     lane and transposed in registers with byte permutes.
+//                     B-operand layout; V comes out of LDS transposed (8 tokens
+//                     of one channel per lane) through ds_read_b64_tr_b16.
 // The contraction index may be permuted freely as long as both operands agree,
 // which is what makes the register layouts line up.
 //
@@ -46,13 +46,14 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 
 constexpr int kOPitch = 132;         // floats per staged output row (128 + 4: conflict-free 16-byte writes)
-constexpr int kStageBytes = 16384;   // one 32-token chunk: 8 KiB of K + 8 KiB of V
+// One 32-token chunk in LDS: 8 KiB of K (row-major, 16-byte pieces XOR-swizzled by row & 7) and
+// the V rows in 8 pieces of 4 rows (tokens i, i+8, i+16, i+24 in piece i), 1088 bytes apart, for
+// the transposing LDS reads (see lds_read_v).
+constexpr int kVPiecePitch = 1088;
+constexpr int kStageBytes = 8192 + 8 * kVPiecePitch;
 constexpr int kStages = 2;           // ring depth per wavefront
 constexpr int kRingBytes = 4 * kStages * kStageBytes;
-// The wide kernel stores the V rows of a chunk in 8 pieces of 4 rows (tokens i, i+8, i+16,
-// i+24 in piece i), 1088 bytes apart, for its transposing LDS reads (see there).
-constexpr int kVPiecePitch = 1088;
-constexpr int kWideStageBytes = 8192 + 8 * kVPiecePitch;
+constexpr int kWideStageBytes = kStageBytes;
 constexpr float kRescaleSlack = 8.f; // the reference max may lag the true max by 2^8
 
 // Exact n / d for 0 <= n < 2^31 with a host-prepared multiplier (no integer divide
@@ -82,10 +83,6 @@ struct MfmaArgs {
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &u) { return __builtin_bit_cast(bf16x8, u); }
-
-// lo16(a) | lo16(b) << 16   and   hi16(a) | hi16(b) << 16
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
 {
@@ -138,26 +135,34 @@ __device__ __forceinline__ void lds_read_k(const uint32_t (&a)[8], uint4 (&k)[8]
         : "memory");
 }
 
-// V rows (e>>2)*8 + (e&3) [+4 for the upper half-wave, folded into addr] of both k-steps.
+// V operands (A operand of O^T += V^T . P^T: per lane 8 tokens of ONE channel) through the
+// transposing LDS read ds_read_b64_tr_b16.  Inside a group of 16 lanes, lane s reads 8 bytes
+// (4 channels) and receives, as lane 4a + c, element c of what lanes a, a+4, a+8, a+12 read.
+// With lane s reading token (s >> 2) of a token quad and channels 4 * (s & 3) .. +3 of a
+// 16-channel group, every lane ends up with the four tokens of the quad for channel
+// (lane & 15) of the group: lane m = lane & 31 holds channel 32j + m of tile j, its k-group the
+// tokens 16*ks2 + 8*hf + 4*kg + 0..3.  The four rows of a quad sit in four different V pieces,
+// 1088 bytes apart, i.e. 64 bytes apart modulo the bank cycle: no bank conflicts.
+// v[(ks2 * 4 + j) * 2 + hf]; addr = piece (4*kg + (s >> 2)), byte 32 * (group & 1) + 8 * (s & 3).
 __device__ __forceinline__ void lds_read_v(uint32_t addr, uint2 (&v)[16])
 {
     asm volatile(
-        "ds_read_b64 %0, %16 offset:0\n\t"
-        "ds_read_b64 %1, %16 offset:256\n\t"
-        "ds_read_b64 %2, %16 offset:512\n\t"
-        "ds_read_b64 %3, %16 offset:768\n\t"
-        "ds_read_b64 %4, %16 offset:2048\n\t"
-        "ds_read_b64 %5, %16 offset:2304\n\t"
-        "ds_read_b64 %6, %16 offset:2560\n\t"
-        "ds_read_b64 %7, %16 offset:2816\n\t"
-        "ds_read_b64 %8, %16 offset:4096\n\t"
-        "ds_read_b64 %9, %16 offset:4352\n\t"
-        "ds_read_b64 %10, %16 offset:4608\n\t"
-        "ds_read_b64 %11, %16 offset:4864\n\t"
-        "ds_read_b64 %12, %16 offset:6144\n\t"
-        "ds_read_b64 %13, %16 offset:6400\n\t"
-        "ds_read_b64 %14, %16 offset:6656\n\t"
-        "ds_read_b64 %15, %16 offset:6912\n\t"
+        "ds_read_b64_tr_b16 %0, %16 offset:0\n\t"
+        "ds_read_b64_tr_b16 %1, %16 offset:256\n\t"
+        "ds_read_b64_tr_b16 %2, %16 offset:64\n\t"
+        "ds_read_b64_tr_b16 %3, %16 offset:320\n\t"
+        "ds_read_b64_tr_b16 %4, %16 offset:128\n\t"
+        "ds_read_b64_tr_b16 %5, %16 offset:384\n\t"
+        "ds_read_b64_tr_b16 %6, %16 offset:192\n\t"
+        "ds_read_b64_tr_b16 %7, %16 offset:448\n\t"
+        "ds_read_b64_tr_b16 %8, %16 offset:512\n\t"
+        "ds_read_b64_tr_b16 %9, %16 offset:768\n\t"
+        "ds_read_b64_tr_b16 %10, %16 offset:576\n\t"
+        "ds_read_b64_tr_b16 %11, %16 offset:832\n\t"
+        "ds_read_b64_tr_b16 %12, %16 offset:640\n\t"
+        "ds_read_b64_tr_b16 %13, %16 offset:896\n\t"
+        "ds_read_b64_tr_b16 %14, %16 offset:704\n\t"
+        "ds_read_b64_tr_b16 %15, %16 offset:960\n\t"
         "s_waitcnt lgkmcnt(0)"
         : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]),
           "=&v"(v[8]), "=&v"(v[9]), "=&v"(v[10]), "=&v"(v[11]), "=&v"(v[12]), "=&v"(v[13]), "=&v"(v[14]), "=&v"(v[15])
@@ -270,7 +275,8 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
         kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u)));
-    const uint32_t vread = ring_addr + 8192u + (uint32_t)kg * 1024u + (uint32_t)n * 8u;  // + stage*16384 + row*256
+    const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
+                           32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
 
     // ---- chunk -> token rows ------------------------------------------------------------
     // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive
@@ -307,8 +313,9 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 
     uint32_t vmask_st[kStages];   // validity bits of the chunk this wavefront last requested rows for, per stage
 
-    // Request this wavefront's half of chunk ci (K rows if rb == 0, V rows if rb == 1): 8 DMA
-    // operations, operation i brings rows 4i .. 4i+3, one 256-byte row per 16 lanes.
+    // Request this wavefront's half of chunk ci: 8 DMA operations of 1 KiB (one 256-byte row per
+    // 16 lanes).  rb == 0: the K rows, operation i brings rows 4i .. 4i+3, pieces swizzled by
+    // row & 7.  rb == 1: the V rows, operation i brings rows i, i+8, i+16, i+24 into piece i.
     auto issue = [&](int ci) {
         const int stg = ci & (kStages - 1);
         int tok;
@@ -322,31 +329,48 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
         vmask_st[stg] = vm;
         const int r4 = lane >> 4, pos = lane & 15;
-        // K pieces are swizzled (piece pos ^ (row & 7)), V pieces are not
-        const uint32_t sw_even = rb == 0 ? 16u * (uint32_t)(pos ^ r4) : 16u * (uint32_t)pos;
-        const uint32_t sw_odd = rb == 0 ? (sw_even ^ 64u) : sw_even;
-        const char *base = rb == 0 ? kb : vb;
-        char *dst = my_ring + stg * kStageBytes + rb * 8192;
+        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+        char *dst = my_ring + stg * kStageBytes;
+        char *dstv = dst + 8192;
         if (ALIGNED && vm == 0xffffffffu) {
             const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
-            const char *src = base + (size_t)t0 * st2;
+            const size_t row0 = (size_t)t0 * st2;
             const uint32_t lane_row_off = (uint32_t)r4 * st2;
             if (st2 == 256u) {
-                // rows are 256 bytes apart (the usual head-major cache): four consecutive
-                // operations differ by 1 KiB on both sides, which the instruction's immediate
-                // offset covers, so they share one base address and one LDS base
-                dma16x4(src, lane_row_off + sw_even, lane_row_off + sw_odd, dst);
-                dma16x4(src + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
+                // rows are 256 bytes apart (the usual head-major cache): the instruction's
+                // immediate offset, added to the global and to the LDS address, covers the step
+                // between consecutive operations (K: 1 KiB on both sides; V: 256 bytes, with the
+                // LDS base adjusted for the rest of the piece pitch)
+                if (rb == 0) {
+                    dma16x4(kb + row0, lane_row_off + sw_even, lane_row_off + sw_odd, dst);
+                    dma16x4(kb + row0 + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
+                } else {
+                    const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
+#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, 0)
+                    SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
+                    SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
+#undef SPECPV_VOP
+                }
+            } else if (rb == 0) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
             } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    dma16(src + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+                    dma16(vb + row0 + (size_t)(8 * r4 + i) * st2 + vsw, dstv + i * kVPiecePitch);
+            }
+        } else if (rb == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
+                dma16(kb + (tv + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4);
-                dma16(base + (tv * st2 + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * st2;
+                dma16(vb + (tv + vsw), dstv + i * kVPiecePitch);
             }
         }
     };
@@ -440,18 +464,13 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         l_run += lsum;
         const uint4 pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]), pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
 #pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-            // 8 tokens x 4 channels  ->  4 channels x 8 tokens
-            const uint2 *w = v + 8 * ks2;
-            uint4 vt[4];
-            vt[0] = make_uint4(pack_lo(w[0].x, w[1].x), pack_lo(w[2].x, w[3].x), pack_lo(w[4].x, w[5].x), pack_lo(w[6].x, w[7].x));
-            vt[1] = make_uint4(pack_hi(w[0].x, w[1].x), pack_hi(w[2].x, w[3].x), pack_hi(w[4].x, w[5].x), pack_hi(w[6].x, w[7].x));
-            vt[2] = make_uint4(pack_lo(w[0].y, w[1].y), pack_lo(w[2].y, w[3].y), pack_lo(w[4].y, w[5].y), pack_lo(w[6].y, w[7].y));
-            vt[3] = make_uint4(pack_hi(w[0].y, w[1].y), pack_hi(w[2].y, w[3].y), pack_hi(w[4].y, w[5].y), pack_hi(w[6].y, w[7].y));
+        for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[j]), as_bf16x8(ks2 ? pf1 : pf0), O[j], 0, 0, 0);
-        }
+            for (int j = 0; j < 4; ++j) {
+                const uint2 lo = v[(ks2 * 4 + j) * 2], hi = v[(ks2 * 4 + j) * 2 + 1];
+                O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)),
+                                                               as_bf16x8(ks2 ? pf1 : pf0), O[j], 0, 0, 0);
+            }
     }
     __syncthreads();   // every wavefront is done with the rings: the epilogue reuses that LDS
 
@@ -463,12 +482,13 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
             ms[tg * 64 + row] = m_ref;
             ls[tg * 64 + row] = l_run;
         }
+        // accumulator element 4q + x of tile j is channel 32j + 8q + 4kg + x of this lane's row
         float *dst = obuf + ((size_t)tg * 64 + row) * kOPitch;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int mi = (i >> 2) * 8 + kg * 4 + (i & 3);
-            *(float4 *)(dst + 4 * mi) = make_float4(O[0][i], O[1][i], O[2][i], O[3][i]);
-        }
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) = make_float4(O[j][4 * q], O[j][4 * q + 1], O[j][4 * q + 2], O[j][4 * q + 3]);
     }
     __syncthreads();
     constexpr int RPW = 8;  // rows each wavefront finishes
