@@ -87,39 +87,57 @@ static Shape make_shape(const specpv_kv *kv, const specpv_tree *tree)
     return s;
 }
 
-// How many KV splits the context part of the attention uses when it covers
-// n_blocks blocks per (sequence, KV head).  Host-only and deterministic in its
+// Which kernel the context part of the attention runs on and how many KV splits it uses when
+// it covers n_blocks blocks per (sequence, KV head).  Host-only and deterministic in its
 // arguments, so specpv_workspace_bytes and the calls agree.
-static int plan_splits(const Shape &s, int dtype, int64_t n_blocks)
+static AttnPlan plan_attention(const Shape &s, int dtype, int64_t n_blocks)
 {
+    AttnPlan plan{1, attn_ctx_mfma_supported(s, dtype) ? kAttnSplit : kAttnGeneric};
     const int64_t tokens = n_blocks * s.B;
-    if (tokens <= 0) return 1;
-    int64_t ns;
-    if (attn_ctx_mfma_supported(s, dtype)) {
-        // one workgroup (4 wavefronts, one 32-token chunk at a time each) per
-        // (sequence, query head, 64-node row tile, split); one workgroup per CU
-        const int64_t base = (int64_t)s.batch * s.Hq * ((s.M + 63) / 64);
-        const int64_t chunks = (tokens + 31) / 32;
+    if (tokens <= 0) return plan;
+    if (plan.kind != kAttnGeneric) {
+        const int64_t chunks = (tokens + 31) / 32;   // 32-token chunks per (sequence, KV head)
         const int64_t cus = device_cu_count();
-        const int64_t max_ns = chunks / 4 > 1 ? (chunks / 4 < 64 ? chunks / 4 : 64) : 1;
-        int64_t best = 1, best_cost = -1;
-        for (int64_t c = 1; c <= max_ns; ++c) {
-            const int64_t rounds = (base * c + cus - 1) / cus;
-            const int64_t per_wave = (chunks + 4 * c - 1) / (4 * c);
-            // chunk-times on the critical path, plus a charge for the epilogue and the partials
-            const int64_t cost = rounds * (per_wave * 8 + 10) + c;
-            if (best_cost < 0 || cost < best_cost) { best = c; best_cost = cost; }
+        const int64_t row_tiles = (s.M + 63) / 64;
+        // splits c that minimise the chunk-times on the critical path (one workgroup per CU, `base`
+        // workgroups per split, `ranges` token ranges per workgroup), plus a charge for the
+        // epilogue and the partials
+        auto best_splits = [&](int64_t base, int64_t ranges, int64_t max_ns) {
+            int64_t best = 1, best_cost = -1;
+            for (int64_t c = 1; c <= max_ns; ++c) {
+                const int64_t rounds = (base * c + cus - 1) / cus;
+                const int64_t per_wave = (chunks + ranges * c - 1) / (ranges * c);
+                const int64_t cost = rounds * (per_wave * 8 + 10) + c;
+                if (best_cost < 0 || cost < best_cost) { best = c; best_cost = cost; }
+            }
+            return best;
+        };
+        // a workgroup per (sequence, query head, 64-node row tile, split), four token ranges each
+        const int64_t max4 = chunks / 4 > 1 ? (chunks / 4 < 64 ? chunks / 4 : 64) : 1;
+        int64_t ns = best_splits((int64_t)s.batch * s.Hq * row_tiles, 4, max4);
+        // Long token ranges per wavefront amortise the longer prologue and epilogue of the kernels
+        // with more rows per wavefront; at a handful of chunks the eight-wavefront kernel hides
+        // latency better.
+        if (chunks >= 8 * 4 * ns) {
+            plan.kind = kAttnWide;
+            if (s.G == 4) {
+                // a workgroup per (sequence, KV head, row tile, split), one token range each
+                plan.kind = kAttnGroup;
+                const int64_t max1 = chunks / 8 > 1 ? (chunks / 8 < 64 ? chunks / 8 : 64) : 1;
+                ns = best_splits((int64_t)s.batch * s.Hkv * row_tiles, 1, max1);
+            }
         }
-        ns = best;
+        plan.nsplit = (int)ns;
     } else {
         const int64_t rows = (int64_t)s.batch * s.Hq * s.M;
         const int64_t chunks = (tokens + 63) / 64;
-        ns = (4096 + rows - 1) / rows;
+        int64_t ns = (4096 + rows - 1) / rows;
         if (ns > chunks) ns = chunks;
         if (ns > 64) ns = 64;
         if (ns < 1) ns = 1;
+        plan.nsplit = (int)ns;
     }
-    return (int)ns;
+    return plan;
 }
 
 struct Workspace {
@@ -145,12 +163,13 @@ static int run_attention(const Shape &s, int dtype, const int32_t *sel_idx, cons
                          int n_sel, void *out, float *lse, void *workspace, size_t workspace_bytes,
                          hipStream_t st)
 {
-    const int nsplit = plan_splits(s, dtype, sel_idx ? n_sel : s.max_blocks);
+    const AttnPlan plan = plan_attention(s, dtype, sel_idx ? n_sel : s.max_blocks);
+    const int nsplit = plan.nsplit;
     const Workspace w = layout_workspace(s, nsplit, workspace);
     if (!workspace || workspace_bytes < w.total) return SPECPV_EWORKSPACE;
     Partials p{w.part_o, w.part_ml, nsplit};
     hipError_t e;
-    if (attn_ctx_mfma_supported(s, dtype)) e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, st);
+    if (plan.kind != kAttnGeneric) e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, plan.kind, st);
     else e = launch_attn_ctx_generic(s, dtype, sel_idx, sel_count, n_sel, p, st);
     if (e != hipSuccess) return fail_hip(e);
     e = launch_combine(s, dtype, p, out, lse, st);
@@ -181,10 +200,10 @@ size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, cons
     if (!tree) { const size_t n = align_up((size_t)kv->batch * sizeof(int32_t)); return n > 256 ? n : 256; }
     if (check_tree(kv, tree, false) != SPECPV_OK) return 0;
     const Shape s = make_shape(kv, tree);
-    int nsplit = plan_splits(s, kv->dtype, s.max_blocks);
+    int nsplit = plan_attention(s, kv->dtype, s.max_blocks).nsplit;
     if (cfg) {
         const int64_t n_sel = (int64_t)cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks;
-        const int n2 = plan_splits(s, kv->dtype, n_sel);
+        const int n2 = plan_attention(s, kv->dtype, n_sel).nsplit;
         if (n2 > nsplit) nsplit = n2;
     }
     return layout_workspace(s, nsplit, nullptr).total;
@@ -248,7 +267,7 @@ int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree, voi
     if (!kmax || !kmin || !out || !sel_idx || !sel_count) return SPECPV_EINVAL;
     if (((uintptr_t)kmax | (uintptr_t)kmin | (uintptr_t)out) & 15) return SPECPV_EINVAL;
     const Shape s = make_shape(kv, tree);
-    const int nsplit = plan_splits(s, kv->dtype, s.max_blocks);
+    const int nsplit = plan_attention(s, kv->dtype, s.max_blocks).nsplit;
     const Workspace w = layout_workspace(s, nsplit, workspace);
     if (!workspace || workspace_bytes < w.total) return SPECPV_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;

@@ -135,6 +135,25 @@ __device__ __forceinline__ void lds_read_k(const uint32_t (&a)[8], uint4 (&k)[8]
         : "memory");
 }
 
+// The same with four address registers: the operand piece of k-step ks + 4 lies 128 bytes
+// behind that of k-step ks (the swizzle only touches the address bits below).
+__device__ __forceinline__ void lds_read_k4(const uint32_t (&a)[4], uint4 (&k)[8])
+{
+    asm volatile(
+        "ds_read_b128 %0, %8\n\t"
+        "ds_read_b128 %1, %9\n\t"
+        "ds_read_b128 %2, %10\n\t"
+        "ds_read_b128 %3, %11\n\t"
+        "ds_read_b128 %4, %8 offset:128\n\t"
+        "ds_read_b128 %5, %9 offset:128\n\t"
+        "ds_read_b128 %6, %10 offset:128\n\t"
+        "ds_read_b128 %7, %11 offset:128\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2]), "=&v"(k[3]), "=&v"(k[4]), "=&v"(k[5]), "=&v"(k[6]), "=&v"(k[7])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3])
+        : "memory");
+}
+
 // V operands (A operand of O^T += V^T . P^T: per lane 8 tokens of ONE channel) through the
 // transposing LDS read ds_read_b64_tr_b16.  Inside a group of 16 lanes, lane s reads 8 bytes
 // (4 channels) and receives, as lane 4a + c, element c of what lanes a, a+4, a+8, a+12 read.
@@ -784,6 +803,16 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
             f.v[e] = __builtin_bit_cast(uint2, t);
         }
     };
+    // every register of f has arrived (the compiler places the wait); nothing is emitted
+    auto settle = [&](const Frags &f) {
+#define SPECPV_K(i) "v"(__builtin_bit_cast(u32x4, f.k[i]))
+#define SPECPV_V(i) "v"(__builtin_bit_cast(u32x2, f.v[i]))
+        asm volatile("" ::SPECPV_K(0), SPECPV_K(1), SPECPV_K(2), SPECPV_K(3), SPECPV_K(4), SPECPV_K(5), SPECPV_K(6), SPECPV_K(7));
+        asm volatile("" ::SPECPV_V(0), SPECPV_V(1), SPECPV_V(2), SPECPV_V(3), SPECPV_V(4), SPECPV_V(5), SPECPV_V(6), SPECPV_V(7),
+                     SPECPV_V(8), SPECPV_V(9), SPECPV_V(10), SPECPV_V(11), SPECPV_V(12), SPECPV_V(13), SPECPV_V(14), SPECPV_V(15));
+#undef SPECPV_K
+#undef SPECPV_V
+    };
     // The arithmetic of one chunk for both 32-row blocks.
     auto compute = [&](const Frags &f) {
         // V^T operands: channels 32j + (lane & 31), tokens as above
@@ -847,43 +876,16 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
                     O[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[ks2][j]), as_bf16x8(ks2 ? pf1 : pf0), O[rb][j], 0, 0, 0);
         }
     };
-    // every register of f has arrived (the compiler places the wait); nothing is emitted
-    auto settle = [&](const Frags &f) {
-#define SPECPV_K(i) "v"(__builtin_bit_cast(u32x4, f.k[i]))
-#define SPECPV_V(i) "v"(__builtin_bit_cast(u32x2, f.v[i]))
-        asm volatile("" ::SPECPV_K(0), SPECPV_K(1), SPECPV_K(2), SPECPV_K(3), SPECPV_K(4), SPECPV_K(5), SPECPV_K(6), SPECPV_K(7));
-        asm volatile("" ::SPECPV_V(0), SPECPV_V(1), SPECPV_V(2), SPECPV_V(3), SPECPV_V(4), SPECPV_V(5), SPECPV_V(6), SPECPV_V(7),
-                     SPECPV_V(8), SPECPV_V(9), SPECPV_V(10), SPECPV_V(11), SPECPV_V(12), SPECPV_V(13), SPECPV_V(14), SPECPV_V(15));
-#undef SPECPV_K
-#undef SPECPV_V
-    };
-    // One pipeline step: `cur` holds chunk i.  The fragments of chunk i + 1 are requested from
-    // LDS first and arrive while chunk i is being computed; chunk i + 2 is requested from
-    // memory into the stage that chunk i has left.
-    auto step = [&](int i, Frags &cur, Frags &nxt) {
-        if (i + 1 < nch) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // chunk i + 1 has landed (nothing younger is in flight)
-            read_frags(i + 1, nxt);
-        }
-        if (i + 2 < nch) {
-            settle(cur);      // the LDS reads of chunk i are complete: its stage may be overwritten
-            issue(i + 2);
-        }
-        compute(cur);
-    };
-
     if (nch > 0) issue(0);
     if (nch > 1) issue(1);
     {
-        Frags fa, fb;
-        if (nch > 0) {
-            if (nch > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        Frags fa;
+        for (int i = 0; i < nch; ++i) {
+            if (i + 1 < nch) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            read_frags(0, fa);
-        }
-        for (int i = 0; i < nch; i += 2) {
-            step(i, fa, fb);
-            if (i + 1 < nch) step(i + 1, fb, fa);
+            read_frags(i, fa);
+            if (i + 2 < nch) { settle(fa); issue(i + 2); }
+            compute(fa);
         }
     }
     __syncthreads();   // every wavefront is done with its ring: the epilogue reuses that LDS
@@ -949,6 +951,310 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
     }
 }
 
+// ---- group variant: the four query heads of a KV head in one workgroup ----------------------
+// For long token ranges and G = 4.  A workgroup owns (sequence, KV head, 64-node row tile, KV
+// split) and walks the split's chunks once for all four query heads: wavefront w takes head
+// (w & 3) and rows 32 * (w >> 2) .. +31 of the tile.  The eight wavefronts share ONE ring of
+// four stages; each brings 2 of a chunk's 16 DMA operations (first four wavefronts: K rows,
+// last four: V rows), so every K / V byte is requested from memory exactly once per row tile,
+// whatever the caches do.  Chunks are requested three ahead of the arithmetic (measured: two is
+// slightly slower, four and six are no faster).  One workgroup barrier per chunk: past the
+// barrier of chunk i every part of chunk i has landed, and every wavefront has finished reading
+// chunk i - 1, whose stage is the one that chunk i + 3 is then requested into.
+// A wavefront keeps its rows to itself over the whole split, so the epilogue has nothing to
+// merge: it only turns the accumulators into row-major partials.
+constexpr int kGroupStages = 4;   // a power of two
+constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
+
+template <bool ALIGNED>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
+{
+    extern __shared__ char lds_raw[];
+    char *ring = lds_raw;                  // [kGroupStages][K 8 KiB | V 8 pieces of 1088 B]
+    float *obuf = (float *)lds_raw;        // [8 wavefronts][32 rows][kOPitch], reuses the ring after the main loop
+
+    const int xcd = blockIdx.x & 7, rt = blockIdx.x >> 3;
+    const int u = blockIdx.y * 8 + xcd;
+    if (u >= a.n_units) return;
+    const int bg = (int)a.div_nsplit.div((uint32_t)u);
+    const int sp = u - bg * part.nsplit;
+    const int b = (int)a.div_hkv.div((uint32_t)bg);
+    const int g = bg - b * s.Hkv;
+    const int m0 = rt * 64;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hh = wave & 3, rb = wave >> 2;
+    const int h = g * 4 + hh;                 // the host only launches this kernel for G == 4
+    const int n = lane & 31, kg = lane >> 5;
+
+    const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
+    const int W = part.nsplit;                // div_W divides by the number of splits here
+    const uint32_t Bu = (uint32_t)s.B;
+    const int L = s.ctx_len[b];
+    const int cnt_raw = sel ? a.sel_count[bg] : 0;
+    auto first_chunk = [&](uint32_t chunks, int w) -> int {
+        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
+        return (int)((uint32_t)w * base + min((uint32_t)w, rem));
+    };
+    int spec_slot = 0, spec_vec = 0;
+    if (ALIGNED && sel) {
+        const uint32_t Cspec = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
+        spec_slot = (int)a.div_B.div((uint32_t)first_chunk(Cspec, sp) * 32u);
+        const int x = spec_slot + lane;
+        spec_vec = x < a.n_sel ? sel[x] : -1;
+    }
+    uint4 qraw[8];
+    {
+        const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
+        const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qraw[ks] = *(const uint4 *)(qrow + ks * 16);
+    }
+
+    int nb = L > 0 ? (int)a.div_B.div((uint32_t)(L + s.B - 1)) : 0;
+    if (nb > s.max_blocks) nb = s.max_blocks;
+    int cnt = nb;
+    if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
+    const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;
+    const uint32_t C = (T + 31u) >> 5;
+    const int c0 = first_chunk(C, sp), c1 = first_chunk(C, sp + 1);
+    const int nch = c1 - c0;                  // the same for all eight wavefronts: the barriers match up
+
+    const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
+    const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
+    const uint32_t st2 = (uint32_t)s.st * 2u;
+
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ring;
+    uint32_t kread[4];   // + stage * kStageBytes; k-step ks + 4 is 128 bytes behind k-step ks
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+        kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u)));
+    const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
+                           32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
+
+    int slot_base = 0, blkvec = 0;
+    auto refill = [&](int slot) {
+        slot_base = slot;
+        const int x = slot + lane;
+        blkvec = (sel && x < cnt) ? sel[x] : x;
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): inside the rare branch, see attn_ctx_mfma_kernel
+    };
+    auto chunk_row0 = [&](int ci) -> int {
+        const uint32_t p0 = (uint32_t)(c0 + ci) * 32u;
+        const uint32_t slot = a.div_B.div(p0);
+        if ((int)slot - slot_base >= 64) refill((int)slot);
+        const int blk = __builtin_amdgcn_readlane(blkvec, (int)slot - slot_base);
+        if (blk < 0 || blk >= nb) return -1;
+        return blk * s.B + (int)(p0 - slot * Bu);
+    };
+    auto lane_row = [&](int ci) -> int {
+        const uint32_t p = (uint32_t)(c0 + ci) * 32u + (uint32_t)n;
+        if (p >= T) return -1;
+        const uint32_t slot = a.div_B.div(p);
+        const int blk = sel ? sel[slot] : (int)slot;
+        if (blk < 0 || blk >= nb) return -1;
+        const int tok = blk * s.B + (int)(p - slot * Bu);
+        return tok < L ? tok : -1;
+    };
+
+    // Request this wavefront's two operations of chunk ci into stage stg (1 KiB each, one 256-byte
+    // row per 16 lanes).  rb == 0: K operations i0, i0 + 1 (operation i brings rows 4i .. 4i+3,
+    // pieces swizzled by row & 7); rb == 1: V operations i0, i0 + 1 (operation i brings rows i,
+    // i+8, i+16, i+24 into piece i).  Returns the validity bits of the chunk's 32 tokens.
+    const int i0 = 2 * hh;
+    auto issue = [&](int ci, int stg) -> uint32_t {
+        int tok;
+        if (ALIGNED) {
+            const int r0 = chunk_row0(ci);
+            tok = (r0 >= 0 && r0 + n < L) ? r0 + n : -1;
+        } else {
+            tok = lane_row(ci);
+        }
+        const uint32_t vm = (uint32_t)__ballot(tok >= 0);
+        const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
+        const int r4 = lane >> 4, pos = lane & 15;
+        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+        char *dst = ring + stg * kStageBytes;
+        char *dstk = dst + i0 * 1024;
+        char *dstv = dst + 8192 + i0 * kVPiecePitch;
+        if (ALIGNED && vm == 0xffffffffu) {
+            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
+            const size_t row0 = (size_t)t0 * st2;
+            const uint32_t lane_row_off = (uint32_t)r4 * st2;
+            if (rb == 0) {
+                // i0 is even: operation i0 takes the even swizzle, i0 + 1 the odd one
+                const char *ksrc = kb + row0 + (size_t)(4 * i0) * st2;
+                if (st2 == 256u) {
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + (lane_row_off + sw_even)), (lds_void_ptr)dstk, 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + (lane_row_off + sw_odd)), (lds_void_ptr)dstk, 16, 1024, 0);
+                } else {
+                    dma16(ksrc + (lane_row_off + sw_even), dstk);
+                    dma16(ksrc + (size_t)4 * st2 + (lane_row_off + sw_odd), dstk + 1024);
+                }
+            } else {
+                const char *vsrc = vb + row0 + (size_t)(8 * r4 + i0) * st2 + vsw;
+                if (st2 == 256u) {
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)dstv, 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (kVPiecePitch - 256)), 16, 256, 0);
+                } else {
+                    dma16(vsrc, dstv);
+                    dma16(vsrc + st2, dstv + kVPiecePitch);
+                }
+            }
+        } else if (rb == 0) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * (i0 + t) + r4) * st2;
+                dma16(kb + (tv + (t ? sw_odd : sw_even)), dstk + t * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i0 + t) * st2;
+                dma16(vb + (tv + vsw), dstv + t * kVPiecePitch);
+            }
+        }
+        return vm;
+    };
+
+    bf16x8 qf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
+    if (ALIGNED && nch > 0) {
+        const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
+        if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }
+        else refill(slot0);
+    }
+    // from here on only this wavefront's DMA groups (2 operations each) are in flight (an
+    // instruction the compiler knows, see attn_ctx_mfma_kernel)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+
+    f32x16 O[4];
+    float m_ref = -INFINITY, l_run = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[j][i] = 0.f;
+
+    // validity bits of the chunks in the ring: lane t holds those of stage t
+    uint32_t vmv = 0u;
+    for (int c = 0; c < kGroupAhead && c < nch; ++c) {
+        const uint32_t vm = issue(c, c);
+        vmv = lane == c ? vm : vmv;
+    }
+    // The barrier puts all eight wavefronts at the same point once per chunk; if they then all did
+    // the same thing, they would queue for the LDS, then for the matrix cores, then for the vector
+    // ALU.  So the two wavefronts of a SIMD (w and w + 4) run half a chunk apart: the second one
+    // keeps P and V of its chunk in registers and does the O^T += V^T . P^T products after the next
+    // barrier, while the first one reads its operands from LDS.
+    uint2 v[16];
+    uint4 pf0 = make_uint4(0u, 0u, 0u, 0u), pf1 = pf0;
+    auto pv = [&]() {
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint2 lo = v[(ks2 * 4 + j) * 2], hi = v[(ks2 * 4 + j) * 2 + 1];
+                O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y)),
+                                                               as_bf16x8(ks2 ? pf1 : pf0), O[j], 0, 0, 0);
+            }
+    };
+    for (int i = 0; i < nch; ++i) {
+        // own part of chunk i has landed: kGroupAhead - 1 younger groups of 2 operations may stay
+        // in flight (towards the end of the range there are fewer: wait for all, they are due anyway)
+        if (i + kGroupAhead - 1 < nch) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (kGroupAhead - 1)) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();   // ... and so have the other seven; chunk i-1 has been read by all
+        if (i + kGroupAhead < nch) {
+            const int is = (i + kGroupAhead) & (kGroupStages - 1);
+            const uint32_t vm = issue(i + kGroupAhead, is);
+            vmv = lane == is ? vm : vmv;
+        }
+        const int rs = i & (kGroupStages - 1);
+        const uint32_t vmask = (uint32_t)__builtin_amdgcn_readlane((int)vmv, rs);
+        if (rb == 1 && i > 0) pv();   // chunk i - 1, before its V registers are overwritten
+        uint4 kf[8];
+        {
+            const uint32_t soff = (uint32_t)rs * kStageBytes;
+            const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
+            lds_read_k4(ka, kf);
+            lds_read_v(vread + soff, v);
+        }
+
+        f32x16 S;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) S[x] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[ks], S, 0, 0, 0);
+
+        if (vmask != 0xffffffffu) {
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
+                if (!((vmask >> tt) & 1u)) S[x] = -INFINITY;
+            }
+        }
+        float mx = fmaxf(S[0], S[1]);
+#pragma unroll
+        for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, S[x]), S[x + 1]);
+        mx = max_xor32(mx) * a.scale_log2;
+        // the reference max only moves when the true max gets more than 2^slack ahead
+        if (__any(mx > m_ref + kRescaleSlack)) {
+            const float m_new = mx > m_ref + kRescaleSlack ? mx : m_ref;
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            l_run *= alpha;
+            if (__any(alpha != 1.f && l_run != 0.f)) {   // nothing to rescale while O is still zero
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) O[j][x] *= alpha;
+            }
+        }
+        const float m_use = m_ref == -INFINITY ? 0.f : m_ref;
+        uint32_t pk[8];
+        float lsum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; x += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(S[x], a.scale_log2, -m_use));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(S[x + 1], a.scale_log2, -m_use));
+            pk[x >> 1] = pack_bf16x2(p0, p1);
+            lsum = add_bf16x2(pk[x >> 1], lsum);   // the sum runs over the rounded weights the MFMA sees
+        }
+        l_run += lsum;
+        pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+        if (rb == 0) pv();
+    }
+    if (rb == 1 && nch > 0) pv();
+    __syncthreads();   // every wavefront is done with the ring: the epilogue reuses that LDS
+
+    // ---- one partial per (head, split, node): accumulators -> row-major through LDS ------
+    l_run = sum_xor32(l_run);
+    const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
+    {
+        // accumulator element 4q + x of tile j is channel 32j + 8q + 4kg + x of this lane's row
+        float *dst = obuf + ((size_t)wave * 32 + n) * kOPitch;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) = make_float4(O[j][4 * q], O[j][4 * q + 1], O[j][4 * q + 2], O[j][4 * q + 3]);
+    }
+    // a wavefront reads back only what it wrote itself: no barrier
+    const int jrow0 = m0 + rb * 32;
+#pragma unroll 8
+    for (int uu = 0; uu < 32; ++uu) {
+        const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
+        if (jrow0 + uu < s.M) *(float2 *)(part.o + (prow0 + jrow0 + uu) * 128 + 2 * lane) = x;
+    }
+    if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
+}
+
 bool attn_ctx_mfma_supported(const Shape &s, int dtype)
 {
     // per-lane byte offsets inside one (sequence, KV head) slab are kept in 32 bits
@@ -957,8 +1263,10 @@ bool attn_ctx_mfma_supported(const Shape &s, int dtype)
 }
 
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
-                                int n_sel, Partials p, hipStream_t st)
+                                int n_sel, Partials p, int kind, hipStream_t st)
 {
+    if (kind != kAttnSplit && kind != kAttnWide && kind != kAttnGroup) return hipErrorInvalidValue;
+    if (kind == kAttnGroup && s.G != 4) return hipErrorInvalidValue;
     MfmaArgs a;
     a.sel_idx = sel_idx;
     a.sel_count = sel_count;
@@ -969,44 +1277,35 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     a.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
     a.div_hkv = make_fastdiv((uint32_t)s.Hkv);
     a.div_B = make_fastdiv((uint32_t)s.B);
-    a.div_W = make_fastdiv((uint32_t)p.nsplit * 4u);
-    const int GR = s.G * a.row_tiles;
+    // token ranges per split: four (one per token group of a workgroup), or one in the group kernel
+    a.div_W = make_fastdiv((uint32_t)p.nsplit * (kind == kAttnGroup ? 1u : 4u));
+    const int GR = (kind == kAttnGroup ? 1 : s.G) * a.row_tiles;
     const dim3 grid(8 * GR, (a.n_units + 7) / 8);
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool aligned = s.B % 32 == 0;
-    const size_t lds = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
-#define SPECPV_LAUNCH(AL)                                                                              \
+    const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
+    const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, 8 * 32 * kOPitch * (int)sizeof(float));
+#define SPECPV_LAUNCH(KERN, THREADS, LDS)                                                              \
     do {                                                                                               \
         static bool attr_set = false;                                                                  \
-        auto kern = attn_ctx_mfma_kernel<AL>;                                                          \
+        auto kern = KERN;                                                                              \
         if (!attr_set) {                                                                               \
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(LDS)); \
             if (e != hipSuccess) return e;                                                             \
             attr_set = true;                                                                           \
         }                                                                                              \
-        hipLaunchKernelGGL(kern, grid, dim3(512), lds, st, s, p, a);                                    \
+        hipLaunchKernelGGL(kern, grid, dim3(THREADS), LDS, st, s, p, a);                                \
     } while (0)
-#define SPECPV_LAUNCH_WIDE(AL)                                                                         \
-    do {                                                                                               \
-        static bool attr_set = false;                                                                  \
-        auto kern = attn_ctx_mfma_wide_kernel<AL>;                                                     \
-        if (!attr_set) {                                                                               \
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-            if (e != hipSuccess) return e;                                                             \
-            attr_set = true;                                                                           \
-        }                                                                                              \
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, s, p, a);                                    \
-    } while (0)
-    // Long token ranges per wavefront amortise the wide variant's longer prologue and epilogue;
-    // at a handful of chunks the eight-wavefront kernel hides latency better.
-    const int64_t chunks = (((int64_t)(sel_idx ? n_sel : s.max_blocks)) * s.B + 31) / 32;
-    const bool wide = chunks >= (int64_t)8 * 4 * p.nsplit;
-    if (wide) {
-        if (aligned) SPECPV_LAUNCH_WIDE(true); else SPECPV_LAUNCH_WIDE(false);
+    if (kind == kAttnGroup) {
+        if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_group_kernel<true>, 512, lds_group);
+        else SPECPV_LAUNCH(attn_ctx_mfma_group_kernel<false>, 512, lds_group);
+    } else if (kind == kAttnWide) {
+        if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_wide_kernel<true>, 256, lds_split);
+        else SPECPV_LAUNCH(attn_ctx_mfma_wide_kernel<false>, 256, lds_split);
     } else {
-        if (aligned) SPECPV_LAUNCH(true); else SPECPV_LAUNCH(false);
+        if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_kernel<true>, 512, lds_split);
+        else SPECPV_LAUNCH(attn_ctx_mfma_kernel<false>, 512, lds_split);
     }
-#undef SPECPV_LAUNCH_WIDE
 #undef SPECPV_LAUNCH
     return hipGetLastError();
 }

@@ -116,15 +116,18 @@ def test_shapes_and_edges(gpu_lib, over, tag):
 
 
 @pytest.mark.parametrize("over,tag", [
-    (dict(ctx=[36000], B=64, M=100, tree="uniform"), "two row tiles, ragged tail"),
-    (dict(ctx=[33333, 40000], B=16, M=24, rho=[0.1, 0.1]), "block 16 (chunks cross blocks), batch of 2"),
+    (dict(ctx=[36000], B=64, M=100, tree="uniform"), "G=4, two row tiles, ragged tail"),
+    (dict(ctx=[33333, 40000], B=16, M=24, rho=[0.1, 0.1]), "G=4, block 16 (chunks cross blocks), batch of 2"),
+    (dict(ctx=[40960, 70], B=64, M=60, rho=[0.1, 0.1]), "G=4, batch with a short sequence (splits without tokens)"),
     (dict(ctx=[34816], B=64, M=30, Hq=10, Hkv=2), "G=5"),
+    (dict(ctx=[35000], B=16, M=70, Hq=10, Hkv=2, tree="uniform"), "G=5, two row tiles, block 16"),
     (dict(ctx=[40000], B=64, M=9, Hq=2, Hkv=2), "G=1"),
 ])
-def test_long_ranges_take_the_wide_kernel(gpu_lib, over, tag):
+def test_long_ranges_take_the_many_chunk_kernels(gpu_lib, over, tag):
     """Full verification over tens of thousands of tokens at small head counts: each wavefront
-    gets eight or more chunks, which selects the one-wavefront-per-SIMD kernel; head-major
-    (256-byte row stride: grouped DMA path) and token-major (general path) layouts."""
+    gets eight or more chunks, which selects the kernel with the four query heads of a KV head in
+    one workgroup (G = 4) or the one-wavefront-per-SIMD kernel (other G); head-major (256-byte
+    row stride: grouped DMA path) and token-major (general path) layouts."""
     say("case", tag)
     cfg = dict(SMALL); cfg.update(over)
     case = workloads.to_device(workloads.make_case(cfg, seed=17), "cuda")
