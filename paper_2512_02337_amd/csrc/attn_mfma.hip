@@ -998,13 +998,6 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
         return (int)((uint32_t)w * base + min((uint32_t)w, rem));
     };
-    int spec_slot = 0, spec_vec = 0;
-    if (ALIGNED && sel) {
-        const uint32_t Cspec = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
-        spec_slot = (int)a.div_B.div((uint32_t)first_chunk(Cspec, sp) * 32u);
-        const int x = spec_slot + lane;
-        spec_vec = x < a.n_sel ? sel[x] : -1;
-    }
     uint4 qraw[8];
     {
         const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
@@ -1034,21 +1027,32 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
                            32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
 
-    int slot_base = 0, blkvec = 0;
-    auto refill = [&](int slot) {
-        slot_base = slot;
-        const int x = slot + lane;
-        blkvec = (sel && x < cnt) ? sel[x] : x;
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): inside the rare branch, see attn_ctx_mfma_kernel
+    // ---- chunk -> token rows ------------------------------------------------------------
+    // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive.  The
+    // first rows of the next 64 chunks sit in a register (lane t: chunk row_base + t) and are
+    // picked with readlane.  Encoding: r >= 0: all 32 rows r .. r+31 are valid tokens (the common
+    // case, handled without any further test); -1: no valid token; -2 - r: rows from r on, cut
+    // off by the context length.
+    int row_base = 0, row0vec = -1;
+    auto fill_rows = [&](int cb) {
+        row_base = cb;
+        int r = -1;
+        if (cb + lane < nch) {
+            const uint32_t p0 = (uint32_t)(c0 + cb + lane) * 32u;   // < T: the slot below is < cnt
+            const uint32_t slot = a.div_B.div(p0);
+            const int blk = sel ? sel[slot] : (int)slot;
+            if (blk >= 0 && blk < nb) {
+                r = blk * s.B + (int)(p0 - slot * Bu);
+                if (r >= L) r = -1;
+                else if (r + 32 > L) r = -2 - r;
+            }
+        }
+        row0vec = r;
+        // wait for the list entries here, inside the rare branch, so that the common path that
+        // joins behind it carries no pending load (and no wait on the DMA prefetch)
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     };
-    auto chunk_row0 = [&](int ci) -> int {
-        const uint32_t p0 = (uint32_t)(c0 + ci) * 32u;
-        const uint32_t slot = a.div_B.div(p0);
-        if ((int)slot - slot_base >= 64) refill((int)slot);
-        const int blk = __builtin_amdgcn_readlane(blkvec, (int)slot - slot_base);
-        if (blk < 0 || blk >= nb) return -1;
-        return blk * s.B + (int)(p0 - slot * Bu);
-    };
+    // general case: this lane's token (t = lane & 31) of chunk ci, or -1
     auto lane_row = [&](int ci) -> int {
         const uint32_t p = (uint32_t)(c0 + ci) * 32u + (uint32_t)n;
         if (p >= T) return -1;
@@ -1063,70 +1067,51 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     // row per 16 lanes).  rb == 0: K operations i0, i0 + 1 (operation i brings rows 4i .. 4i+3,
     // pieces swizzled by row & 7); rb == 1: V operations i0, i0 + 1 (operation i brings rows i,
     // i+8, i+16, i+24 into piece i).  Returns the validity bits of the chunk's 32 tokens.
+    // Everything that depends on the role of the wavefront is folded into a few registers up
+    // front, so that the common path is straight-line code.
     const int i0 = 2 * hh;
+    const int r4 = lane >> 4, pos = lane & 15;
+    const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+    // per-lane byte offsets of the two operations relative to the chunk's first row (i0 is even:
+    // operation i0 takes the even swizzle, i0 + 1 the odd one)
+    const uint32_t lane_off0 = rb == 0 ? (uint32_t)(4 * i0 + r4) * st2 + sw_even : (uint32_t)(8 * r4 + i0) * st2 + vsw;
+    const uint32_t lane_off1 = rb == 0 ? (uint32_t)(4 * i0 + 4 + r4) * st2 + sw_odd : lane_off0 + st2;
+    const char *const src_base = rb == 0 ? kb : vb;
+    const char *const src_lane0 = src_base + lane_off0, *const src_lane1 = src_base + lane_off1;
+    const int dst_off0 = rb == 0 ? i0 * 1024 : 8192 + i0 * kVPiecePitch;
+    const int dst_off1 = dst_off0 + (rb == 0 ? 1024 : kVPiecePitch);
+    // the general path: source lanes of the two operations and the swizzles that go with them
+    const int shfl0 = rb == 0 ? 4 * i0 + r4 : 8 * r4 + i0;
+    const int shfl1 = rb == 0 ? shfl0 + 4 : shfl0 + 1;
+    const uint32_t gsw0 = rb == 0 ? sw_even : vsw, gsw1 = rb == 0 ? sw_odd : vsw;
     auto issue = [&](int ci, int stg) -> uint32_t {
+        char *dst = ring + stg * kStageBytes;
         int tok;
         if (ALIGNED) {
-            const int r0 = chunk_row0(ci);
-            tok = (r0 >= 0 && r0 + n < L) ? r0 + n : -1;
+            if (ci - row_base >= 64) fill_rows(ci);
+            const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
+            if (r0 >= 0) {
+                const uint32_t row_off = (uint32_t)r0 * st2;   // fits 32 bits (host-checked)
+                dma16(src_lane0 + row_off, dst + dst_off0);
+                dma16(src_lane1 + row_off, dst + dst_off1);
+                return 0xffffffffu;
+            }
+            const int rr = -2 - r0;   // r0 == -1 gives -1
+            tok = (rr >= 0 && rr + n < L) ? rr + n : -1;
         } else {
             tok = lane_row(ci);
         }
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
-        const int r4 = lane >> 4, pos = lane & 15;
-        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-        char *dst = ring + stg * kStageBytes;
-        char *dstk = dst + i0 * 1024;
-        char *dstv = dst + 8192 + i0 * kVPiecePitch;
-        if (ALIGNED && vm == 0xffffffffu) {
-            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
-            const size_t row0 = (size_t)t0 * st2;
-            const uint32_t lane_row_off = (uint32_t)r4 * st2;
-            if (rb == 0) {
-                // i0 is even: operation i0 takes the even swizzle, i0 + 1 the odd one
-                const char *ksrc = kb + row0 + (size_t)(4 * i0) * st2;
-                if (st2 == 256u) {
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + (lane_row_off + sw_even)), (lds_void_ptr)dstk, 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + (lane_row_off + sw_odd)), (lds_void_ptr)dstk, 16, 1024, 0);
-                } else {
-                    dma16(ksrc + (lane_row_off + sw_even), dstk);
-                    dma16(ksrc + (size_t)4 * st2 + (lane_row_off + sw_odd), dstk + 1024);
-                }
-            } else {
-                const char *vsrc = vb + row0 + (size_t)(8 * r4 + i0) * st2 + vsw;
-                if (st2 == 256u) {
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)dstv, 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (kVPiecePitch - 256)), 16, 256, 0);
-                } else {
-                    dma16(vsrc, dstv);
-                    dma16(vsrc + st2, dstv + kVPiecePitch);
-                }
-            }
-        } else if (rb == 0) {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * (i0 + t) + r4) * st2;
-                dma16(kb + (tv + (t ? sw_odd : sw_even)), dstk + t * 1024);
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i0 + t) * st2;
-                dma16(vb + (tv + vsw), dstv + t * kVPiecePitch);
-            }
-        }
+        dma16(src_base + ((uint32_t)__shfl((int)tk, shfl0) * st2 + gsw0), dst + dst_off0);
+        dma16(src_base + ((uint32_t)__shfl((int)tk, shfl1) * st2 + gsw1), dst + dst_off1);
         return vm;
     };
 
     bf16x8 qf[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
-    if (ALIGNED && nch > 0) {
-        const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
-        if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }
-        else refill(slot0);
-    }
+    if (ALIGNED && nch > 0) fill_rows(0);
     // from here on only this wavefront's DMA groups (2 operations each) are in flight (an
     // instruction the compiler knows, see attn_ctx_mfma_kernel)
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -1181,9 +1166,8 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             const uint32_t soff = (uint32_t)rs * kStageBytes;
             const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
             lds_read_k4(ka, kf);
-            lds_read_v(vread + soff, v);
         }
-
+        lds_read_v(vread + (uint32_t)rs * kStageBytes, v);
         f32x16 S;
 #pragma unroll
         for (int x = 0; x < 16; ++x) S[x] = 0.f;
