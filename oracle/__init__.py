@@ -82,13 +82,15 @@ def block_summarize(K, B):
     return kmax, kmin
 
 
-def row_scores(Q, kmax, kmin):
-    """eq. 2.  Q [M,Hq,D], summaries [nb,Hkv,D] -> s [Hkv,nb,M*G]."""
+def row_scores(Q, kmax, kmin, score="eq2"):
+    """eq. 2 (score="eq2") or the channel-wise bound (score="channel_bound").
+    Q [M,Hq,D], summaries [nb,Hkv,D] -> s [Hkv,nb,M*G]."""
     Q, kmax, kmin = _f64(Q), _f64(kmax), _f64(kmin)
     M, Hq, D = Q.shape
     nb, Hkv, _ = kmax.shape
     s = np.empty((Hkv, nb, M * (Hq // Hkv)))
-    _load().oracle_row_scores(_p(Q), M, Hq, _p(kmax), _p(kmin), nb, Hkv, D, _p(s))
+    fn = {"eq2": _load().oracle_row_scores, "channel_bound": _load().oracle_row_scores_channel}[score]
+    fn(_p(Q), M, Hq, _p(kmax), _p(kmin), nb, Hkv, D, _p(s))
     return s
 
 
@@ -102,12 +104,12 @@ def reduce_scores(s, M, G, reduce="mean", last_node=0):
     return out
 
 
-def block_scores(Q, kmax, kmin, reduce="mean", last_node=0):
-    """eq. 2 then eq. 3."""
+def block_scores(Q, kmax, kmin, reduce="mean", last_node=0, score="eq2"):
+    """eq. 2 (or the channel-wise bound) then eq. 3."""
     Q = _f64(Q)
     M, Hq, _ = Q.shape
     Hkv = kmax.shape[1]
-    return reduce_scores(row_scores(Q, kmax, kmin), M, Hq // Hkv, reduce, last_node)
+    return reduce_scores(row_scores(Q, kmax, kmin, score), M, Hq // Hkv, reduce, last_node)
 
 
 def select_blocks(scores, ns, nr, k):

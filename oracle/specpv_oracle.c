@@ -91,6 +91,35 @@ void oracle_row_scores(const double *Q, int M, int Hq,
                 }
 }
 
+/* The channel-wise variant of the block score, in the style of the query-aware
+ * page selection that Section 3.2 names as the inspiration for its summaries:
+ * per channel the larger of  q_r[d] * Kmax_i[d]  and  q_r[d] * Kmin_i[d],
+ * summed over the channels.  Unlike eq. 2 this is an upper bound of q_r . k_t
+ * for every token t of the block.  Same output layout as oracle_row_scores. */
+void oracle_row_scores_channel(const double *Q, int M, int Hq,
+                               const double *kmax, const double *kmin, int nb,
+                               int Hkv, int D, double *s)
+{
+    int G = Hq / Hkv;
+    int R = M * G;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int g = 0; g < Hkv; ++g)
+        for (int i = 0; i < nb; ++i)
+            for (int j = 0; j < M; ++j)
+                for (int hh = 0; hh < G; ++hh) {
+                    int h = g * G + hh;
+                    const double *q = Q + ((size_t)j * Hq + h) * D;
+                    const double *a = kmax + ((size_t)i * Hkv + g) * D;
+                    const double *b = kmin + ((size_t)i * Hkv + g) * D;
+                    double sum = 0.0;
+                    for (int d = 0; d < D; ++d) {
+                        double pa = q[d] * a[d], pb = q[d] * b[d];
+                        sum += pa > pb ? pa : pb;
+                    }
+                    s[((size_t)g * nb + i) * R + (size_t)j * G + hh] = sum;
+                }
+}
+
 /* Section 3.2, eq. 3: the per-row scores of a block are reduced to one score
  * by f in {mean, max, last}.  mean and max run over all M*G rows of the KV
  * head; "last" keeps only the rows of one designated node (the most recently

@@ -67,6 +67,40 @@ def test_scores_block_of_one_token_is_plain_dot_product():
     np.testing.assert_allclose(s, ref, rtol=0, atol=1e-12)
 
 
+def test_channel_bound_hand_example():
+    g = json.load(open(os.path.join(GOLD, "eq1_eq2_eq3_hand_example.json")))
+    Q = np.array(g["Q"], float)
+    kmax, kmin = np.array(g["kmax"], float), np.array(g["kmin"], float)
+    s = oracle.row_scores(Q, kmax, kmin, "channel_bound")
+    assert np.array_equal(s, np.array(g["row_scores_channel_bound"], float))
+    assert np.array_equal(oracle.reduce_scores(s, 2, 2, "mean"), np.array(g["mean_channel_bound"]))
+    assert np.array_equal(oracle.block_scores(Q, kmax, kmin, "mean", 0, "channel_bound"), np.array(g["mean_channel_bound"]))
+
+
+def test_channel_bound_is_an_upper_bound_and_tight_for_single_tokens():
+    # What defines the variant: it bounds q . k_t from above for EVERY token of the block (eq. 2
+    # does not), it is never below eq. 2, it equals q . k for blocks of one token, and it is
+    # attained when a block's tokens are all alike.
+    M, Hq, Hkv, D, L, B = 4, 6, 2, 9, 40, 8
+    G = Hq // Hkv
+    rng = np.random.default_rng(77)
+    Q, K = rng.standard_normal((M, Hq, D)), rng.standard_normal((L, Hkv, D))
+    kmax, kmin = oracle.block_summarize(K, B)
+    sc = oracle.row_scores(Q, kmax, kmin, "channel_bound")        # [Hkv, nb, M*G]
+    s2 = oracle.row_scores(Q, kmax, kmin, "eq2")
+    assert np.all(sc >= s2 - 1e-12)
+    assert np.any(sc > s2 + 1e-6)
+    dots = np.einsum("jghd,tgd->gtjh", Q.reshape(M, Hkv, G, D), K).reshape(Hkv, L, M * G)
+    per_block_max = dots.reshape(Hkv, L // B, B, M * G).max(axis=2)
+    assert np.all(sc >= per_block_max - 1e-12)
+    assert not np.all(s2 >= per_block_max - 1e-12)                # eq. 2 is no such bound
+    k1max, k1min = oracle.block_summarize(K, 1)
+    np.testing.assert_allclose(oracle.row_scores(Q, k1max, k1min, "channel_bound"), dots, rtol=0, atol=1e-12)
+    Kc = np.repeat(K[:5], B, axis=0)                              # 5 blocks of identical tokens
+    cmax, cmin = oracle.block_summarize(Kc, B)
+    np.testing.assert_allclose(oracle.row_scores(Q, cmax, cmin, "channel_bound"), dots[:, :5], rtol=0, atol=1e-12)
+
+
 def test_scores_gqa_head_mapping_and_row_order():
     # A query head must only see the summaries of KV head h // G, and row
     # r = j*G + hh.  Make every (node, head) pair and every KV head distinct.
