@@ -56,6 +56,13 @@ typedef enum { SPECPV_F32 = 0, SPECPV_BF16 = 1 } specpv_dtype;
 /* eq. 3: how the per-query scores of a block are reduced to one score. */
 typedef enum { SPECPV_REDUCE_MEAN = 0, SPECPV_REDUCE_MAX = 1, SPECPV_REDUCE_LAST = 2 } specpv_reduce;
 
+/* The per-query score of a block.  SPECPV_SCORE_EQ2 is the paper's (Section 3.2, eq. 2):
+ * max(q . Kmax, q . Kmin), two full inner products.  SPECPV_SCORE_CHANNEL_BOUND is the
+ * per-channel form of the query-aware page selection that the section names as the
+ * inspiration of its summaries: sum over the channels d of max(q[d] * Kmax[d], q[d] * Kmin[d]),
+ * an upper bound of q . k for every token of the block; it is here for comparison. */
+typedef enum { SPECPV_SCORE_EQ2 = 0, SPECPV_SCORE_CHANNEL_BOUND = 1 } specpv_score;
+
 #define SPECPV_MAX_M 128
 #define SPECPV_MAX_G 16
 
@@ -90,6 +97,7 @@ typedef struct specpv_tree {
 typedef struct specpv_select_cfg {
     int32_t n_sink_blocks, n_recent_blocks, k_blocks;
     specpv_reduce reduce;
+    specpv_score score;    /* SPECPV_SCORE_EQ2 (= 0) is the paper's                        */
 } specpv_select_cfg;
 
 /* Bytes of workspace that any of the calls below needs for these descriptors
@@ -107,7 +115,7 @@ int specpv_block_summarize(const specpv_kv *kv, int32_t blk_begin, int32_t blk_e
 
 /* Section 3.2, eq. 2 + eq. 3 + block selection.  Per (b, g):
  *   s[i, r] = max(q_r . kmax_i, q_r . kmin_i) for the M*G query rows r of the KV
- *   head (fp32 accumulation); score[i] = mean / max over all rows, or the mean
+ *   head (fp32 accumulation; or the channel-wise bound if cfg->score says so); score[i] = mean / max over all rows, or the mean
  *   over the G rows of tree->last_node;
  *   kept = blocks [0, ns) + the k best candidates of [ns, nb_b - nr) by (fp32
  *   score descending, block index ascending) + blocks [nb_b - nr, nb_b);

@@ -5,13 +5,13 @@ behind the C ABI declared in include/specpv.h.  torch is used for device memory
 and streams.  There is no CPU fallback: if the HIP library is not built, load()
 raises.
 """
-from .binding import (REDUCE_LAST, REDUCE_MAX, REDUCE_MEAN, SpecPVError, KV, Tree, SelectCfg, load,
+from .binding import (REDUCE_LAST, REDUCE_MAX, REDUCE_MEAN, SCORE_EQ2, SCORE_CHANNEL_BOUND, SpecPVError, KV, Tree, SelectCfg, load,
                       lib_path, specpv_block_summarize, specpv_full_verify_refresh,
                       specpv_partial_verify_attn, specpv_select_blocks, specpv_workspace_bytes,
                       specpv_strerror, specpv_version, EXPORTS, MODE_FULL, MODE_PARTIAL, MODE_REFRESH,
                       specpv_select_mode, specpv_extend_parents, specpv_commit_accepted, specpv_gather_blocks)
 
-__all__ = ["REDUCE_LAST", "REDUCE_MAX", "REDUCE_MEAN", "SpecPVError", "KV", "Tree", "SelectCfg", "load",
+__all__ = ["REDUCE_LAST", "REDUCE_MAX", "REDUCE_MEAN", "SCORE_EQ2", "SCORE_CHANNEL_BOUND", "SpecPVError", "KV", "Tree", "SelectCfg", "load",
            "lib_path", "specpv_block_summarize", "specpv_full_verify_refresh", "specpv_partial_verify_attn",
            "specpv_select_blocks", "specpv_workspace_bytes", "specpv_strerror", "specpv_version", "EXPORTS",
            "MODE_FULL", "MODE_PARTIAL", "MODE_REFRESH", "specpv_select_mode", "specpv_extend_parents",

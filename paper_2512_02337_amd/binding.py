@@ -14,6 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "libspecpv.so")
 
 REDUCE_MEAN, REDUCE_MAX, REDUCE_LAST = 0, 1, 2
 _REDUCE = {"mean": 0, "max": 1, "last": 2, 0: 0, 1: 1, 2: 2}
+SCORE_EQ2, SCORE_CHANNEL_BOUND = 0, 1
+_SCORE = {"eq2": 0, "channel_bound": 1, 0: 0, 1: 1}
 _DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 
 MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
@@ -50,7 +52,7 @@ class _Policy(ctypes.Structure):
 
 class _Cfg(ctypes.Structure):
     _fields_ = [("n_sink_blocks", ctypes.c_int32), ("n_recent_blocks", ctypes.c_int32),
-                ("k_blocks", ctypes.c_int32), ("reduce", ctypes.c_int)]
+                ("k_blocks", ctypes.c_int32), ("reduce", ctypes.c_int), ("score", ctypes.c_int)]
 
 
 _lib = None
@@ -178,10 +180,10 @@ class Tree:
 
 
 class SelectCfg:
-    def __init__(self, n_sink_blocks, n_recent_blocks, k_blocks, reduce="mean"):
+    def __init__(self, n_sink_blocks, n_recent_blocks, k_blocks, reduce="mean", score="eq2"):
         self.ns, self.nr, self.k = int(n_sink_blocks), int(n_recent_blocks), int(k_blocks)
         self.n_sel = self.ns + self.k + self.nr
-        self.c = _Cfg(self.ns, self.nr, self.k, _REDUCE[reduce])
+        self.c = _Cfg(self.ns, self.nr, self.k, _REDUCE[reduce], _SCORE[score])
 
 
 def _match(kv, tree):

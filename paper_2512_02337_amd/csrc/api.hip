@@ -67,6 +67,7 @@ static int check_cfg(const specpv_tree *tree, const specpv_select_cfg *cfg)
         return SPECPV_EINVAL;
     if (cfg->reduce == SPECPV_REDUCE_LAST && (tree->last_node < 0 || tree->last_node >= tree->M))
         return SPECPV_EINVAL;
+    if (cfg->score != SPECPV_SCORE_EQ2 && cfg->score != SPECPV_SCORE_CHANNEL_BOUND) return SPECPV_EINVAL;
     if ((int64_t)cfg->n_sink_blocks + cfg->n_recent_blocks + cfg->k_blocks > ((int64_t)1 << 24)) return SPECPV_ELIMIT;
     return SPECPV_OK;
 }
@@ -181,7 +182,7 @@ static int run_select(const Shape &s, int dtype, const specpv_tree *tree, const 
                       const specpv_select_cfg *cfg, int32_t *sel_idx, int32_t *sel_count, float *scores,
                       hipStream_t st)
 {
-    hipError_t e = launch_scores(s, dtype, kmax, kmin, (int)cfg->reduce, tree->last_node, scores, st);
+    hipError_t e = launch_scores(s, dtype, kmax, kmin, (int)cfg->reduce, tree->last_node, (int)cfg->score, scores, st);
     if (e != hipSuccess) return fail_hip(e);
     e = launch_topk(s, scores, cfg->n_sink_blocks, cfg->n_recent_blocks, cfg->k_blocks, sel_idx, sel_count, st);
     if (e != hipSuccess) return fail_hip(e);

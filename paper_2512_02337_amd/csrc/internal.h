@@ -90,8 +90,9 @@ __device__ __forceinline__ float wave_sum(float x) {
 // ---- launchers (each returns the hipError_t of its launches) ----
 hipError_t launch_summarize(const Shape &s, int dtype, int blk_begin, int blk_end,
                             void *kmax, void *kmin, hipStream_t st);
+// kind: SPECPV_SCORE_EQ2 or SPECPV_SCORE_CHANNEL_BOUND
 hipError_t launch_scores(const Shape &s, int dtype, const void *kmax, const void *kmin,
-                         int reduce, int last_node, float *scores, hipStream_t st);
+                         int reduce, int last_node, int kind, float *scores, hipStream_t st);
 hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k,
                        int32_t *sel_idx, int32_t *sel_count, hipStream_t st);
 hipError_t launch_attn_ctx_generic(const Shape &s, int dtype, const int32_t *sel_idx,

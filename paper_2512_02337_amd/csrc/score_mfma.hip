@@ -1,4 +1,5 @@
-// Block scoring (Section 3.2, eq. 2 and eq. 3) on the matrix cores for bf16, head dim 128.
+// Block scoring (Section 3.2, eq. 2 and eq. 3; optionally the channel-wise bound) on the matrix
+// cores for bf16, head dim 128.
 //
 // Per KV head the scores are max(Q . Kmax^T, Q . Kmin^T) reduced over the M*G query rows:
 // two [rows x 128] x [128 x blocks] products.  A workgroup owns a tile of 32 blocks and
@@ -21,6 +22,10 @@ constexpr int kScoreMaxWaves = 16;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 
+// BOUND: the channel-wise bound instead of eq. 2.  Per channel the larger product is q * Kmax
+// where q >= 0 and q * Kmin where q < 0 (Kmax >= Kmin), so the bound is the sum of two inner
+// products as well: max(q, 0) . Kmax + min(q, 0) . Kmin, accumulated into one tile.
+template <bool BOUND>
 __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s, const uint16_t *__restrict__ kmax,
                                                                          const uint16_t *__restrict__ kmin, int reduce,
                                                                          int last_node, float *__restrict__ scores)
@@ -83,15 +88,32 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
         for (int x = 0; x < 16; ++x) { sx[x] = 0.f; sn[x] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, qa[ks]);
-            sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[ks], sx, 0, 0, 0);
-            sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bn[ks], sn, 0, 0, 0);
+            if (BOUND) {
+                // split the packed bf16 pairs by sign: 0xffff in the halves whose sign bit is set
+                uint4 neg, pos;
+                const uint32_t w[4] = {qa[ks].x, qa[ks].y, qa[ks].z, qa[ks].w};
+                uint32_t pw[4], nw[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t m = ((w[e] >> 15) & 0x00010001u) * 0xffffu;
+                    nw[e] = w[e] & m;
+                    pw[e] = w[e] & ~m;
+                }
+                pos = make_uint4(pw[0], pw[1], pw[2], pw[3]);
+                neg = make_uint4(nw[0], nw[1], nw[2], nw[3]);
+                sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pos), bx[ks], sx, 0, 0, 0);
+                sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, neg), bn[ks], sx, 0, 0, 0);
+            } else {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, qa[ks]);
+                sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[ks], sx, 0, 0, 0);
+                sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bn[ks], sn, 0, 0, 0);
+            }
         }
         // accumulator slot x holds row r0 + (x>>2)*8 + kg*4 + (x&3) of this lane's block
 #pragma unroll
         for (int x = 0; x < 16; ++x) {
             const int row = r0 + (x >> 2) * 8 + kg * 4 + (x & 3);
-            const float sv = fmaxf(sx[x], sn[x]);
+            const float sv = BOUND ? sx[x] : fmaxf(sx[x], sn[x]);
             if (reduce == SPECPV_REDUCE_MAX) {
                 if (row < R) acc = fmaxf(acc, sv);
             } else if (reduce == SPECPV_REDUCE_MEAN) {
@@ -121,12 +143,16 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
 bool score_mfma_supported(const Shape &s, int dtype) { return dtype == SPECPV_BF16 && s.D == 128; }
 
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
-                              int last_node, float *scores, hipStream_t st)
+                              int last_node, int kind, float *scores, hipStream_t st)
 {
     const int tiles = (s.max_blocks + 31) / 32, row_tiles = (s.M * s.G + 31) / 32;
     dim3 grid(tiles, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
-    hipLaunchKernelGGL(score_mfma_kernel, grid, block, 0, st, s, (const uint16_t *)kmax, (const uint16_t *)kmin,
-                       reduce, last_node, scores);
+    if (kind == SPECPV_SCORE_CHANNEL_BOUND)
+        hipLaunchKernelGGL(score_mfma_kernel<true>, grid, block, 0, st, s, (const uint16_t *)kmax,
+                           (const uint16_t *)kmin, reduce, last_node, scores);
+    else
+        hipLaunchKernelGGL(score_mfma_kernel<false>, grid, block, 0, st, s, (const uint16_t *)kmax,
+                           (const uint16_t *)kmin, reduce, last_node, scores);
     return hipGetLastError();
 }
 

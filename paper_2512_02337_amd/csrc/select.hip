@@ -13,7 +13,7 @@ namespace specpv {
 // ---------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(64) void score_generic_kernel(Shape s, const void *kmax, const void *kmin,
-                                                          int reduce, int last_node, float *scores)
+                                                          int reduce, int last_node, int kind, float *scores)
 {
     constexpr int RC = 32;  // query rows per LDS pass
     __shared__ float qs[RC][D];
@@ -51,20 +51,32 @@ __global__ __launch_bounds__(64) void score_generic_kernel(Shape s, const void *
                 kx[e] = Elem<T>::load(kmax, so + d0 + e);
                 kn[e] = Elem<T>::load(kmin, so + d0 + e);
             }
+            if (kind == SPECPV_SCORE_CHANNEL_BOUND) {
+                // per channel the larger product: q * Kmax where q >= 0, q * Kmin where q < 0 (Kmax >= Kmin)
 #pragma unroll
-            for (int r = 0; r < RC; ++r) {
+                for (int r = 0; r < RC; ++r) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float qv = qs[r][d0 + e];
-                    am[r] = fmaf(qv, kx[e], am[r]);
-                    an[r] = fmaf(qv, kn[e], an[r]);
+                    for (int e = 0; e < 8; ++e) {
+                        const float qv = qs[r][d0 + e];
+                        am[r] = fmaf(qv, qv < 0.f ? kn[e] : kx[e], am[r]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < RC; ++r) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float qv = qs[r][d0 + e];
+                        am[r] = fmaf(qv, kx[e], am[r]);
+                        an[r] = fmaf(qv, kn[e], an[r]);
+                    }
                 }
             }
         }
 #pragma unroll
         for (int r = 0; r < RC; ++r) {
             if (r < nrows) {
-                const float sv = fmaxf(am[r], an[r]);
+                const float sv = kind == SPECPV_SCORE_CHANNEL_BOUND ? am[r] : fmaxf(am[r], an[r]);
                 if (reduce == SPECPV_REDUCE_MAX) acc_max = fmaxf(acc_max, sv);
                 else if (reduce == SPECPV_REDUCE_MEAN) acc_sum += sv;
                 else if ((r0 + r) / s.G == last_node) acc_sum += sv;
@@ -79,11 +91,11 @@ __global__ __launch_bounds__(64) void score_generic_kernel(Shape s, const void *
 }
 
 static hipError_t launch_scores_generic(const Shape &s, int dtype, const void *kmax, const void *kmin,
-                                 int reduce, int last_node, float *scores, hipStream_t st)
+                                 int reduce, int last_node, int kind, float *scores, hipStream_t st)
 {
     dim3 grid((s.max_blocks + 63) / 64, s.Hkv, s.batch), block(64);
 #define SPECPV_LAUNCH(T, DD) \
-    hipLaunchKernelGGL((score_generic_kernel<T, DD>), grid, block, 0, st, s, kmax, kmin, reduce, last_node, scores)
+    hipLaunchKernelGGL((score_generic_kernel<T, DD>), grid, block, 0, st, s, kmax, kmin, reduce, last_node, kind, scores)
     if (dtype == SPECPV_BF16) {
         if (s.D == 128) SPECPV_LAUNCH(bf16_t, 128); else SPECPV_LAUNCH(bf16_t, 64);
     } else {
@@ -386,14 +398,14 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
 
 bool score_mfma_supported(const Shape &s, int dtype);
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
-                              int last_node, float *scores, hipStream_t st);
+                              int last_node, int kind, float *scores, hipStream_t st);
 
 hipError_t launch_scores(const Shape &s, int dtype, const void *kmax, const void *kmin,
-                         int reduce, int last_node, float *scores, hipStream_t st)
+                         int reduce, int last_node, int kind, float *scores, hipStream_t st)
 {
     if (score_mfma_supported(s, dtype))
-        return launch_scores_mfma(s, kmax, kmin, reduce, last_node, scores, st);
-    return launch_scores_generic(s, dtype, kmax, kmin, reduce, last_node, scores, st);
+        return launch_scores_mfma(s, kmax, kmin, reduce, last_node, kind, scores, st);
+    return launch_scores_generic(s, dtype, kmax, kmin, reduce, last_node, kind, scores, st);
 }
 
 hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k,

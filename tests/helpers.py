@@ -17,7 +17,7 @@ def say(*a):
 class GpuRun:
     """Device buffers + descriptors of one case."""
 
-    def __init__(self, specpv, case, layout="bhtd", reduce="mean", last_node=0, cfg=None):
+    def __init__(self, specpv, case, layout="bhtd", reduce="mean", last_node=0, cfg=None, score="eq2"):
         self.sp, self.case = specpv, case
         dev = case["q"].device
         assert dev.type == "cuda"
@@ -29,7 +29,7 @@ class GpuRun:
         self.kv = specpv.KV(k, v, case["ctx_len"], case["B"], case["max_blocks"], layout=layout)
         self.tree = specpv.Tree(case["q"], case["kd"], case["vd"], case["parent"], last_node=last_node)
         ns, nr, kb = cfg if cfg is not None else (case["ns"], case["nr"], case["k_blocks"])
-        self.cfg = specpv.SelectCfg(ns, nr, kb, reduce)
+        self.cfg = specpv.SelectCfg(ns, nr, kb, reduce, score)
         dt = case["q"].dtype
         b, hkv, nbm, D = self.kv.summary_shape()
         self.kmax = torch.zeros((b, hkv, nbm, D), dtype=dt, device=dev)
@@ -60,11 +60,11 @@ class GpuRun:
                                            self.lse, self.sel_idx, self.sel_count, self.scores, self.ws)
 
 
-def oracle_select(case, b, reduce="mean", last_node=0, cfg=None):
+def oracle_select(case, b, reduce="mean", last_node=0, cfg=None, score="eq2"):
     o = workloads.oracle_views(case, b)
     ns, nr, kb = cfg if cfg is not None else (case["ns"], case["nr"], case["k_blocks"])
     kmax, kmin = oracle.block_summarize(o["K"], case["B"])
-    sc = oracle.block_scores(o["Q"], kmax, kmin, reduce, last_node)
+    sc = oracle.block_scores(o["Q"], kmax, kmin, reduce, last_node, score)
     idx, cnt = oracle.select_blocks(sc, ns, nr, kb)
     return o, kmax, kmin, sc, idx, cnt
 

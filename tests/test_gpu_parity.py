@@ -156,6 +156,31 @@ def test_reducers(gpu_lib, reduce, last_node):
                     case["ns"], case["nr"], case["k_blocks"], reduce)
 
 
+@pytest.mark.parametrize("over,tag", [
+    (dict(), "bf16 D=128 (matrix-core scorer)"),
+    (dict(dtype="f32", D=64), "f32 D=64 (vector-ALU scorer)"),
+    (dict(ctx=[4000], B=64, M=60, k=20), "bf16, 240 query rows over several wavefronts"),
+])
+@pytest.mark.parametrize("reduce", ["mean", "max"])
+def test_channel_bound_scores(gpu_lib, over, tag, reduce):
+    """The channel-wise bound as block score (a comparison variant): scores against the oracle's
+    per-channel definition, and the selection that follows from them."""
+    say("channel bound", tag, reduce)
+    cfg = dict(SMALL); cfg.update(over)
+    case = workloads.to_device(workloads.make_case(cfg, seed=23), "cuda")
+    run = GpuRun(gpu_lib, case, reduce=reduce, score="channel_bound")
+    run.summarize(); run.select()
+    torch.cuda.synchronize()
+    o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0, reduce, 0, score="channel_bound")
+    nb = kmax.shape[0]
+    got = run.scores.cpu().numpy()[0][:, :nb]
+    np.testing.assert_allclose(got, sc, rtol=2e-5, atol=2e-4)
+    sc_eq2 = oracle_select(case, 0, reduce, 0)[3]
+    assert np.all(got >= sc_eq2 - 1e-3) and np.any(got > sc_eq2 + 1e-2)   # it is a different, larger score
+    check_selection(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0], idx, cnt, sc,
+                    case["ns"], case["nr"], case["k_blocks"], "channel bound " + tag)
+
+
 def test_selection_ties_and_extremes(gpu_lib):
     """Exact ties (duplicated blocks) must go to the lower index; k = 0, no sink, no
     local window and k larger than the candidates are all legal."""
