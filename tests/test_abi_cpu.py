@@ -42,7 +42,7 @@ def _tree(**over):
 
 
 def _cfg(**over):
-    d = dict(n_sink_blocks=1, n_recent_blocks=2, k_blocks=4, reduce=0)
+    d = dict(n_sink_blocks=1, n_recent_blocks=2, k_blocks=4, reduce=0, score=0)
     d.update(over)
     return binding._Cfg(**d)
 
@@ -85,6 +85,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     sel = (vp(0x100), vp(0x200), None, vp(0x8000), ws_bytes, None)
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg(k_blocks=-1)), *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg(reduce=9)), *sel) == -1
+    assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg(score=2)), *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree(last_node=60)), vp(16), vp(32), B(_cfg(reduce=2)), *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), None, *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg()), vp(0x100), vp(0x200), None,
