@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
         const int sp = min(u, part.nsplit - 1);
         const int64_t prow = prow0 + (int64_t)sp * s.M;
 #pragma unroll
-        for (int x = 0; x < DPL; ++x) po[u][x] = part.o[prow * D + lane + 64 * x];
+        for (int x = 0; x < DPL; ++x) po[u][x] = __builtin_nontemporal_load(part.o + prow * D + lane + 64 * x);
     }
 
     // ---- root path of node j as a bit set (wave-uniform walk over the parent registers) --
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
             const int sp = min(sp0 + u, part.nsplit - 1);
             const int64_t prow = prow0 + (int64_t)sp * s.M;
 #pragma unroll
-            for (int x = 0; x < DPL; ++x) po[u][x] = part.o[prow * D + lane + 64 * x];
+            for (int x = 0; x < DPL; ++x) po[u][x] = __builtin_nontemporal_load(part.o + prow * D + lane + 64 * x);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
