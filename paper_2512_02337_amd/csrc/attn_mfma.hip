@@ -559,7 +559,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     }
     if (lane < RPW) {
         const int j = m0 + wave * RPW + lane;
-        if (j < s.M) store_partial(part.ml + (prow0 + j) * 2, make_float2(m_row, l_row));
+        if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
     }
 }
 
@@ -958,7 +958,7 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
     }
     if (lane < RPW) {
         const int j = m0 + tg * RPW + lane;
-        if (j < s.M) store_partial(part.ml + (prow0 + j) * 2, make_float2(m_row, l_row));
+        if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
     }
 }
 
@@ -1103,8 +1103,8 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
             if (r0 >= 0) {
                 const uint32_t row_off = (uint32_t)r0 * st2;   // fits 32 bits (host-checked)
-                dma16(src_lane0 + row_off, dst + dst_off0);
-                dma16(src_lane1 + row_off, dst + dst_off1);
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane0 + row_off), (lds_void_ptr)(dst + dst_off0), 16, 0, 2);
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane1 + row_off), (lds_void_ptr)(dst + dst_off1), 16, 0, 2);
                 return 0xffffffffu;
             }
             const int rr = -2 - r0;   // r0 == -1 gives -1
@@ -1247,7 +1247,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
         if (jrow0 + uu < s.M) store_partial(part.o + (prow0 + jrow0 + uu) * 128 + 2 * lane, x);
     }
-    if (kg == 0 && jrow0 + n < s.M) store_partial(part.ml + (prow0 + jrow0 + n) * 2, make_float2(m_ref, l_run));
+    if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
 }
 
 bool attn_ctx_mfma_supported(const Shape &s, int dtype)

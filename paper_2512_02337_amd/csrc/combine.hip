@@ -182,7 +182,7 @@ __global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, voi
     const float den = l * wd + l_ctx * wc;
     const float inv = 1.f / den;
 #pragma unroll
-    for (int x = 0; x < DPL; ++x) Elem<T>::store(out, qrow + lane + 64 * x, (od[x] * wd + o[x] * wc) * inv);
+    for (int x = 0; x < DPL; ++x) Elem<T>::store_stream(out, qrow + lane + 64 * x, (od[x] * wd + o[x] * wc) * inv);
     if (lse && lane == 0) lse[((int64_t)b * s.M + j) * s.Hq + h] = (m_all + log2f(den)) * kLn2;
 }
 

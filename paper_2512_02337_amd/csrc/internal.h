@@ -45,6 +45,7 @@ template <> struct Elem<float> {
     }
     static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
     static __device__ __forceinline__ void store(void *p, int64_t i, float x) { ((float *)p)[i] = x; }
+    static __device__ __forceinline__ void store_stream(void *p, int64_t i, float x) { __builtin_nontemporal_store(x, (float *)p + i); }
 };
 struct bf16_t { uint16_t bits; };
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
@@ -73,6 +74,9 @@ template <> struct Elem<bf16_t> {
     }
     static __device__ __forceinline__ void store(void *p, int64_t i, float x) {
         ((uint16_t *)p)[i] = float_to_bf16_bits(x);
+    }
+    static __device__ __forceinline__ void store_stream(void *p, int64_t i, float x) {
+        __builtin_nontemporal_store(float_to_bf16_bits(x), (uint16_t *)p + i);
     }
 };
 
