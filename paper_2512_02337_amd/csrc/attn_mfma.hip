@@ -54,6 +54,7 @@ constexpr int kStageBytes = 8192 + 8 * kVPiecePitch;
 constexpr int kStages = 2;           // ring depth per wavefront
 constexpr int kRingBytes = 4 * kStages * kStageBytes;
 constexpr int kWideStageBytes = kStageBytes;
+constexpr int kKvAux = 2;
 constexpr float kRescaleSlack = 8.f; // the reference max may lag the true max by 2^8
 
 // Exact n / d for 0 <= n < 2^31 with a host-prepared multiplier (no integer divide
@@ -100,7 +101,7 @@ __device__ __forceinline__ float add_bf16x2(uint32_t p, float acc)
 // lane l of the wavefront lands at lds_dst + 16*l.
 __device__ __forceinline__ void dma16(const char *gsrc, char *lds_dst)
 {
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_dst, 16, 0, kKvAux);
 }
 
 // Four such operations 1 KiB apart on both sides: gbase is wavefront-uniform, the per-lane
@@ -108,10 +109,10 @@ __device__ __forceinline__ void dma16(const char *gsrc, char *lds_dst)
 // immediate offset of the instruction is added to the global and to the LDS address.
 __device__ __forceinline__ void dma16x4(const char *gbase, uint32_t off_even, uint32_t off_odd, char *lds_dst)
 {
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 1024, 0);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 2048, 0);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 3072, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 0, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 1024, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 2048, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 3072, kKvAux);
 }
 
 // The LDS reads of staged K / V are written in assembly so that the compiler does not
@@ -376,7 +377,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
                     dma16x4(kb + row0 + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
                 } else {
                     const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
-#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, 0)
+#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, kKvAux)
                     SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
                     SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
 #undef SPECPV_VOP
@@ -732,7 +733,7 @@ void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
                 dma16x4(kb + row0, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst);
                 dma16x4(kb + row0 + 4096, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst + 4096);
                 const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
-#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, 0)
+#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, kKvAux)
                 SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
                 SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
 #undef SPECPV_VOP
@@ -1103,8 +1104,8 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
             if (r0 >= 0) {
                 const uint32_t row_off = (uint32_t)r0 * st2;   // fits 32 bits (host-checked)
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane0 + row_off), (lds_void_ptr)(dst + dst_off0), 16, 0, 2);
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane1 + row_off), (lds_void_ptr)(dst + dst_off1), 16, 0, 2);
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane0 + row_off), (lds_void_ptr)(dst + dst_off0), 16, 0, kKvAux);
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane1 + row_off), (lds_void_ptr)(dst + dst_off1), 16, 0, kKvAux);
                 return 0xffffffffu;
             }
             const int rr = -2 - r0;   // r0 == -1 gives -1
