@@ -162,6 +162,17 @@ namespace specpv {
 // Gathered (physically contiguous) partial cache, Section 3.2: one workgroup per (list slot,
 // KV head, sequence) copies one block of K and of V with 16-byte accesses, all of a thread's
 // reads issued before its writes.
+// 16-byte copies with the streaming hint (every byte is read once and written once)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const void *p)
+{
+    return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t *)p));
+}
+__device__ __forceinline__ void stream_store16(void *p, uint4 v)
+{
+    __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, v), (u32x4_t *)p);
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_blocks_kernel(Shape s, const int32_t *sel_idx, const int32_t *sel_count,
                                                             int n_sel, T *out_k, T *out_v, int32_t *out_len)
@@ -187,16 +198,16 @@ __global__ __launch_bounds__(256) void gather_blocks_kernel(Shape s, const int32
             kk[x] = make_uint4(0, 0, 0, 0);
             vv[x] = kk[x];
             if (valid && r < s.B && t < L) {
-                kk[x] = *(const uint4 *)((const T *)s.k + src0 + (int64_t)t * s.st);
-                vv[x] = *(const uint4 *)((const T *)s.v + src0 + (int64_t)t * s.st);
+                kk[x] = stream_load16((const T *)s.k + src0 + (int64_t)t * s.st);
+                vv[x] = stream_load16((const T *)s.v + src0 + (int64_t)t * s.st);
             }
         }
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int r = r0 + x * RPP + rsub;
             if (r < s.B) {
-                *(uint4 *)(out_k + dst0 + (int64_t)r * D) = kk[x];
-                *(uint4 *)(out_v + dst0 + (int64_t)r * D) = vv[x];
+                stream_store16(out_k + dst0 + (int64_t)r * D, kk[x]);
+                stream_store16(out_v + dst0 + (int64_t)r * D, vv[x]);
             }
         }
     }

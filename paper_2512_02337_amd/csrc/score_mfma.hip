@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
             const int i = d & 7, row = 4 * i + r4;
             const int blk = min(i0 + row, s.max_blocks - 1);
             const char *src = (const char *)(d < 8 ? kmax : kmin) + ((arr_row0 + blk) * 128) * 2 + 16 * (pos ^ (row & 7));
-            __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile[d >> 3] + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile[d >> 3] + i * 1024), 16, 0, 2);   // streaming hint: read once
         }
     }
 
