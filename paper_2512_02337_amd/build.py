@@ -10,6 +10,8 @@ SOURCES = ["api.hip", "summarize.hip", "select.hip", "score_mfma.hip", "attn_gen
            "attn_mfma.hip", "combine.hip", "commit.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # leading scalar kernel arguments arrive in registers instead of through a load
+         "-mllvm", "-amdgpu-kernarg-preload-count=12",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 

@@ -267,12 +267,14 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
         return (int)((uint32_t)w * base + min((uint32_t)w, rem));
     };
-    int spec_slot = 0, spec_vec = 0;
+    // lane t: the kept-block id that chunk t of this wavefront falls into, if the list is full
+    // (its length is not known yet; the usual case)
+    uint32_t spec_C = 0u;
+    int spec_blk = -1;
     if (ALIGNED && sel) {
-        const uint32_t Cspec = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
-        spec_slot = (int)a.div_B.div((uint32_t)first_chunk(Cspec, wsid) * 32u);
-        const int x = spec_slot + lane;
-        spec_vec = x < a.n_sel ? sel[x] : -1;
+        spec_C = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
+        const uint32_t slot = a.div_B.div((uint32_t)(first_chunk(spec_C, wsid) + lane) * 32u);
+        spec_blk = slot < (uint32_t)a.n_sel ? sel[slot] : -1;
     }
     uint4 qraw[8];
     {
@@ -310,26 +312,29 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
                            32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
 
     // ---- chunk -> token rows ------------------------------------------------------------
-    // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive
-    // and everything about it is wavefront-uniform.  The kept-block ids of the next 64
-    // list slots sit in a register (one per lane) and are picked with readlane.
-    int slot_base = 0, blkvec = 0;
-    auto refill = [&](int slot) {
-        slot_base = slot;
-        const int x = slot + lane;
-        blkvec = (sel && x < cnt) ? sel[x] : x;
-        // wait for the list entries here, inside the rare branch, so that the common path
-        // that joins behind it carries no pending load (and no wait on the DMA prefetch)
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    };
-    // first token row of chunk ci (relative to c0), or -1 if the block is not valid
-    auto chunk_row0 = [&](int ci) -> int {
-        const uint32_t p0 = (uint32_t)(c0 + ci) * 32u;
-        const uint32_t slot = a.div_B.div(p0);
-        if ((int)slot - slot_base >= 64) refill((int)slot);
-        const int blk = __builtin_amdgcn_readlane(blkvec, (int)slot - slot_base);
+    // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive.  The
+    // first rows of the next 64 chunks of this wavefront sit in a register (lane t: chunk
+    // row_base + t) and are picked with readlane.  Encoding: r >= 0: all 32 rows r .. r+31 are
+    // valid tokens (the common case, handled without any further test); -1: no valid token;
+    // -2 - r: rows from r on, cut off by the context length.
+    int row_base = 0, row0vec = -1;
+    auto encode_row = [&](int blk, uint32_t p0, uint32_t slot) -> int {
         if (blk < 0 || blk >= nb) return -1;
-        return blk * s.B + (int)(p0 - slot * Bu);
+        const int r = blk * s.B + (int)(p0 - slot * Bu);
+        return r >= L ? -1 : (r + 32 > L ? -2 - r : r);
+    };
+    auto fill_rows = [&](int cb) {
+        row_base = cb;
+        int r = -1;
+        if (cb + lane < nch) {
+            const uint32_t p0 = (uint32_t)(c0 + cb + lane) * 32u;   // < T: the slot below is < cnt
+            const uint32_t slot = a.div_B.div(p0);
+            r = encode_row(sel ? sel[slot] : (int)slot, p0, slot);
+        }
+        row0vec = r;
+        // wait for the list entries here, inside the rare branch, so that the common path that
+        // joins behind it carries no pending load (and no wait on the DMA prefetch)
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     };
     // general case: this lane's token (t = lane & 31) of chunk ci, or -1
     auto lane_row = [&](int ci) -> int {
@@ -347,51 +352,55 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     // Request this wavefront's half of chunk ci: 8 DMA operations of 1 KiB (one 256-byte row per
     // 16 lanes).  rb == 0: the K rows, operation i brings rows 4i .. 4i+3, pieces swizzled by
     // row & 7.  rb == 1: the V rows, operation i brings rows i, i+8, i+16, i+24 into piece i.
+    const int r4 = lane >> 4, pos = lane & 15;
+    const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+    const uint32_t lane_row_off = (uint32_t)r4 * st2;
     auto issue = [&](int ci) {
         const int stg = ci & (kStages - 1);
+        char *dst = my_ring + stg * kStageBytes;
+        char *dstv = dst + 8192;
         int tok;
         if (ALIGNED) {
-            const int r0 = chunk_row0(ci);
-            tok = (r0 >= 0 && r0 + n < L) ? r0 + n : -1;
+            if (ci - row_base >= 64) fill_rows(ci);
+            const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
+            if (r0 >= 0) {
+                vmask_st[stg] = 0xffffffffu;
+                const size_t row0 = (size_t)((uint32_t)r0 * st2);   // fits 32 bits (host-checked)
+                if (st2 == 256u) {
+                    // rows are 256 bytes apart (the usual head-major cache): the instruction's
+                    // immediate offset, added to the global and to the LDS address, covers the step
+                    // between consecutive operations (K: 1 KiB on both sides; V: 256 bytes, with the
+                    // LDS base adjusted for the rest of the piece pitch)
+                    if (rb == 0) {
+                        dma16x4(kb + row0, lane_row_off + sw_even, lane_row_off + sw_odd, dst);
+                        dma16x4(kb + row0 + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
+                    } else {
+                        const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
+#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, kKvAux)
+                        SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
+                        SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
+#undef SPECPV_VOP
+                    }
+                } else if (rb == 0) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        dma16(vb + row0 + (size_t)(8 * r4 + i) * st2 + vsw, dstv + i * kVPiecePitch);
+                }
+                return;
+            }
+            const int rr = -2 - r0;   // r0 == -1 gives -1
+            tok = (rr >= 0 && rr + n < L) ? rr + n : -1;
         } else {
             tok = lane_row(ci);
         }
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
         vmask_st[stg] = vm;
-        const int r4 = lane >> 4, pos = lane & 15;
-        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-        char *dst = my_ring + stg * kStageBytes;
-        char *dstv = dst + 8192;
-        if (ALIGNED && vm == 0xffffffffu) {
-            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
-            const size_t row0 = (size_t)t0 * st2;
-            const uint32_t lane_row_off = (uint32_t)r4 * st2;
-            if (st2 == 256u) {
-                // rows are 256 bytes apart (the usual head-major cache): the instruction's
-                // immediate offset, added to the global and to the LDS address, covers the step
-                // between consecutive operations (K: 1 KiB on both sides; V: 256 bytes, with the
-                // LDS base adjusted for the rest of the piece pitch)
-                if (rb == 0) {
-                    dma16x4(kb + row0, lane_row_off + sw_even, lane_row_off + sw_odd, dst);
-                    dma16x4(kb + row0 + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
-                } else {
-                    const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
-#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, kKvAux)
-                    SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
-                    SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
-#undef SPECPV_VOP
-                }
-            } else if (rb == 0) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    dma16(vb + row0 + (size_t)(8 * r4 + i) * st2 + vsw, dstv + i * kVPiecePitch);
-            }
-        } else if (rb == 0) {
+        if (rb == 0) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
@@ -411,9 +420,12 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
     if (ALIGNED && nch > 0) {
-        const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
-        if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }   // the usual case
-        else refill(slot0);
+        if (sel && C == spec_C) {   // the usual case: the speculative ids are the right ones
+            const uint32_t p0 = (uint32_t)(c0 + lane) * 32u;
+            row0vec = lane < nch ? encode_row(spec_blk, p0, a.div_B.div(p0)) : -1;
+        } else {
+            fill_rows(0);
+        }
     }
     // every load above has been consumed here: from now on the only vector-memory
     // operations of this wavefront in flight are its own DMA groups (8 operations each)

@@ -39,9 +39,13 @@ __device__ __forceinline__ float wave_max_u(float x)
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(64) void combine_kernel(Shape s, Partials part, void *out, float *lse,
-                                                     float scale_log2)
+__global__ __launch_bounds__(64) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
+                                                     const float *a_pml, int a_M, int a_Hq, int a_G, int a_nsplit,
+                                                     Shape s, Partials part, void *out, float *lse, float scale_log2)
 {
+    // the leading scalar arguments repeat what the first round of reads needs; they can be preloaded into registers
+    s.parent = a_parent; s.q = a_q; s.M = a_M; s.Hq = a_Hq; s.G = a_G;
+    part.o = const_cast<float *>(a_po); part.ml = const_cast<float *>(a_pml); part.nsplit = a_nsplit;
     constexpr int DPL = D / 64;   // channels per lane: d = lane + 64 * x
     const int lane = threadIdx.x;
     const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z, g = h / s.G;
@@ -191,7 +195,7 @@ hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, floa
     dim3 grid(s.M, s.Hq, s.batch), block(64);
     const float scale_log2 = kLog2e / sqrtf((float)s.D);
 #define SPECPV_LAUNCH(T, DD) \
-    hipLaunchKernelGGL((combine_kernel<T, DD>), grid, block, 0, st, s, p, out, lse, scale_log2)
+    hipLaunchKernelGGL((combine_kernel<T, DD>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
     if (dtype == SPECPV_BF16) {
         if (s.D == 128) SPECPV_LAUNCH(bf16_t, 128); else SPECPV_LAUNCH(bf16_t, 64);
     } else {
