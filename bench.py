@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-offload", action="store_true", help="skip the host-offload leg of the extras (2 GiB of pinned memory)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run 4 plain device copies of 256 MiB (read 256 MiB + write 256 MiB each) so that "
@@ -200,6 +201,43 @@ def main():
                 specpv.specpv_partial_verify_attn(x["kv"], l["tree"], None, None, l["out"], None, ws)
         extras["gather_us_per_step"] = round(timed(gather_step, k2, 3, use_graph) * 1e3, 2)
         extras["partial_on_gathered_us_per_step"] = round(timed(gathered_partial_step, k2, 3, use_graph) * 1e3, 2)
+        # Section 3.3's offload: the full cache of 4 layers in pinned host memory, two device slots,
+        # the next layer copied in while the current one runs its full verification + refresh + gather
+        # of the new partial cache (PCIe-bound: reported per layer, with the host-to-device rate)
+        if n_layers >= 4 and not args.no_offload:
+            from paper_2512_02337_amd.offload import LayerPrefetcher
+            sub = layers[:4]
+            hk = [l["kv"].k.cpu().pin_memory() for l in sub]
+            hv = [l["kv"].v.cpu().pin_memory() for l in sub]
+            pf = LayerPrefetcher(hk, hv, slots=2)
+            staged = []
+            for i in range(2):
+                c = sub[i]["case"]
+                staged.append(specpv.KV(pf.dev_k[i], pf.dev_v[i], c["ctx_len"], c["B"], c["max_blocks"]))
+
+            def offload_pass():
+                pf.prefetch(0)
+                for i, (l, x) in enumerate(zip(sub, g)):
+                    if i + 1 < len(sub):
+                        pf.prefetch(i + 1)
+                    pf.acquire(i)
+                    kv = staged[i % 2]
+                    specpv.specpv_full_verify_refresh(kv, l["tree"], l["kmax"], l["kmin"], -1, l["cfg"], l["out_full"],
+                                                      None, l["sel_idx"], l["sel_count"], None, ws)
+                    specpv.specpv_gather_blocks(kv, l["sel_idx"], l["sel_count"], x["k"], x["v"], x["len"])
+                    pf.release(i)
+            offload_pass()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(2):
+                offload_pass()
+            e1.record()
+            torch.cuda.synchronize()
+            per_layer_ms = e0.elapsed_time(e1) / (2 * len(sub))
+            extras["offload_full_refresh_us_per_layer"] = round(per_layer_ms * 1e3, 1)
+            extras["offload_h2d_GBs"] = round((hk[0].numel() + hv[0].numel()) * hk[0].element_size() / (per_layer_ms * 1e-3) / 1e9, 1)
+            del pf, hk, hv, staged
         extras["setup_s"] = round(setup_s, 1)
 
     cpu = None

@@ -16,3 +16,6 @@ __all__ = ["REDUCE_LAST", "REDUCE_MAX", "REDUCE_MEAN", "SCORE_EQ2", "SCORE_CHANN
            "specpv_select_blocks", "specpv_workspace_bytes", "specpv_strerror", "specpv_version", "EXPORTS",
            "MODE_FULL", "MODE_PARTIAL", "MODE_REFRESH", "specpv_select_mode", "specpv_extend_parents",
            "specpv_commit_accepted", "specpv_gather_blocks"]
+from .offload import LayerPrefetcher  # noqa: E402  (host-memory staging for the offloaded full cache)
+
+__all__.append("LayerPrefetcher")
