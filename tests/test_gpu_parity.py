@@ -87,6 +87,7 @@ SMALL = dict(Hq=8, Hkv=2, D=128, dtype="bf16", ctx=[1000], B=16, M=24, tree="bou
     (dict(M=100, tree="uniform", Hq=10, Hkv=2), "M=100 G=5"),
     (dict(ctx=[100], k=20), "context shorter than the budget: every block kept"),
     (dict(ctx=[640, 1000, 48, 333], rho=[0.1] * 4), "ragged batch of 4"),
+    (dict(ctx=[0, 500], rho=[0.1] * 2), "batch with an empty context (only the draft tokens to attend to)"),
     (dict(Hq=16, Hkv=1), "G=16"),
     (dict(B=7, ctx=[500], ns=3, nr=5, k=11), "odd block size 7"),
 ])
