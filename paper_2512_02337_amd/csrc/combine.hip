@@ -39,7 +39,7 @@ __device__ __forceinline__ float wave_max_u(float x)
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(64) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
+__global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
                                                      const float *a_pml, int a_M, int a_Hq, int a_G, int a_nsplit,
                                                      Shape s, Partials part, void *out, float *lse, float scale_log2)
 {
@@ -47,8 +47,9 @@ __global__ __launch_bounds__(64) void combine_kernel(const int32_t *a_parent, co
     s.parent = a_parent; s.q = a_q; s.M = a_M; s.Hq = a_Hq; s.G = a_G;
     part.o = const_cast<float *>(a_po); part.ml = const_cast<float *>(a_pml); part.nsplit = a_nsplit;
     constexpr int DPL = D / 64;   // channels per lane: d = lane + 64 * x
-    const int lane = threadIdx.x;
-    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z, g = h / s.G;
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.y, b = blockIdx.z, j = blockIdx.x;
+    const int h = g * s.G + (int)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // one wavefront per query head of the KV group
 
     // ---- every read whose address is known from the arguments goes out first ----------
     const int32_t *par = s.parent + (int64_t)b * s.M;
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(64) void combine_kernel(const int32_t *a_parent, co
 
 hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st)
 {
-    dim3 grid(s.M, s.Hq, s.batch), block(64);
+    dim3 grid(s.M, s.Hkv, s.batch), block(64 * s.G);
     const float scale_log2 = kLog2e / sqrtf((float)s.D);
 #define SPECPV_LAUNCH(T, DD) \
     hipLaunchKernelGGL((combine_kernel<T, DD>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
