@@ -29,10 +29,10 @@
 // Epilogue: the four token groups merge their (O, m, l) through LDS and write one
 // split-KV partial per (head, split, node); combine.hip finishes.
 //
-// Two kernels share this decomposition.  attn_ctx_mfma_kernel (above description) is
-// used when a wavefront has only a few chunks to go through (the partial verification
-// over a 4K-token cache); attn_ctx_mfma_wide_kernel, further down, when it has many
-// (full verification of a long context).
+// attn_ctx_mfma_kernel (above description) is used when a wavefront has only a few chunks to go
+// through (the partial verification over a 4K-token cache); attn_ctx_mfma_group_kernel, further
+// down, when it has many (full verification of a long context): there a workgroup serves all
+// query heads of a KV head.
 #include "internal.h"
 
 namespace specpv {
@@ -53,7 +53,6 @@ constexpr int kVPiecePitch = 1088;
 constexpr int kStageBytes = 8192 + 8 * kVPiecePitch;
 constexpr int kStages = 2;           // ring depth per wavefront
 constexpr int kRingBytes = 4 * kStages * kStageBytes;
-constexpr int kWideStageBytes = kStageBytes;
 constexpr int kKvAux = 2;
 constexpr float kRescaleSlack = 8.f; // the reference max may lag the true max by 2^8
 
@@ -80,6 +79,7 @@ struct MfmaArgs {
     int n_sel;
     float scale_log2;
     int n_units, row_tiles;
+    int rph, n_row_blocks;   // group kernel: 32-row blocks per query head, and per KV group (G * rph)
     FastDiv div_nsplit, div_hkv, div_B, div_W;
 };
 
@@ -576,455 +576,64 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     }
 }
 
-// acc *= alpha for a 32x32 accumulator tile that lives in accumulation registers, without
-// giving the compiler a reason to keep a copy of the tile in vector registers (it would do
-// that on every iteration, for this rarely taken path).  The waits cover the distance that
-// the hardware needs between an MFMA writing the tile and these reads, and between these
-// writes and the next MFMA reading it; the compiler cannot see into the block.
-__device__ __forceinline__ void scale_acc_tile(f32x16 &acc, float alpha)
-{
-    float e[16];
-#pragma unroll
-    for (int x = 0; x < 16; ++x) e[x] = acc[x];
-    float t;
-    asm volatile(
-        "s_nop 15\n\ts_nop 15\n\t"
-        "v_accvgpr_read_b32 %16, %0\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %0, %16\n\t"
-        "v_accvgpr_read_b32 %16, %1\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %1, %16\n\t"
-        "v_accvgpr_read_b32 %16, %2\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %2, %16\n\t"
-        "v_accvgpr_read_b32 %16, %3\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %3, %16\n\t"
-        "v_accvgpr_read_b32 %16, %4\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %4, %16\n\t"
-        "v_accvgpr_read_b32 %16, %5\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %5, %16\n\t"
-        "v_accvgpr_read_b32 %16, %6\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %6, %16\n\t"
-        "v_accvgpr_read_b32 %16, %7\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %7, %16\n\t"
-        "v_accvgpr_read_b32 %16, %8\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %8, %16\n\t"
-        "v_accvgpr_read_b32 %16, %9\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %9, %16\n\t"
-        "v_accvgpr_read_b32 %16, %10\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %10, %16\n\t"
-        "v_accvgpr_read_b32 %16, %11\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %11, %16\n\t"
-        "v_accvgpr_read_b32 %16, %12\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %12, %16\n\t"
-        "v_accvgpr_read_b32 %16, %13\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %13, %16\n\t"
-        "v_accvgpr_read_b32 %16, %14\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %14, %16\n\t"
-        "v_accvgpr_read_b32 %16, %15\n\tv_mul_f32 %16, %16, %17\n\tv_accvgpr_write_b32 %15, %16\n\t"
-        "s_nop 4"
-        : "+a"(e[0]), "+a"(e[1]), "+a"(e[2]), "+a"(e[3]), "+a"(e[4]), "+a"(e[5]), "+a"(e[6]), "+a"(e[7]),
-          "+a"(e[8]), "+a"(e[9]), "+a"(e[10]), "+a"(e[11]), "+a"(e[12]), "+a"(e[13]), "+a"(e[14]), "+a"(e[15]),
-          "=&v"(t)
-        : "v"(alpha));
-#pragma unroll
-    for (int x = 0; x < 16; ++x) acc[x] = e[x];
-}
-
-// ---- wide variant: one wavefront per SIMD, 64 rows per wavefront ---------------------------
-// Same decomposition over workgroups and the same partials as attn_ctx_mfma_kernel, but a
-// workgroup is 4 wavefronts (one per SIMD, up to 512 registers each) and every wavefront
-// owns its chunks alone: it requests K and V of a chunk into its private LDS ring (16 DMA
-// operations), reads the fragments once and uses them for both 32-row blocks of the tile.
-// No wavefront ever touches another one's ring, so the main loop has no barrier at all,
-// the LDS traffic per MFMA halves, and the two row blocks give the scheduler independent
-// MFMA and softmax work to overlap inside one wavefront.
-template <bool ALIGNED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void attn_ctx_mfma_wide_kernel(Shape s, Partials part, MfmaArgs a)
-{
-    extern __shared__ char lds_raw[];
-    float *ms = (float *)lds_raw;            // [4 token groups][64 rows]
-    float *ls = ms + 4 * 64;                 // [4][64]
-    char *ring = lds_raw + 2048;             // [4 wavefronts][kStages][K 8 KiB | V 8 pieces of 1088 B]
-    float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
-
-    const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
-    const int u = blockIdx.y * 8 + xcd;
-    if (u >= a.n_units) return;
-    const int bg = (int)a.div_nsplit.div((uint32_t)u);
-    const int sp = u - bg * part.nsplit;
-    const int b = (int)a.div_hkv.div((uint32_t)bg);
-    const int g = bg - b * s.Hkv;
-    const int rt = r >= s.G ? 1 : 0;
-    const int hh = r - rt * s.G;
-    const int h = g * s.G + hh;
-    const int m0 = rt * 64;
-
-    const int lane = threadIdx.x & 63;
-    const int tg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // token group = wavefront
-    const int n = lane & 31, kg = lane >> 5;
-
-    const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
-    const int W = part.nsplit * 4, wsid = sp * 4 + tg;
-    const uint32_t Bu = (uint32_t)s.B;
-    const int L = s.ctx_len[b];
-    const int cnt_raw = sel ? a.sel_count[bg] : 0;
-    auto first_chunk = [&](uint32_t chunks, int w) -> int {
-        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
-        return (int)((uint32_t)w * base + min((uint32_t)w, rem));
-    };
-    int spec_slot = 0, spec_vec = 0;
-    if (ALIGNED && sel) {
-        const uint32_t Cspec = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
-        spec_slot = (int)a.div_B.div((uint32_t)first_chunk(Cspec, wsid) * 32u);
-        const int x = spec_slot + lane;
-        spec_vec = x < a.n_sel ? sel[x] : -1;
-    }
-    uint4 qraw[2][8];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
-        const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qraw[rb][ks] = *(const uint4 *)(qrow + ks * 16);
-    }
-
-    int nb = L > 0 ? (int)a.div_B.div((uint32_t)(L + s.B - 1)) : 0;
-    if (nb > s.max_blocks) nb = s.max_blocks;
-    int cnt = nb;
-    if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
-    const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;
-    const uint32_t C = (T + 31u) >> 5;
-    const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
-    const int nch = c1 - c0;
-
-    const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
-    const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
-    const uint32_t st2 = (uint32_t)s.st * 2u;
-
-    char *my_ring = ring + tg * (kStages * kWideStageBytes);
-    int slot_base = 0, blkvec = 0;
-    auto refill = [&](int slot) {
-        slot_base = slot;
-        const int x = slot + lane;
-        blkvec = (sel && x < cnt) ? sel[x] : x;
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): inside the rare branch, see attn_ctx_mfma_kernel
-    };
-    auto chunk_row0 = [&](int ci) -> int {
-        const uint32_t p0 = (uint32_t)(c0 + ci) * 32u;
-        const uint32_t slot = a.div_B.div(p0);
-        if ((int)slot - slot_base >= 64) refill((int)slot);
-        const int blk = __builtin_amdgcn_readlane(blkvec, (int)slot - slot_base);
-        if (blk < 0 || blk >= nb) return -1;
-        return blk * s.B + (int)(p0 - slot * Bu);
-    };
-    auto lane_row = [&](int ci) -> int {
-        const uint32_t p = (uint32_t)(c0 + ci) * 32u + (uint32_t)n;
-        if (p >= T) return -1;
-        const uint32_t slot = a.div_B.div(p);
-        const int blk = sel ? sel[slot] : (int)slot;
-        if (blk < 0 || blk >= nb) return -1;
-        const int tok = blk * s.B + (int)(p - slot * Bu);
-        return tok < L ? tok : -1;
-    };
-
-    uint32_t vmask_st[kStages];
-
-    // Request chunk ci: 16 DMA operations of 1 KiB (one 256-byte row per 16 lanes).  K: operation
-    // i brings rows 4i .. 4i+3, pieces swizzled by row & 7.  V: operation i brings rows i, i+8,
-    // i+16, i+24 into piece i.
-    auto issue = [&](int ci) {
-        const int stg = ci & (kStages - 1);
-        int tok;
-        if (ALIGNED) {
-            const int r0 = chunk_row0(ci);
-            tok = (r0 >= 0 && r0 + n < L) ? r0 + n : -1;
-        } else {
-            tok = lane_row(ci);
-        }
-        const uint32_t vm = (uint32_t)__ballot(tok >= 0);
-        const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
-        vmask_st[stg] = vm;
-        const int r4 = lane >> 4, pos = lane & 15;
-        const uint32_t ksw_even = 16u * (uint32_t)(pos ^ r4), ksw_odd = ksw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-        char *dst = my_ring + stg * kWideStageBytes;
-        char *dstv = dst + 8192;
-        if (ALIGNED && vm == 0xffffffffu) {
-            const uint32_t t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)tk);
-            const size_t row0 = (size_t)t0 * st2;
-            const uint32_t lane_row_off = (uint32_t)r4 * st2;
-            if (st2 == 256u) {
-                // rows are 256 bytes apart (the usual head-major cache): the instruction's
-                // immediate offset, added to the global and to the LDS address, covers the step
-                // between consecutive operations (K: 1 KiB on both sides; V: 256 bytes, with the
-                // LDS base adjusted for the rest of the piece pitch)
-                dma16x4(kb + row0, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst);
-                dma16x4(kb + row0 + 4096, lane_row_off + ksw_even, lane_row_off + ksw_odd, dst + 4096);
-                const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
-#define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, kKvAux)
-                SPECPV_VOP(0); SPECPV_VOP(1); SPECPV_VOP(2); SPECPV_VOP(3);
-                SPECPV_VOP(4); SPECPV_VOP(5); SPECPV_VOP(6); SPECPV_VOP(7);
-#undef SPECPV_VOP
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    dma16(vb + row0 + (size_t)(8 * r4 + i) * st2 + vsw, dstv + i * kVPiecePitch);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
-                dma16(kb + (tv + ((i & 1) ? ksw_odd : ksw_even)), dst + i * 1024);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * st2;
-                dma16(vb + (tv + vsw), dstv + i * kVPiecePitch);
-            }
-        }
-    };
-
-    if (ALIGNED && nch > 0) {
-        const int slot0 = (int)a.div_B.div((uint32_t)c0 * 32u);
-        if (sel && slot0 == spec_slot) { slot_base = slot0; blkvec = spec_vec; }
-        else refill(slot0);
-    }
-    // every load above is complete from here on (an instruction the compiler knows, see
-    // attn_ctx_mfma_kernel): only this wavefront's DMA groups (16 operations each) are in flight
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    asm volatile("" ::: "memory");
-
-    f32x16 O[2][4];
-    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[rb][j][i] = 0.f;
-
-    // K / V fragments of one chunk, as the MFMAs want them.  V (the A operand of O^T += V^T . P^T)
-    // needs, per lane, 8 tokens of ONE channel, while memory and LDS hold 128 channels of one
-    // token contiguously: the transposing LDS read (ds_read_b64_tr_b16) does that exchange
-    // inside groups of 16 lanes.  Lane s of a group reads 8 bytes (4 channels) and receives,
-    // as lane 4a + c of the group, element c of what lanes a, a+4, a+8, a+12 read.  With lane
-    // s reading token (s >> 2) of a token quad and channels 4 * (s & 3) .. +3 of a 16-channel
-    // group, every lane ends up with the four tokens of the quad for channel (lane & 15) of
-    // the group: lane m = lane & 31 holds channel 32j + m of tile j, its k-group the tokens
-    // 16*ks2 + 8*hf + 4*kg + 0..3.  The four token rows of a quad sit in four different V
-    // pieces, 1088 bytes apart, i.e. 64 bytes apart modulo the bank cycle: no bank conflicts.
-    struct Frags { uint4 k[8]; uint2 v[16]; uint32_t vmask; };
-    const char *kptr = my_ring + n * 256;
-    uint32_t koff[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) koff[ks] = ((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u));
-    const char *vptr;
-    {
-        const int s16 = lane & 15, grp = lane >> 4;
-        vptr = my_ring + 8192 + (4 * kg + (s16 >> 2)) * kVPiecePitch + 32 * (grp & 1) + 8 * (s16 & 3);
-    }
-    // Plain LDS loads: the compiler tracks when they arrive, so they can stay in flight
-    // behind the arithmetic of the previous chunk.
-    auto read_frags = [&](int ci, Frags &f) {
-        const int stg = ci & 1;
-        f.vmask = vmask_st[stg];
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) f.k[ks] = *(const uint4 *)(kptr + stg * kWideStageBytes + koff[ks]);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            // e = (ks2 * 4 + j) * 2 + hf: token quad 16*ks2 + 8*hf (+ 4*kg) is rows 2*ks2 + hf of the pieces
-            const int hf = e & 1, j = (e >> 1) & 3, ks2 = e >> 3;
-            typedef short v4s __attribute__((ext_vector_type(4)));
-            const v4s t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) v4s *)(vptr + stg * kWideStageBytes + (2 * ks2 + hf) * 256 + 64 * j));
-            f.v[e] = __builtin_bit_cast(uint2, t);
-        }
-    };
-    // every register of f has arrived (the compiler places the wait); nothing is emitted
-    auto settle = [&](const Frags &f) {
-#define SPECPV_K(i) "v"(__builtin_bit_cast(u32x4, f.k[i]))
-#define SPECPV_V(i) "v"(__builtin_bit_cast(u32x2, f.v[i]))
-        asm volatile("" ::SPECPV_K(0), SPECPV_K(1), SPECPV_K(2), SPECPV_K(3), SPECPV_K(4), SPECPV_K(5), SPECPV_K(6), SPECPV_K(7));
-        asm volatile("" ::SPECPV_V(0), SPECPV_V(1), SPECPV_V(2), SPECPV_V(3), SPECPV_V(4), SPECPV_V(5), SPECPV_V(6), SPECPV_V(7),
-                     SPECPV_V(8), SPECPV_V(9), SPECPV_V(10), SPECPV_V(11), SPECPV_V(12), SPECPV_V(13), SPECPV_V(14), SPECPV_V(15));
-#undef SPECPV_K
-#undef SPECPV_V
-    };
-    // The arithmetic of one chunk for both 32-row blocks.
-    auto compute = [&](const Frags &f) {
-        // V^T operands: channels 32j + (lane & 31), tokens as above
-        uint4 vt[2][4];
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint2 lo = f.v[(ks2 * 4 + j) * 2], hi = f.v[(ks2 * 4 + j) * 2 + 1];
-                vt[ks2][j] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-            }
-        const uint32_t vmask = f.vmask;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            f32x16 S;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) S[x] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f.k[ks]), as_bf16x8(qraw[rb][ks]), S, 0, 0, 0);
-            float sv[16];
-#pragma unroll
-            for (int x = 0; x < 16; ++x) sv[x] = S[x];
-            if (vmask != 0xffffffffu) {
-#pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
-                    if (!((vmask >> tt) & 1u)) sv[x] = -INFINITY;
-                }
-            }
-            float mx = fmaxf(sv[0], sv[1]);
-#pragma unroll
-            for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, sv[x]), sv[x + 1]);
-            mx = max_xor32(mx) * a.scale_log2;
-            if (__any(mx > m_ref[rb] + kRescaleSlack)) {
-                const float m_new = mx > m_ref[rb] + kRescaleSlack ? mx : m_ref[rb];
-                const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref[rb] - m_new);
-                m_ref[rb] = m_new;
-                l_run[rb] *= alpha;
-                if (__any(alpha != 1.f && l_run[rb] != 0.f)) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) scale_acc_tile(O[rb][j], alpha);
-                }
-            }
-            const float m_use = m_ref[rb] == -INFINITY ? 0.f : m_ref[rb];
-            uint32_t pk[8];
-            float lsum = 0.f;
-#pragma unroll
-            for (int x = 0; x < 16; x += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[x], a.scale_log2, -m_use));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[x + 1], a.scale_log2, -m_use));
-                pk[x >> 1] = pack_bf16x2(p0, p1);
-                lsum = add_bf16x2(pk[x >> 1], lsum);
-            }
-            l_run[rb] += lsum;
-            const uint4 pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]), pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-#pragma unroll
-            for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    O[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt[ks2][j]), as_bf16x8(ks2 ? pf1 : pf0), O[rb][j], 0, 0, 0);
-        }
-    };
-    if (nch > 0) issue(0);
-    if (nch > 1) issue(1);
-    {
-        Frags fa;
-        for (int i = 0; i < nch; ++i) {
-            if (i + 1 < nch) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            read_frags(i, fa);
-            if (i + 2 < nch) { settle(fa); issue(i + 2); }
-            compute(fa);
-        }
-    }
-    __syncthreads();   // every wavefront is done with its ring: the epilogue reuses that LDS
-
-    // ---- merge the four token groups ---------------------------------------------------
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const float lr = sum_xor32(l_run[rb]);
-        const int row = rb * 32 + n;
-        if (kg == 0) {
-            ms[tg * 64 + row] = m_ref[rb];
-            ls[tg * 64 + row] = lr;
-        }
-        // accumulator element 4q + x of tile j is channel 32j + 8q + 4kg + x of this lane's row
-        float *dst = obuf + ((size_t)tg * 64 + row) * kOPitch;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) =
-                    make_float4(O[rb][j][4 * q], O[rb][j][4 * q + 1], O[rb][j][4 * q + 2], O[rb][j][4 * q + 3]);
-    }
-    __syncthreads();
-    constexpr int RPW = 16;  // rows each wavefront finishes
-    const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
-    float wgt[4], m_row = -INFINITY, l_row = 0.f;
-    {
-        const int row = tg * RPW + (lane & (RPW - 1));
-        float mw[4];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) { mw[w] = ms[w * 64 + row]; m_row = fmaxf(m_row, mw[w]); }
-        const float m_use = m_row == -INFINITY ? 0.f : m_row;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            wgt[w] = __builtin_amdgcn_exp2f(mw[w] - m_use);
-            l_row = fmaf(ls[w * 64 + row], wgt[w], l_row);
-        }
-    }
-#pragma unroll
-    for (int u0 = 0; u0 < RPW; u0 += 8) {
-        float2 acc[8];
-#pragma unroll
-        for (int uu = 0; uu < 8; ++uu) {
-            const int row = tg * RPW + u0 + uu;
-            acc[uu] = make_float2(0.f, 0.f);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float ww = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt[w]), u0 + uu));
-                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + 2 * lane);
-                acc[uu].x = fmaf(ww, x.x, acc[uu].x);
-                acc[uu].y = fmaf(ww, x.y, acc[uu].y);
-            }
-        }
-#pragma unroll
-        for (int uu = 0; uu < 8; ++uu) {
-            const int j = m0 + tg * RPW + u0 + uu;
-            if (j < s.M) store_partial(part.o + (prow0 + j) * 128 + 2 * lane, acc[uu]);
-        }
-    }
-    if (lane < RPW) {
-        const int j = m0 + tg * RPW + lane;
-        if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
-    }
-}
-
-// ---- group variant: the four query heads of a KV head in one workgroup ----------------------
-// For long token ranges and G = 4.  A workgroup owns (sequence, KV head, 64-node row tile, KV
-// split) and walks the split's chunks once for all four query heads: wavefront w takes head
-// (w & 3) and rows 32 * (w >> 2) .. +31 of the tile.  The eight wavefronts share ONE ring of
-// four stages; each brings 2 of a chunk's 16 DMA operations (first four wavefronts: K rows,
-// last four: V rows), so every K / V byte is requested from memory exactly once per row tile,
-// whatever the caches do.  Chunks are requested three ahead of the arithmetic (measured: two is
-// slightly slower, four and six are no faster).  One workgroup barrier per chunk: past the
-// barrier of chunk i every part of chunk i has landed, and every wavefront has finished reading
-// chunk i - 1, whose stage is the one that chunk i + 3 is then requested into.
+// ---- group variant: the query heads of a KV head in one workgroup --------------------------
+// For long token ranges.  The G x ceil(M / 32) blocks of 32 query rows that share a KV head are
+// dealt to workgroups of up to 8 wavefronts, one row block per wavefront (G = 4, M <= 64: one
+// workgroup of 8; G = 5: two workgroups of 5).  A workgroup owns (sequence, KV head, its row
+// blocks, KV split) and walks the split's chunks once for all of them: its W wavefronts share
+// ONE ring of four stages and each brings its share of a chunk's 16 DMA operations, so every
+// K / V byte is requested from memory exactly once per workgroup, whatever the caches do.
+// Chunks are requested three ahead of the arithmetic (measured: two is slightly slower, four
+// and six are no faster).  One workgroup barrier per chunk: past the barrier of chunk i every
+// part of chunk i has landed, and every wavefront has finished reading chunk i - 1, whose stage
+// is the one that chunk i + 3 is then requested into.
 // A wavefront keeps its rows to itself over the whole split, so the epilogue has nothing to
 // merge: it only turns the accumulators into row-major partials.
 constexpr int kGroupStages = 4;   // a power of two
 constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
 
-template <bool ALIGNED>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <bool ALIGNED, int W>   // W wavefronts per workgroup: 2, 4, 6 or 8
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 {
     extern __shared__ char lds_raw[];
     char *ring = lds_raw;                  // [kGroupStages][K 8 KiB | V 8 pieces of 1088 B]
-    float *obuf = (float *)lds_raw;        // [8 wavefronts][32 rows][kOPitch], reuses the ring after the main loop
+    float *obuf = (float *)lds_raw;        // [W wavefronts][32 rows][kOPitch], reuses the ring after the main loop
 
-    const int xcd = blockIdx.x & 7, rt = blockIdx.x >> 3;
+    const int xcd = blockIdx.x & 7, wg_part = blockIdx.x >> 3;
     const int u = blockIdx.y * 8 + xcd;
     if (u >= a.n_units) return;
     const int bg = (int)a.div_nsplit.div((uint32_t)u);
     const int sp = u - bg * part.nsplit;
     const int b = (int)a.div_hkv.div((uint32_t)bg);
     const int g = bg - b * s.Hkv;
-    const int m0 = rt * 64;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int hh = wave & 3, rb = wave >> 2;
-    const int h = g * 4 + hh;                 // the host only launches this kernel for G == 4
+    // this wavefront's row block: head hh of the KV group, rows m0 .. m0 + 31 of the tree.  A
+    // workgroup may have a wavefront too many (row block counts that do not divide): it brings
+    // its share of the chunks and keeps the barriers, but computes and stores nothing.
+    const int rbx = wg_part * W + wave;
+    const bool live = rbx < a.n_row_blocks;
+    const int rbx_c = live ? rbx : a.n_row_blocks - 1;
+    const int hh = rbx_c / a.rph;
+    const int m0 = (rbx_c - hh * a.rph) * 32;
+    const int h = g * s.G + hh;
+    const bool second = wave >= 4;            // the second wavefront of its SIMD (wavefronts w and w + 4 share one)
     const int n = lane & 31, kg = lane >> 5;
 
     const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
-    const int W = part.nsplit;                // div_W divides by the number of splits here
+    const int NS = part.nsplit;               // div_W divides by the number of splits here
     const uint32_t Bu = (uint32_t)s.B;
     const int L = s.ctx_len[b];
     const int cnt_raw = sel ? a.sel_count[bg] : 0;
     auto first_chunk = [&](uint32_t chunks, int w) -> int {
-        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
+        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)NS;
         return (int)((uint32_t)w * base + min((uint32_t)w, rem));
     };
     uint4 qraw[8];
     {
-        const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
+        const int j = min(m0 + n, s.M - 1);   // rows past M repeat row M-1; never stored
         const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qraw[ks] = *(const uint4 *)(qrow + ks * 16);
@@ -1037,7 +646,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;
     const uint32_t C = (T + 31u) >> 5;
     const int c0 = first_chunk(C, sp), c1 = first_chunk(C, sp + 1);
-    const int nch = c1 - c0;                  // the same for all eight wavefronts: the barriers match up
+    const int nch = c1 - c0;                  // the same for all wavefronts: the barriers match up
 
     const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
     const char *vb = (const char *)s.v + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
@@ -1087,27 +696,29 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         return tok < L ? tok : -1;
     };
 
-    // Request this wavefront's two operations of chunk ci into stage stg (1 KiB each, one 256-byte
-    // row per 16 lanes).  rb == 0: K operations i0, i0 + 1 (operation i brings rows 4i .. 4i+3,
-    // pieces swizzled by row & 7); rb == 1: V operations i0, i0 + 1 (operation i brings rows i,
-    // i+8, i+16, i+24 into piece i).  Returns the validity bits of the chunk's 32 tokens.
-    // Everything that depends on the role of the wavefront is folded into a few registers up
-    // front, so that the common path is straight-line code.
-    const int i0 = 2 * hh;
+    // Request this wavefront's operations of chunk ci into stage stg (1 KiB each, one 256-byte row
+    // per 16 lanes).  A chunk is 16 operations: K operation i (0 .. 7) brings rows 4i .. 4i+3, pieces
+    // swizzled by row & 7; V operation i brings rows i, i+8, i+16, i+24 into piece i.  Wavefront w
+    // takes operations w, w + W, w + 2W, ...  Returns the validity bits of the chunk's 32 tokens.
+    // Everything that depends on the wavefront is folded into a few registers up front, so that
+    // the common path is straight-line code.
+    constexpr int NOPS = (16 + W - 1) / W;
+    const int n_ops = (16 - wave + W - 1) / W;       // NOPS or NOPS - 1
     const int r4 = lane >> 4, pos = lane & 15;
     const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-    // per-lane byte offsets of the two operations relative to the chunk's first row (i0 is even:
-    // operation i0 takes the even swizzle, i0 + 1 the odd one)
-    const uint32_t lane_off0 = rb == 0 ? (uint32_t)(4 * i0 + r4) * st2 + sw_even : (uint32_t)(8 * r4 + i0) * st2 + vsw;
-    const uint32_t lane_off1 = rb == 0 ? (uint32_t)(4 * i0 + 4 + r4) * st2 + sw_odd : lane_off0 + st2;
-    const char *const src_base = rb == 0 ? kb : vb;
-    const char *const src_lane0 = src_base + lane_off0, *const src_lane1 = src_base + lane_off1;
-    const int dst_off0 = rb == 0 ? i0 * 1024 : 8192 + i0 * kVPiecePitch;
-    const int dst_off1 = dst_off0 + (rb == 0 ? 1024 : kVPiecePitch);
-    // the general path: source lanes of the two operations and the swizzles that go with them
-    const int shfl0 = rb == 0 ? 4 * i0 + r4 : 8 * r4 + i0;
-    const int shfl1 = rb == 0 ? shfl0 + 4 : shfl0 + 1;
-    const uint32_t gsw0 = rb == 0 ? sw_even : vsw, gsw1 = rb == 0 ? sw_odd : vsw;
+    const char *src_lane[NOPS];   // per operation: source of this lane relative to the chunk's first row
+    int dst_off[NOPS];            // ... and where it lands in the stage
+#pragma unroll
+    for (int t = 0; t < NOPS; ++t) {
+        const int o = min(wave + W * t, 15), i = o & 7;
+        if (o < 8) {
+            src_lane[t] = kb + ((uint32_t)(4 * i + r4) * st2 + ((i & 1) ? sw_odd : sw_even));
+            dst_off[t] = i * 1024;
+        } else {
+            src_lane[t] = vb + ((uint32_t)(8 * r4 + i) * st2 + vsw);
+            dst_off[t] = 8192 + i * kVPiecePitch;
+        }
+    }
     auto issue = [&](int ci, int stg) -> uint32_t {
         char *dst = ring + stg * kStageBytes;
         int tok;
@@ -1116,8 +727,10 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
             if (r0 >= 0) {
                 const uint32_t row_off = (uint32_t)r0 * st2;   // fits 32 bits (host-checked)
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane0 + row_off), (lds_void_ptr)(dst + dst_off0), 16, 0, kKvAux);
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane1 + row_off), (lds_void_ptr)(dst + dst_off1), 16, 0, kKvAux);
+#pragma unroll
+                for (int t = 0; t < NOPS; ++t)
+                    if (16 % W == 0 || t < NOPS - 1 || n_ops == NOPS)
+                        __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane[t] + row_off), (lds_void_ptr)(dst + dst_off[t]), 16, 0, kKvAux);
                 return 0xffffffffu;
             }
             const int rr = -2 - r0;   // r0 == -1 gives -1
@@ -1127,8 +740,18 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         }
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
-        dma16(src_base + ((uint32_t)__shfl((int)tk, shfl0) * st2 + gsw0), dst + dst_off0);
-        dma16(src_base + ((uint32_t)__shfl((int)tk, shfl1) * st2 + gsw1), dst + dst_off1);
+#pragma unroll
+        for (int t = 0; t < NOPS; ++t) {
+            if (16 % W != 0 && t == NOPS - 1 && n_ops != NOPS) continue;
+            const int o = wave + W * t, i = o & 7;
+            if (o < 8) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
+                dma16(kb + (tv + ((i & 1) ? sw_odd : sw_even)), dst + dst_off[t]);
+            } else {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * st2;
+                dma16(vb + (tv + vsw), dst + dst_off[t]);
+            }
+        }
         return vm;
     };
 
@@ -1136,7 +759,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
     if (ALIGNED && nch > 0) fill_rows(0);
-    // from here on only this wavefront's DMA groups (2 operations each) are in flight (an
+    // from here on only this wavefront's DMA groups (n_ops operations each) are in flight (an
     // instruction the compiler knows, see attn_ctx_mfma_kernel)
     __builtin_amdgcn_s_waitcnt(0x0F70);
     asm volatile("" ::: "memory");
@@ -1172,11 +795,12 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             }
     };
     for (int i = 0; i < nch; ++i) {
-        // own part of chunk i has landed: kGroupAhead - 1 younger groups of 2 operations may stay
-        // in flight (towards the end of the range there are fewer: wait for all, they are due anyway)
-        if (i + kGroupAhead - 1 < nch) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (kGroupAhead - 1)) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();   // ... and so have the other seven; chunk i-1 has been read by all
+        // own part of chunk i has landed: kGroupAhead - 1 younger groups of n_ops operations may
+        // stay in flight (towards the end of the range there are fewer: wait for all, they are due anyway)
+        if (i + kGroupAhead - 1 >= nch) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (n_ops == NOPS) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NOPS * (kGroupAhead - 1)) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NOPS - 1) * (kGroupAhead - 1)) : "memory");
+        __builtin_amdgcn_s_barrier();   // ... and so have the others'; chunk i-1 has been read by all
         if (i + kGroupAhead < nch) {
             const int is = (i + kGroupAhead) & (kGroupStages - 1);
             const uint32_t vm = issue(i + kGroupAhead, is);
@@ -1184,7 +808,8 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         }
         const int rs = i & (kGroupStages - 1);
         const uint32_t vmask = (uint32_t)__builtin_amdgcn_readlane((int)vmv, rs);
-        if (rb == 1 && i > 0) pv();   // chunk i - 1, before its V registers are overwritten
+        if (!live) continue;
+        if (second && i > 0) pv();   // chunk i - 1, before its V registers are overwritten
         uint4 kf[8];
         {
             const uint32_t soff = (uint32_t)rs * kStageBytes;
@@ -1236,10 +861,11 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         l_run += lsum;
         pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        if (rb == 0) pv();
+        if (!second) pv();
     }
-    if (rb == 1 && nch > 0) pv();
+    if (second && live && nch > 0) pv();
     __syncthreads();   // every wavefront is done with the ring: the epilogue reuses that LDS
+    if (!live) return;
 
     // ---- one partial per (head, split, node): accumulators -> row-major through LDS ------
     l_run = sum_xor32(l_run);
@@ -1254,7 +880,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
                 *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) = make_float4(O[j][4 * q], O[j][4 * q + 1], O[j][4 * q + 2], O[j][4 * q + 3]);
     }
     // a wavefront reads back only what it wrote itself: no barrier
-    const int jrow0 = m0 + rb * 32;
+    const int jrow0 = m0;
 #pragma unroll 8
     for (int uu = 0; uu < 32; ++uu) {
         const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
@@ -1270,29 +896,47 @@ bool attn_ctx_mfma_supported(const Shape &s, int dtype)
     return dtype == SPECPV_BF16 && s.D == 128 && s.st % 8 == 0 && span < ((int64_t)1 << 31);
 }
 
+// Row blocks of 32 query rows per KV group, and how the group kernel deals them to workgroups.
+struct GroupLayout {
+    int rph, n_row_blocks, parts, waves;
+};
+static GroupLayout group_layout(const Shape &s)
+{
+    GroupLayout g;
+    g.rph = (s.M + 31) / 32;
+    g.n_row_blocks = s.G * g.rph;
+    g.parts = (g.n_row_blocks + 7) / 8;
+    const int w = (g.n_row_blocks + g.parts - 1) / g.parts;   // 1 .. 8
+    g.waves = w <= 2 ? 2 : (w <= 4 ? 4 : (w <= 6 ? 6 : 8));
+    return g;
+}
+int attn_group_parts(const Shape &s) { return group_layout(s).parts; }
+
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
                                 int n_sel, Partials p, int kind, hipStream_t st)
 {
-    if (kind != kAttnSplit && kind != kAttnWide && kind != kAttnGroup) return hipErrorInvalidValue;
-    if (kind == kAttnGroup && s.G != 4) return hipErrorInvalidValue;
+    if (kind != kAttnSplit && kind != kAttnGroup) return hipErrorInvalidValue;
+    const GroupLayout gl = group_layout(s);
     MfmaArgs a;
     a.sel_idx = sel_idx;
     a.sel_count = sel_count;
     a.n_sel = n_sel;
     a.scale_log2 = kLog2e / sqrtf(128.f);
     a.row_tiles = (s.M + 63) / 64;
+    a.rph = gl.rph;
+    a.n_row_blocks = gl.n_row_blocks;
     a.n_units = s.batch * s.Hkv * p.nsplit;
     a.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
     a.div_hkv = make_fastdiv((uint32_t)s.Hkv);
     a.div_B = make_fastdiv((uint32_t)s.B);
     // token ranges per split: four (one per token group of a workgroup), or one in the group kernel
     a.div_W = make_fastdiv((uint32_t)p.nsplit * (kind == kAttnGroup ? 1u : 4u));
-    const int GR = (kind == kAttnGroup ? 1 : s.G) * a.row_tiles;
+    const int GR = kind == kAttnGroup ? gl.parts : s.G * a.row_tiles;
     const dim3 grid(8 * GR, (a.n_units + 7) / 8);
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool aligned = s.B % 32 == 0;
     const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
-    const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, 8 * 32 * kOPitch * (int)sizeof(float));
+    const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, gl.waves * 32 * kOPitch * (int)sizeof(float));
 #define SPECPV_LAUNCH(KERN, THREADS, LDS)                                                              \
     do {                                                                                               \
         static bool attr_set = false;                                                                  \
@@ -1304,16 +948,23 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
         }                                                                                              \
         hipLaunchKernelGGL(kern, grid, dim3(THREADS), LDS, st, s, p, a);                                \
     } while (0)
+#define SPECPV_LAUNCH_GROUP(WW)                                                                        \
+    do {                                                                                               \
+        if (aligned) SPECPV_LAUNCH((attn_ctx_mfma_group_kernel<true, WW>), 64 * WW, lds_group);         \
+        else SPECPV_LAUNCH((attn_ctx_mfma_group_kernel<false, WW>), 64 * WW, lds_group);                \
+    } while (0)
     if (kind == kAttnGroup) {
-        if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_group_kernel<true>, 512, lds_group);
-        else SPECPV_LAUNCH(attn_ctx_mfma_group_kernel<false>, 512, lds_group);
-    } else if (kind == kAttnWide) {
-        if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_wide_kernel<true>, 256, lds_split);
-        else SPECPV_LAUNCH(attn_ctx_mfma_wide_kernel<false>, 256, lds_split);
+        switch (gl.waves) {
+        case 2: SPECPV_LAUNCH_GROUP(2); break;
+        case 4: SPECPV_LAUNCH_GROUP(4); break;
+        case 6: SPECPV_LAUNCH_GROUP(6); break;
+        default: SPECPV_LAUNCH_GROUP(8); break;
+        }
     } else {
         if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_kernel<true>, 512, lds_split);
         else SPECPV_LAUNCH(attn_ctx_mfma_kernel<false>, 512, lds_split);
     }
+#undef SPECPV_LAUNCH_GROUP
 #undef SPECPV_LAUNCH
     return hipGetLastError();
 }

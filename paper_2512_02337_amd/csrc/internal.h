@@ -103,16 +103,18 @@ hipError_t launch_attn_ctx_generic(const Shape &s, int dtype, const int32_t *sel
                                    const int32_t *sel_count, int n_sel, Partials p, hipStream_t st);
 bool attn_ctx_mfma_supported(const Shape &s, int dtype);
 // Which kernel computes the context part, and with how many KV splits.  kAttnSplit: eight
-// wavefronts per (query head, split), for short token ranges; kAttnWide: four wavefronts of 64
-// rows per (query head, split), for long ranges; kAttnGroup: the four query heads of a KV head
-// in one workgroup (G == 4 only), for long ranges; kAttnGeneric: any dtype / head dim.
-enum AttnKind { kAttnGeneric = 0, kAttnSplit = 1, kAttnWide = 2, kAttnGroup = 3 };
+// wavefronts per (query head, split), for short token ranges; kAttnGroup: the query heads of a KV
+// head in one workgroup (two or more for more than eight 32-row blocks), for long ranges;
+// kAttnGeneric: any dtype / head dim.
+enum AttnKind { kAttnGeneric = 0, kAttnSplit = 1, kAttnGroup = 3 };
 struct AttnPlan {
     int nsplit;
     int kind;
 };
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
                                 int n_sel, Partials p, int kind, hipStream_t st);
+// workgroups per (sequence, KV head, split) of the kAttnGroup kernel
+int attn_group_parts(const Shape &s);
 hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st);
 // to_cache != 0: pending + accepted rows go to the cache tail (lengths, summaries updated);
 // otherwise the accepted rows join the pending rows of the buffer.  old_len: [batch] scratch.

@@ -123,12 +123,15 @@ def test_shapes_and_edges(gpu_lib, over, tag):
     (dict(ctx=[34816], B=64, M=30, Hq=10, Hkv=2), "G=5"),
     (dict(ctx=[35000], B=16, M=70, Hq=10, Hkv=2, tree="uniform"), "G=5, two row tiles, block 16"),
     (dict(ctx=[40000], B=64, M=9, Hq=2, Hkv=2), "G=1"),
+    (dict(ctx=[33000], B=64, M=40, Hq=4, Hkv=2), "G=2, four wavefronts"),
+    (dict(ctx=[36864], B=64, M=60, Hq=16, Hkv=2), "G=8, two workgroups of eight"),
+    (dict(ctx=[34000], B=16, M=50, Hq=6, Hkv=2, tree="uniform"), "G=3, six wavefronts, block 16"),
 ])
-def test_long_ranges_take_the_many_chunk_kernels(gpu_lib, over, tag):
+def test_long_ranges_take_the_group_kernel(gpu_lib, over, tag):
     """Full verification over tens of thousands of tokens at small head counts: each wavefront
-    gets eight or more chunks, which selects the kernel with the four query heads of a KV head in
-    one workgroup (G = 4) or the one-wavefront-per-SIMD kernel (other G); head-major (256-byte
-    row stride: grouped DMA path) and token-major (general path) layouts."""
+    gets eight or more chunks, which selects the kernel that serves all query heads of a KV head
+    from one workgroup: 8 wavefronts at G = 4, 6 (one idle) at G = 5, two workgroups for two row
+    tiles, 2 (one idle) at G = 1; head-major (256-byte row stride) and token-major layouts."""
     say("case", tag)
     cfg = dict(SMALL); cfg.update(over)
     case = workloads.to_device(workloads.make_case(cfg, seed=17), "cuda")
