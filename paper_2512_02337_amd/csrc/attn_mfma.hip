@@ -8,10 +8,9 @@
 // a pair taking 32 rows of the tile each.  Nothing is gathered: K and V rows go
 // from their place in the cache straight into a small per-pair LDS ring by LDS-DMA
 // (global_load_lds), two chunks ahead of the arithmetic, and from there into MFMA
-// operand registers.  The G query heads of a
-// KV head that read the same split are placed on one XCD, next to each other in
-// dispatch order, so that the split's K/V bytes come from HBM once and from that
-// XCD's L2 afterwards.
+// operand registers.  The G query heads of a KV head that read the same split are
+// placed on one XCD, next to each other in dispatch order, so that the split's K/V
+// bytes come from HBM once and from that XCD's L2 afterwards.
 //
 // Per chunk (v_mfma_f32_32x32x16_bf16, fp32 accumulate):
 //   S^T = K . Q^T     tokens are the M index, query rows the N index, so each
@@ -51,8 +50,11 @@ constexpr int kOPitch = 132;         // floats per staged output row (128 + 4: c
 // the transposing LDS reads (see lds_read_v).
 constexpr int kVPiecePitch = 1088;
 constexpr int kStageBytes = 8192 + 8 * kVPiecePitch;
-constexpr int kStages = 2;           // ring depth per wavefront
+constexpr int kStages = 2;           // ring depth per wavefront pair (eight-wavefront kernel)
 constexpr int kRingBytes = 4 * kStages * kStageBytes;
+// Cache policy of the K / V requests: 2 = the streaming hint (nt).  K / V rows are used once per
+// workgroup; with the hint the requests are served faster, and the sharing of a KV head's rows
+// between its query heads' workgroups through L2 is unaffected (same fetch counters).
 constexpr int kKvAux = 2;
 constexpr float kRescaleSlack = 8.f; // the reference max may lag the true max by 2^8
 
