@@ -78,6 +78,10 @@ def test_llama8b_128k_partial_step(gpu_lib, layer):
     got_idx, got_cnt = run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy()
     exact = check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "128k lists")
     say("   kept lists bit-exact:", exact)
+    if layer == 0:
+        # the full verification itself at 128K (the launch configuration bench.py times for the refresh)
+        qh, O, lse = _oracle_attention_on_heads(case, 0, [6])
+        _compare(run, case, 0, qh, O, lse, "full verification at 128K, KV head 6")
     run.out.zero_()
     run.attend()
     torch.cuda.synchronize()
