@@ -124,11 +124,14 @@ def test_qwen14b_ragged_batch(gpu_lib):
     for b in range(case["batch"]):
         qh, O, lse = _oracle_attention_on_heads(case, b, [(2 * b + 1) % 8], lists[b])
         _compare(run, case, b, qh, O, lse, "seq %d partial" % b)
-    # full verification of the shortest and the longest sequence is covered by the refresh call
+    # full verification of the shortest and of the longest sequence (G = 5: two workgroups of five
+    # wavefronts per KV head and split, many splits because the lengths differ)
     run.refresh(stale=-1)
     torch.cuda.synchronize()
     qh, O, lse = _oracle_attention_on_heads(case, 0, [3])
     _compare(run, case, 0, qh, O, lse, "seq 0 full")
+    qh, O, lse = _oracle_attention_on_heads(case, 3, [6])
+    _compare(run, case, 3, qh, O, lse, "seq 3 (the longest) full")
 
 
 def test_paper_default_geometry(gpu_lib):
