@@ -181,6 +181,16 @@ def main():
                 specpv.specpv_commit_accepted(l["kv"], cb["k"], cb["v"], P, Mt, cb["n_pending"], cb["accepted"],
                                               cb["n_accepted"], specpv.MODE_PARTIAL, None, None, ws)
         extras["commit_partial_us_per_step"] = round(timed(commit_step, k2, 3, use_graph) * 1e3, 2)
+        # ... and the same through the call that commits every layer of the model at once (one buffer
+        # per layer, the counters shared)
+        bufs_k = [torch.zeros_like(cb["k"]) for _ in layers]
+        bufs_v = [torch.zeros_like(cb["k"]) for _ in layers]
+        shared_kvs = [specpv.KV(l["kv"].k, l["kv"].v, layers[0]["kv"].ctx_len, c0["B"], c0["max_blocks"]) for l in layers]
+
+        def commit_all_step():
+            specpv.specpv_commit_accepted_layers(shared_kvs, bufs_k, bufs_v, P, Mt, cb["n_pending"], cb["accepted"],
+                                                 cb["n_accepted"], specpv.MODE_PARTIAL, None, None, ws)
+        extras["commit_partial_all_layers_us_per_step"] = round(timed(commit_all_step, k2, 3, use_graph) * 1e3, 2)
         # the paper's physically gathered partial cache (Section 3.2) against reading the blocks in
         # place: one gather per layer, and the partial step over the gathered segments
         g = []

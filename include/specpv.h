@@ -219,6 +219,20 @@ int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_
                            int32_t max_accept, specpv_mode mode, void *kmax, void *kmin,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same for the n_layers layers of a model in one go (the accepted path is the same for every
+ * layer of a verify step).  kv, buf_k, buf_v, kmax, kmin: HOST arrays of n_layers descriptors /
+ * device pointers (kmax, kmin may be NULL, or arrays of NULLs, to skip the summaries).  All
+ * layers must share one shape, one set of strides, one dtype and ONE ctx_len array; the counters
+ * (ctx_len, n_pending) are read by every layer's copies and updated once afterwards, so the
+ * result is what specpv_commit_accepted would give per layer on private copies of the counters.
+ * 1 <= n_layers <= SPECPV_MAX_LAYERS.  Three launches for up to 32 layers instead of three per layer. */
+#define SPECPV_MAX_LAYERS 256
+int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k, void *const *buf_v,
+                                  int32_t n_layers, int32_t pending_cap, int32_t M_tree,
+                                  int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
+                                  int32_t max_accept, specpv_mode mode, void *const *kmax, void *const *kmin,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
 const char *specpv_strerror(int status);
 /* Text of the HIP error behind the calling thread's last SPECPV_EHIP. */
 const char *specpv_last_hip_error(void);

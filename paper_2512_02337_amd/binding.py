@@ -22,7 +22,7 @@ MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
 
 EXPORTS = ["specpv_workspace_bytes", "specpv_block_summarize", "specpv_select_blocks",
            "specpv_partial_verify_attn", "specpv_full_verify_refresh", "specpv_gather_blocks", "specpv_select_mode",
-           "specpv_extend_parents", "specpv_commit_accepted", "specpv_strerror",
+           "specpv_extend_parents", "specpv_commit_accepted", "specpv_commit_accepted_layers", "specpv_strerror",
            "specpv_last_hip_error", "specpv_version"]
 
 
@@ -91,6 +91,9 @@ def load():
     lib.specpv_extend_parents.argtypes = [P(i32), i32, i32, P(i32)]
     lib.specpv_commit_accepted.restype = ctypes.c_int
     lib.specpv_commit_accepted.argtypes = [P(_KV), vp, vp, i32, i32, vp, vp, vp, i32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.specpv_commit_accepted_layers.restype = ctypes.c_int
+    lib.specpv_commit_accepted_layers.argtypes = [P(P(_KV)), P(vp), P(vp), i32, i32, i32, vp, vp, vp, i32, ctypes.c_int,
+                                                  P(vp), P(vp), vp, sz, vp]
     lib.specpv_strerror.restype = ctypes.c_char_p
     lib.specpv_strerror.argtypes = [ctypes.c_int]
     lib.specpv_last_hip_error.restype = ctypes.c_char_p
@@ -322,6 +325,41 @@ def specpv_commit_accepted(kv, buf_k, buf_v, pending_cap, M_tree, n_pending, acc
                                          _ptr(accepted, torch.int32, "accepted"), _ptr(n_accepted, torch.int32, "n_accepted"),
                                          int(accepted.shape[1]), int(mode), _ptr(kmax, kv.dtype, "kmax"),
                                          _ptr(kmin, kv.dtype, "kmin"), wp, wb, _stream()))
+
+
+def specpv_commit_accepted_layers(kvs, buf_ks, buf_vs, pending_cap, M_tree, n_pending, accepted, n_accepted, mode,
+                                  kmaxs=None, kmins=None, workspace=None):
+    """specpv_commit_accepted for all layers of a model at once: kvs, buf_ks, buf_vs (and kmaxs, kmins)
+    are lists with one entry per layer; the layers share shape, strides, dtype and ONE ctx_len tensor."""
+    n = len(kvs)
+    if n < 1 or len(buf_ks) != n or len(buf_vs) != n:
+        raise ValueError("one kv, buf_k and buf_v per layer")
+    kv0 = kvs[0]
+    for t in list(buf_ks) + list(buf_vs):
+        if tuple(t.shape) != (kv0.batch, pending_cap + M_tree, kv0.Hkv, kv0.D):
+            raise ValueError("buffers: [batch, pending_cap + M_tree, Hkv, D]")
+    if tuple(n_pending.shape) != (kv0.batch,) or tuple(n_accepted.shape) != (kv0.batch,) or accepted.dim() != 2 \
+            or accepted.shape[0] != kv0.batch:
+        raise ValueError("n_pending, n_accepted: int32 [batch]; accepted: int32 [batch, max_accept]")
+    if (kmaxs is None) != (kmins is None) or (kmaxs is not None and (len(kmaxs) != n or len(kmins) != n)):
+        raise ValueError("kmaxs, kmins: both or neither, one per layer")
+    for t in list(kmaxs or []) + list(kmins or []):
+        if tuple(t.shape) != kv0.summary_shape():
+            raise ValueError("summaries: [batch, Hkv, max_blocks, D]")
+    kv_arr = (ctypes.POINTER(_KV) * n)(*[ctypes.pointer(k.c) for k in kvs])
+    vp = ctypes.c_void_p
+
+    def table(ts, name):
+        return (vp * n)(*[_ptr(t, kv0.dtype, name) for t in ts])
+    bk, bv = table(buf_ks, "buf_k"), table(buf_vs, "buf_v")
+    km = table(kmaxs, "kmax") if kmaxs is not None else None
+    kn = table(kmins, "kmin") if kmins is not None else None
+    wp, wb = _ws(workspace)
+    _check(load().specpv_commit_accepted_layers(kv_arr, bk, bv, n, int(pending_cap), int(M_tree),
+                                                _ptr(n_pending, torch.int32, "n_pending"),
+                                                _ptr(accepted, torch.int32, "accepted"),
+                                                _ptr(n_accepted, torch.int32, "n_accepted"), int(accepted.shape[1]),
+                                                int(mode), km, kn, wp, wb, _stream()))
 
 
 def specpv_strerror(status):

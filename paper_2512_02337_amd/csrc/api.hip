@@ -339,9 +339,50 @@ int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_
     if ((int64_t)pending_cap + max_accept > 128 || (int64_t)pending_cap + M_tree > SPECPV_MAX_M) return SPECPV_ELIMIT;
     if (!workspace || workspace_bytes < (size_t)kv->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
     const Shape s = make_shape(kv, nullptr);
-    const hipError_t e = launch_commit(s, kv->dtype, buf_k, buf_v, pending_cap, M_tree, n_pending, accepted, n_accepted,
-                                       max_accept, mode != SPECPV_MODE_PARTIAL, kmax, kmin, (int32_t *)workspace,
-                                       (hipStream_t)stream);
+    void *k1 = const_cast<void *>(kv->k), *v1 = const_cast<void *>(kv->v);
+    const hipError_t e = launch_commit(s, kv->dtype, 1, &k1, &v1, &buf_k, &buf_v, pending_cap, M_tree, n_pending, accepted,
+                                       n_accepted, max_accept, mode != SPECPV_MODE_PARTIAL, &kmax, &kmin,
+                                       (int32_t *)workspace, (hipStream_t)stream);
+    return e == hipSuccess ? SPECPV_OK : fail_hip(e);
+}
+
+int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k, void *const *buf_v, int32_t n_layers,
+                                  int32_t pending_cap, int32_t M_tree, int32_t *n_pending, const int32_t *accepted,
+                                  const int32_t *n_accepted, int32_t max_accept, specpv_mode mode,
+                                  void *const *kmax, void *const *kmin, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    if (!kv || !buf_k || !buf_v || n_layers < 1 || n_layers > SPECPV_MAX_LAYERS) return SPECPV_EINVAL;
+    if (!n_pending || !accepted || !n_accepted) return SPECPV_EINVAL;
+    if (pending_cap < 0 || M_tree < 1 || max_accept < 1) return SPECPV_EINVAL;
+    if (mode != SPECPV_MODE_FULL && mode != SPECPV_MODE_PARTIAL && mode != SPECPV_MODE_REFRESH) return SPECPV_EINVAL;
+    if ((int64_t)pending_cap + max_accept > 128 || (int64_t)pending_cap + M_tree > SPECPV_MAX_M) return SPECPV_ELIMIT;
+    if ((kmax == nullptr) != (kmin == nullptr)) return SPECPV_EINVAL;
+    void *kp[SPECPV_MAX_LAYERS], *vp[SPECPV_MAX_LAYERS];
+    for (int l = 0; l < n_layers; ++l) {
+        const specpv_kv *x = kv[l];
+        const int rc = check_kv(x);
+        if (rc != SPECPV_OK) return rc;
+        // one shape, one set of strides, one dtype and the same length counters for all layers
+        if (x->batch != kv[0]->batch || x->n_kv_heads != kv[0]->n_kv_heads || x->head_dim != kv[0]->head_dim ||
+            x->block_size != kv[0]->block_size || x->max_blocks != kv[0]->max_blocks || x->dtype != kv[0]->dtype ||
+            x->stride_b != kv[0]->stride_b || x->stride_h != kv[0]->stride_h || x->stride_t != kv[0]->stride_t ||
+            x->ctx_len != kv[0]->ctx_len)
+            return SPECPV_EINVAL;
+        if (!buf_k[l] || !buf_v[l] || (((uintptr_t)buf_k[l] | (uintptr_t)buf_v[l]) & 15)) return SPECPV_EINVAL;
+        if (kmax) {   // summaries for every layer or for none
+            const bool want = kmax[0] != nullptr;
+            if ((kmax[l] != nullptr) != want || (kmin[l] != nullptr) != want) return SPECPV_EINVAL;
+            if (((uintptr_t)kmax[l] | (uintptr_t)kmin[l]) & 15) return SPECPV_EINVAL;
+        }
+        kp[l] = const_cast<void *>(x->k);
+        vp[l] = const_cast<void *>(x->v);
+    }
+    if (!workspace || workspace_bytes < (size_t)kv[0]->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
+    const Shape s = make_shape(kv[0], nullptr);
+    const hipError_t e = launch_commit(s, kv[0]->dtype, n_layers, kp, vp, buf_k, buf_v, pending_cap, M_tree, n_pending,
+                                       accepted, n_accepted, max_accept, mode != SPECPV_MODE_PARTIAL, kmax, kmin,
+                                       (int32_t *)workspace, (hipStream_t)stream);
     return e == hipSuccess ? SPECPV_OK : fail_hip(e);
 }
 

@@ -12,11 +12,22 @@ constexpr int kCommitMaxRows = 128;   // pending + accepted rows one call moves 
 // One workgroup per (KV head, sequence); a row of D elements is D * sizeof(T) / 16 lanes.
 // Every source row is read into registers before anything is written (the compaction of
 // the buffer moves rows within one array).
+// Several layers in one launch: blockIdx.z picks the layer's pointers from a table that travels
+// with the kernel arguments.  All layers share one shape, one set of strides and the counters.
+constexpr int kCommitLayers = 32;   // layers per launch
+struct CommitLayers {
+    void *k[kCommitLayers], *v[kCommitLayers], *buf_k[kCommitLayers], *buf_v[kCommitLayers];
+    void *kmax[kCommitLayers], *kmin[kCommitLayers];
+};
+
 template <typename T, int D>
-__global__ __launch_bounds__(256) void commit_copy_kernel(Shape s, T *buf_k, T *buf_v, int P, int Mt,
+__global__ __launch_bounds__(256) void commit_copy_kernel(Shape s, CommitLayers lay, int P, int Mt,
                                                           const int32_t *n_pending, const int32_t *accepted,
                                                           const int32_t *n_accepted, int max_accept, int to_cache)
 {
+    T *const buf_k = (T *)lay.buf_k[blockIdx.z], *const buf_v = (T *)lay.buf_v[blockIdx.z];
+    s.k = lay.k[blockIdx.z];
+    s.v = lay.v[blockIdx.z];
     constexpr int LPR = D * (int)sizeof(T) / 16;   // lanes per row
     constexpr int RPP = 256 / LPR;                 // rows per pass
     constexpr int PASSES = (kCommitMaxRows + RPP - 1) / RPP;
@@ -83,12 +94,15 @@ __global__ void commit_update_kernel(Shape s, int P, int32_t *ctx_len, int32_t *
 // eq. 1 for the blocks old_len / B .. (new length - 1) / B of every sequence: one wavefront per
 // (block, KV head), lanes over 16-byte pieces of a row, rows strided over the lane groups.
 template <typename T, int D>
-__global__ __launch_bounds__(64) void summarize_tail_kernel(Shape s, const int32_t *old_len, void *kmax, void *kmin)
+__global__ __launch_bounds__(64) void summarize_tail_kernel(Shape s, CommitLayers lay, const int32_t *old_len)
 {
     constexpr int E = Elem<T>::kPerVec;
     constexpr int LPR = D / E;
     constexpr int RPP = 64 / LPR;
-    const int lane = threadIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int layer = blockIdx.z / s.batch;
+    const int lane = threadIdx.x, g = blockIdx.y, b = blockIdx.z - layer * s.batch;
+    void *const kmax = lay.kmax[layer], *const kmin = lay.kmin[layer];
+    s.k = lay.k[layer];
     const int L = s.ctx_len[b], L0 = old_len[b];
     if (L <= L0) return;
     const int i = L0 / s.B + blockIdx.x;
@@ -121,38 +135,59 @@ __global__ __launch_bounds__(64) void summarize_tail_kernel(Shape s, const int32
     }
 }
 
-hipError_t launch_commit(const Shape &s, int dtype, void *buf_k, void *buf_v, int P, int Mt,
+// layers: n_layers entries each of k, v (the caches), buf_k, buf_v (the buffers) and, for a commit to
+// the cache, kmax, kmin (or all NULL).  s carries the shape, the strides and ctx_len (shared).
+hipError_t launch_commit(const Shape &s, int dtype, int n_layers, void *const *k, void *const *v,
+                         void *const *buf_k, void *const *buf_v, int P, int Mt,
                          int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
-                         int max_accept, int to_cache, void *kmax, void *kmin, int32_t *old_len, hipStream_t st)
+                         int max_accept, int to_cache, void *const *kmax, void *const *kmin, int32_t *old_len,
+                         hipStream_t st)
 {
     if (P + max_accept > kCommitMaxRows) return hipErrorInvalidValue;
-    const dim3 grid(s.Hkv, s.batch);
+    const bool summaries = to_cache && kmax && kmin && kmax[0] && kmin[0];
+    // the copies of every layer read the counters, so all of them go before the update
+    for (int l0 = 0; l0 < n_layers; l0 += kCommitLayers) {
+        const int nl = n_layers - l0 < kCommitLayers ? n_layers - l0 : kCommitLayers;
+        CommitLayers lay = {};
+        for (int l = 0; l < nl; ++l) {
+            lay.k[l] = k[l0 + l]; lay.v[l] = v[l0 + l];
+            lay.buf_k[l] = buf_k[l0 + l]; lay.buf_v[l] = buf_v[l0 + l];
+        }
+        const dim3 grid(s.Hkv, s.batch, nl);
 #define SPECPV_COPY(T, DD)                                                                             \
-    hipLaunchKernelGGL((commit_copy_kernel<T, DD>), grid, dim3(256), 0, st, s, (T *)buf_k, (T *)buf_v, P, Mt, \
+    hipLaunchKernelGGL((commit_copy_kernel<T, DD>), grid, dim3(256), 0, st, s, lay, P, Mt,              \
                        n_pending, accepted, n_accepted, max_accept, to_cache)
-    if (dtype == SPECPV_BF16) {
-        if (s.D == 128) SPECPV_COPY(bf16_t, 128); else SPECPV_COPY(bf16_t, 64);
-    } else {
-        if (s.D == 128) SPECPV_COPY(float, 128); else SPECPV_COPY(float, 64);
-    }
+        if (dtype == SPECPV_BF16) {
+            if (s.D == 128) SPECPV_COPY(bf16_t, 128); else SPECPV_COPY(bf16_t, 64);
+        } else {
+            if (s.D == 128) SPECPV_COPY(float, 128); else SPECPV_COPY(float, 64);
+        }
 #undef SPECPV_COPY
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(commit_update_kernel, dim3((s.batch + 63) / 64), dim3(64), 0, st, s, P,
                        (int32_t *)s.ctx_len, n_pending, n_accepted, max_accept, to_cache, old_len);
-    e = hipGetLastError();
-    if (e != hipSuccess || !to_cache || !kmax || !kmin) return e;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !summaries) return e;
     // blocks that can have received one of at most P + max_accept tokens
     const int touched = (P + max_accept + s.B - 1) / s.B + 1;
-    const dim3 g2(touched, s.Hkv, s.batch);
-#define SPECPV_SUM(T, DD) hipLaunchKernelGGL((summarize_tail_kernel<T, DD>), g2, dim3(64), 0, st, s, old_len, kmax, kmin)
-    if (dtype == SPECPV_BF16) {
-        if (s.D == 128) SPECPV_SUM(bf16_t, 128); else SPECPV_SUM(bf16_t, 64);
-    } else {
-        if (s.D == 128) SPECPV_SUM(float, 128); else SPECPV_SUM(float, 64);
-    }
+    for (int l0 = 0; l0 < n_layers; l0 += kCommitLayers) {
+        const int nl = n_layers - l0 < kCommitLayers ? n_layers - l0 : kCommitLayers;
+        CommitLayers lay = {};
+        for (int l = 0; l < nl; ++l) { lay.k[l] = k[l0 + l]; lay.kmax[l] = kmax[l0 + l]; lay.kmin[l] = kmin[l0 + l]; }
+        const dim3 g2(touched, s.Hkv, s.batch * nl);
+#define SPECPV_SUM(T, DD) hipLaunchKernelGGL((summarize_tail_kernel<T, DD>), g2, dim3(64), 0, st, s, lay, old_len)
+        if (dtype == SPECPV_BF16) {
+            if (s.D == 128) SPECPV_SUM(bf16_t, 128); else SPECPV_SUM(bf16_t, 64);
+        } else {
+            if (s.D == 128) SPECPV_SUM(float, 128); else SPECPV_SUM(float, 64);
+        }
 #undef SPECPV_SUM
-    return hipGetLastError();
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace specpv

@@ -118,9 +118,12 @@ int attn_group_parts(const Shape &s);
 hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st);
 // to_cache != 0: pending + accepted rows go to the cache tail (lengths, summaries updated);
 // otherwise the accepted rows join the pending rows of the buffer.  old_len: [batch] scratch.
-hipError_t launch_commit(const Shape &s, int dtype, void *buf_k, void *buf_v, int P, int Mt,
+// n_layers layers that share shape, strides and counters are committed together.
+hipError_t launch_commit(const Shape &s, int dtype, int n_layers, void *const *k, void *const *v,
+                         void *const *buf_k, void *const *buf_v, int P, int Mt,
                          int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
-                         int max_accept, int to_cache, void *kmax, void *kmin, int32_t *old_len, hipStream_t st);
+                         int max_accept, int to_cache, void *const *kmax, void *const *kmin, int32_t *old_len,
+                         hipStream_t st);
 
 hipError_t launch_gather(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count, int n_sel,
                          void *out_k, void *out_v, int32_t *out_len, hipStream_t st);

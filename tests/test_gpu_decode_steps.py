@@ -170,3 +170,62 @@ def test_gathered_partial_cache(gpu_lib, name, seed):
     assert d <= 2e-2 * 0.25
     O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], B, idx, cnt)
     assert np.abs(_f64(out2[0]) - O).max() <= ATOL[case["dtype"]]
+
+
+@pytest.mark.parametrize("mode_name", ["partial", "refresh"])
+def test_commit_of_all_layers_at_once(gpu_lib, mode_name):
+    """specpv_commit_accepted_layers on 34 layers (more than one launch's worth) that share their
+    length counters gives, bit for bit, what specpv_commit_accepted gives layer by layer on private
+    copies of the counters (which the decode test above checks against the oracle)."""
+    sp = gpu_lib
+    dev = torch.device("cuda")
+    g = torch.Generator(device="cpu").manual_seed(77)
+    n_layers, batch, Hkv, D, T, B, P, Mt = 34, 2, 2, 128, 512, 16, 28, 24
+    mode = sp.MODE_PARTIAL if mode_name == "partial" else sp.MODE_REFRESH
+
+    def rnd(*shape):
+        return torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
+    ks = [rnd(batch, Hkv, T, D) for _ in range(n_layers)]
+    vs = [rnd(batch, Hkv, T, D) for _ in range(n_layers)]
+    bks = [rnd(batch, P + Mt, Hkv, D) for _ in range(n_layers)]
+    bvs = [rnd(batch, P + Mt, Hkv, D) for _ in range(n_layers)]
+    ctx0 = torch.tensor([100, 333], dtype=torch.int32, device=dev)
+    pend0 = torch.tensor([5, 0], dtype=torch.int32, device=dev)
+    accepted = torch.tensor([[0, 2, 5, 9], [1, 3, 0, 0]], dtype=torch.int32, device=dev)
+    n_acc = torch.tensor([4, 2], dtype=torch.int32, device=dev)
+    max_blocks = T // B
+    ws = torch.empty((256,), dtype=torch.uint8, device=dev)
+
+    # layer by layer, private counters
+    ref = []
+    for l in range(n_layers):
+        k, v, bk, bv = ks[l].clone(), vs[l].clone(), bks[l].clone(), bvs[l].clone()
+        ctx, pend = ctx0.clone(), pend0.clone()
+        kv = sp.KV(k, v, ctx, B, max_blocks)
+        kmax = torch.zeros(kv.summary_shape(), dtype=k.dtype, device=dev); kmin = torch.zeros_like(kmax)
+        sp.specpv_block_summarize(kv, 0, -1, kmax, kmin)
+        sp.specpv_commit_accepted(kv, bk, bv, P, Mt, pend, accepted, n_acc, mode, kmax, kmin, ws)
+        ref.append((k, v, bk, bv, ctx, pend, kmax, kmin))
+    # all layers at once, shared counters
+    ctx, pend = ctx0.clone(), pend0.clone()
+    k2, v2 = [x.clone() for x in ks], [x.clone() for x in vs]
+    bk2, bv2 = [x.clone() for x in bks], [x.clone() for x in bvs]
+    kvs = [sp.KV(k2[l], v2[l], ctx, B, max_blocks) for l in range(n_layers)]
+    kmaxs, kmins = [], []
+    for l in range(n_layers):
+        kmax = torch.zeros(kvs[l].summary_shape(), dtype=k2[l].dtype, device=dev); kmin = torch.zeros_like(kmax)
+        sp.specpv_block_summarize(kvs[l], 0, -1, kmax, kmin)
+        kmaxs.append(kmax); kmins.append(kmin)
+    say("commit of", n_layers, "layers,", mode_name)
+    sp.specpv_commit_accepted_layers(kvs, bk2, bv2, P, Mt, pend, accepted, n_acc, mode, kmaxs, kmins, ws)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        k, v, bk, bv, c1, p1, kmax, kmin = ref[l]
+        assert torch.equal(k2[l], k) and torch.equal(v2[l], v), "cache rows, layer %d" % l
+        assert torch.equal(bk2[l], bk) and torch.equal(bv2[l], bv), "buffer rows, layer %d" % l
+        assert torch.equal(kmaxs[l], kmax) and torch.equal(kmins[l], kmin), "summaries, layer %d" % l
+        assert torch.equal(ctx, c1) and torch.equal(pend, p1), "counters"
+    if mode_name == "partial":
+        assert ctx.tolist() == [100, 333] and pend.tolist() == [9, 2]
+    else:
+        assert ctx.tolist() == [109, 335] and pend.tolist() == [0, 0]
