@@ -147,3 +147,32 @@ def test_mode_policy_and_extended_parents_on_the_host():
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -3          # buffer beyond the limits
     a = list(ok_args); a[12] = 2
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -2          # workspace too small
+
+
+def test_commit_of_all_layers_validates_on_the_host():
+    """Fake pointers again: the layers of one call must share shape, strides, dtype and the length
+    counters, and every table entry must be there."""
+    lib = specpv.load()
+    vp, P = ctypes.c_void_p, ctypes.POINTER
+
+    def call(kvs, n=None, buf_k=(0x10000, 0x20000), buf_v=(0x30000, 0x40000), kmax=None, kmin=None, pending_cap=28):
+        n = len(kvs) if n is None else n
+        arr = (P(binding._KV) * len(kvs))(*[ctypes.pointer(k) for k in kvs])
+        bk, bv = (vp * len(buf_k))(*buf_k), (vp * len(buf_v))(*buf_v)
+        km = (vp * len(kmax))(*kmax) if kmax is not None else None
+        kn = (vp * len(kmin))(*kmin) if kmin is not None else None
+        return lib.specpv_commit_accepted_layers(arr, bk, bv, n, pending_cap, 60, vp(0x100), vp(0x200), vp(0x300), 8, 1,
+                                                 km, kn, None, 0, None)
+    two = [_kv(), _kv(k=0x9000, v=0xA000)]
+    assert call(two) == -2                                    # everything valid up to the (missing) workspace
+    assert call(two, n=0) == -1
+    assert call(two, n=1000) == -1
+    assert call([_kv(), _kv(ctx_len=0x3100)]) == -1           # two length arrays
+    assert call([_kv(), _kv(max_blocks=32)]) == -1
+    assert call([_kv(), _kv(stride_t=256)]) == -1
+    assert call(two, buf_k=(0x10000, 0)) == -1
+    assert call(two, buf_v=(0x30004, 0x40000)) == -1
+    assert call(two, kmax=(0x50000, 0x60000)) == -1           # kmax without kmin
+    assert call(two, kmax=(0x50000, 0), kmin=(0x70000, 0x80000)) == -1
+    assert call(two, kmax=(0x50000, 0x60000), kmin=(0x70000, 0x80000)) == -2
+    assert call(two, pending_cap=120) == -3
