@@ -128,11 +128,12 @@ static AttnPlan plan_attention(const Shape &s, int dtype, int64_t n_blocks)
             ns = best_splits(base1, 1, max1);
             if (s.batch > 1) {
                 // The sequences of a batch may differ in length, and the lengths live on the device:
-                // many small workgroups (about eight per CU, 16 chunks or more each) let the hardware
-                // scheduler even that out (measured on 32K + 64K + 96K + 128K: 1089 -> 841 us).
+                // many small workgroups (about eight per CU, 64 chunks or more each: shorter ones are
+                // mostly prologue and epilogue) let the hardware scheduler even that out (measured on
+                // 32K + 64K + 96K + 128K: 1089 -> 841 us).
                 int64_t c = (8 * cus + base1 - 1) / base1;
                 if (c > max1) c = max1;
-                while (c > ns && (chunks + c - 1) / c < 16) --c;
+                while (c > ns && (chunks + c - 1) / c < 64) --c;
                 if (c > ns) ns = c;
             }
         }
