@@ -38,7 +38,50 @@ __device__ __forceinline__ float wave_max_u(float x)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
-template <typename T, int D>
+// A lane's DPL adjacent channels of one row, one memory instruction each way (rows are 16-byte aligned).
+typedef float cmb_f32x2 __attribute__((ext_vector_type(2)));
+template <typename T, int DPL> struct Chan;
+template <> struct Chan<float, 1> {
+    static __device__ __forceinline__ void load(const void *p, int64_t i, float *f) { f[0] = ((const float *)p)[i]; }
+    static __device__ __forceinline__ void store_stream(void *p, int64_t i, const float *f) { __builtin_nontemporal_store(f[0], (float *)p + i); }
+};
+template <> struct Chan<float, 2> {
+    static __device__ __forceinline__ void load(const void *p, int64_t i, float *f) {
+        const cmb_f32x2 v = *(const cmb_f32x2 *)((const float *)p + i);
+        f[0] = v.x; f[1] = v.y;
+    }
+    static __device__ __forceinline__ void store_stream(void *p, int64_t i, const float *f) {
+        cmb_f32x2 v; v.x = f[0]; v.y = f[1];
+        __builtin_nontemporal_store(v, (cmb_f32x2 *)((float *)p + i));
+    }
+};
+template <> struct Chan<bf16_t, 1> {
+    static __device__ __forceinline__ void load(const void *p, int64_t i, float *f) { f[0] = bf16_bits_to_float(((const uint16_t *)p)[i]); }
+    static __device__ __forceinline__ void store_stream(void *p, int64_t i, const float *f) { __builtin_nontemporal_store(float_to_bf16_bits(f[0]), (uint16_t *)p + i); }
+};
+template <> struct Chan<bf16_t, 2> {
+    static __device__ __forceinline__ void load(const void *p, int64_t i, float *f) {
+        const uint32_t w = *(const uint32_t *)((const uint16_t *)p + i);
+        f[0] = __uint_as_float(w << 16); f[1] = __uint_as_float(w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store_stream(void *p, int64_t i, const float *f) {
+        const uint32_t w = float_to_bf16_bits(f[0]) | ((uint32_t)float_to_bf16_bits(f[1]) << 16);
+        __builtin_nontemporal_store(w, (uint32_t *)((uint16_t *)p + i));
+    }
+};
+template <int DPL> __device__ __forceinline__ void load_partial(const float *p, int64_t i, float *f)
+{
+    if constexpr (DPL == 2) {
+        const cmb_f32x2 v = __builtin_nontemporal_load((const cmb_f32x2 *)(p + i));
+        f[0] = v.x; f[1] = v.y;
+    } else {
+        f[0] = __builtin_nontemporal_load(p + i);
+    }
+}
+
+// NP: context partials fetched per round (the smallest of 2, 4, 8 that covers the split count in
+// one round keeps the registers, and with them the resident wavefronts of a batch, in proportion).
+template <typename T, int D, int NP>
 __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
                                                      const float *a_pml, int a_M, int a_Hq, int a_G, int a_nsplit,
                                                      Shape s, Partials part, void *out, float *lse, float scale_log2)
@@ -46,8 +89,9 @@ __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, 
     // the leading scalar arguments repeat what the first round of reads needs; they can be preloaded into registers
     s.parent = a_parent; s.q = a_q; s.M = a_M; s.Hq = a_Hq; s.G = a_G;
     part.o = const_cast<float *>(a_po); part.ml = const_cast<float *>(a_pml); part.nsplit = a_nsplit;
-    constexpr int DPL = D / 64;   // channels per lane: d = lane + 64 * x
+    constexpr int DPL = D / 64;   // channels per lane: d = lane * DPL + x
     const int lane = threadIdx.x & 63;
+    const int d0 = lane * DPL;
     const int g = blockIdx.y, b = blockIdx.z, j = blockIdx.x;
     const int h = g * s.G + (int)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // one wavefront per query head of the KV group
 
@@ -57,20 +101,18 @@ __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, 
     const int par1 = lane + 64 < s.M ? par[lane + 64] : -1;
     const int64_t qrow = (((int64_t)b * s.M + j) * s.Hq + h) * D;
     float qv[DPL];
-#pragma unroll
-    for (int x = 0; x < DPL; ++x) qv[x] = Elem<T>::load(s.q, qrow + lane + 64 * x);
+    Chan<T, DPL>::load(s.q, qrow + d0, qv);
     const int64_t prow0 = (((int64_t)b * s.Hq + h) * part.nsplit) * s.M + j;
     float2 mlv = make_float2(-INFINITY, 0.f);   // lane sp holds (m, l) of split sp
     if (lane < part.nsplit) mlv = *(const float2 *)(part.ml + (prow0 + (int64_t)lane * s.M) * 2);
 
-    // ... including the first 8 context partials (all of them in the usual case)
-    float po[8][DPL];
+    // ... including the first NP context partials (all of them in the usual case)
+    float po[NP][DPL];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < NP; ++u) {
         const int sp = min(u, part.nsplit - 1);
         const int64_t prow = prow0 + (int64_t)sp * s.M;
-#pragma unroll
-        for (int x = 0; x < DPL; ++x) po[u][x] = __builtin_nontemporal_load(part.o + prow * D + lane + 64 * x);
+        load_partial<DPL>(part.o, prow * D + d0, po[u]);
     }
 
     // ---- root path of node j as a bit set (wave-uniform walk over the parent registers) --
@@ -96,11 +138,8 @@ __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, 
     for (int u = 0; u < 8; ++u) {
         a8[u] = pop();
         const int64_t drow = (((int64_t)b * s.M + max(a8[u], 0)) * s.Hkv + g) * D;
-#pragma unroll
-        for (int x = 0; x < DPL; ++x) {
-            kd8[u][x] = Elem<T>::load(s.kd, drow + lane + 64 * x);
-            vd8[u][x] = Elem<T>::load(s.vd, drow + lane + 64 * x);
-        }
+        Chan<T, DPL>::load(s.kd, drow + d0, kd8[u]);
+        Chan<T, DPL>::load(s.vd, drow + d0, vd8[u]);
     }
 
     // ---- context partials, merged relative to their own maximum (first-round data) -------
@@ -112,21 +151,20 @@ __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, 
 #pragma unroll
     for (int x = 0; x < DPL; ++x) o[x] = 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < NP; ++u) {
         const float w = u < part.nsplit ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_mine), u)) : 0.f;
 #pragma unroll
         for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, po[u][x], o[x]);
     }
-    for (int sp0 = 8; sp0 < part.nsplit; sp0 += 8) {
+    for (int sp0 = NP; sp0 < part.nsplit; sp0 += NP) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < NP; ++u) {
             const int sp = min(sp0 + u, part.nsplit - 1);
             const int64_t prow = prow0 + (int64_t)sp * s.M;
-#pragma unroll
-            for (int x = 0; x < DPL; ++x) po[u][x] = __builtin_nontemporal_load(part.o + prow * D + lane + 64 * x);
+            load_partial<DPL>(part.o, prow * D + d0, po[u]);
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < NP; ++u) {
             const float w = sp0 + u < part.nsplit ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w_mine), sp0 + u)) : 0.f;
 #pragma unroll
             for (int x = 0; x < DPL; ++x) o[x] = fmaf(w, po[u][x], o[x]);
@@ -171,11 +209,8 @@ __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, 
         for (int u = 0; u < 4; ++u) {
             a[u] = pop();
             const int64_t drow = (((int64_t)b * s.M + max(a[u], 0)) * s.Hkv + g) * D;
-#pragma unroll
-            for (int x = 0; x < DPL; ++x) {
-                kdv[u][x] = Elem<T>::load(s.kd, drow + lane + 64 * x);
-                vdv[u][x] = Elem<T>::load(s.vd, drow + lane + 64 * x);
-            }
+            Chan<T, DPL>::load(s.kd, drow + d0, kdv[u]);
+            Chan<T, DPL>::load(s.vd, drow + d0, vdv[u]);
         }
         four(a, kdv, vdv);
     }
@@ -186,8 +221,10 @@ __global__ __launch_bounds__(1024) void combine_kernel(const int32_t *a_parent, 
     const float wc = m_ctx == -INFINITY ? 0.f : exp2f(m_ctx - m_all);
     const float den = l * wd + l_ctx * wc;
     const float inv = 1.f / den;
+    float res[DPL];
 #pragma unroll
-    for (int x = 0; x < DPL; ++x) Elem<T>::store_stream(out, qrow + lane + 64 * x, (od[x] * wd + o[x] * wc) * inv);
+    for (int x = 0; x < DPL; ++x) res[x] = (od[x] * wd + o[x] * wc) * inv;
+    Chan<T, DPL>::store_stream(out, qrow + d0, res);
     if (lse && lane == 0) lse[((int64_t)b * s.M + j) * s.Hq + h] = (m_all + log2f(den)) * kLn2;
 }
 
@@ -195,14 +232,21 @@ hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, floa
 {
     dim3 grid(s.M, s.Hkv, s.batch), block(64 * s.G);
     const float scale_log2 = kLog2e / sqrtf((float)s.D);
+#define SPECPV_LAUNCH_NP(T, DD, NP) \
+    hipLaunchKernelGGL((combine_kernel<T, DD, NP>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
 #define SPECPV_LAUNCH(T, DD) \
-    hipLaunchKernelGGL((combine_kernel<T, DD>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
+    do { \
+        if (p.nsplit <= 2) SPECPV_LAUNCH_NP(T, DD, 2); \
+        else if (p.nsplit <= 4) SPECPV_LAUNCH_NP(T, DD, 4); \
+        else SPECPV_LAUNCH_NP(T, DD, 8); \
+    } while (0)
     if (dtype == SPECPV_BF16) {
         if (s.D == 128) SPECPV_LAUNCH(bf16_t, 128); else SPECPV_LAUNCH(bf16_t, 64);
     } else {
         if (s.D == 128) SPECPV_LAUNCH(float, 128); else SPECPV_LAUNCH(float, 64);
     }
 #undef SPECPV_LAUNCH
+#undef SPECPV_LAUNCH_NP
     return hipGetLastError();
 }
 
