@@ -248,6 +248,21 @@ def main():
             extras["offload_full_refresh_us_per_layer"] = round(per_layer_ms * 1e3, 1)
             extras["offload_h2d_GBs"] = round((hk[0].numel() + hv[0].numel()) * hk[0].element_size() / (per_layer_ms * 1e-3) / 1e9, 1)
             del pf, hk, hv, staged
+        # what this machine's HBM delivers to plain streaming kernels, next to the published peak: a device
+        # copy of 1 GiB (read + write bytes), and the library's own read-only stream (eq. 1 over one
+        # layer's K, rotating over the layers so that the 256 MB last-level cache cannot serve it)
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        cp = timed(lambda: dst.copy_(src), 10, 2, False)
+        extras["hbm_copy_ceiling_GBs"] = round(2 * src.numel() / (cp * 1e-3) / 1e9, 1)
+        del src, dst
+
+        def summarize_all():
+            for l in layers:
+                specpv.specpv_block_summarize(l["kv"], 0, -1, l["kmax"], l["kmin"])
+        sm = timed(summarize_all, 5, 1, False)
+        k_bytes = sum(int(x) for x in c0["ctx_len"]) * c0["Hkv"] * c0["D"] * 2
+        extras["hbm_read_stream_GBs"] = round(k_bytes * n_layers / (sm * 1e-3) / 1e9, 1)
         extras["setup_s"] = round(setup_s, 1)
 
     cpu = None
@@ -276,7 +291,8 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if n_layers == cfg["layers"] else None,
                      "kernel": "attn_ctx_mfma_kernel + combine_kernel = one specpv_partial_verify_attn call (one layer)",
-                     "algorithmic_bytes_per_launch": bytes_layer, "us_per_launch": round(us_layer, 3)},
+                     "algorithmic_bytes_per_launch": bytes_layer, "us_per_launch": round(us_layer, 3),
+                     "box_copy_GBs": extras.get("hbm_copy_ceiling_GBs"), "box_read_stream_GBs": extras.get("hbm_read_stream_GBs")},
         "cpu_baseline": cpu,
         "extras": extras,
     }
