@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-offload", action="store_true", help="skip the host-offload leg of the extras (2 GiB of pinned memory)")
+    ap.add_argument("--no-batch", action="store_true", help="skip the 16-sequence leg of the extras (4 GiB of K / V)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run 4 plain device copies of 256 MiB (read 256 MiB + write 256 MiB each) so that "
@@ -248,6 +249,34 @@ def main():
             extras["offload_full_refresh_us_per_layer"] = round(per_layer_ms * 1e3, 1)
             extras["offload_h2d_GBs"] = round((hk[0].numel() + hv[0].numel()) * hk[0].element_size() / (per_layer_ms * 1e-3) / 1e9, 1)
             del pf, hk, hv, staged
+        # the same partial step as a throughput problem: 16 sequences of this shape with 32K of context
+        # each in ONE call per layer (two layers' inputs in turn: 4 GiB of K / V, kept blocks scattered)
+        if args.workload == "llama8b_128k" and not args.no_batch:
+            bcfg = dict(cfg)
+            bcfg.update(ctx=[32768] * 16, rho=[0.05] * 16, layers=1, name="llama8b_batch16_32k")
+            bsets = []
+            for layer in range(2):
+                bc = workloads.make_case(bcfg, seed=args.seed, layer=layer, device=dev)
+                bkv = specpv.KV(bc["k"], bc["v"], bc["ctx_len"], bc["B"], bc["max_blocks"])
+                btree = specpv.Tree(bc["q"], bc["kd"], bc["vd"], bc["parent"])
+                bscfg = specpv.SelectCfg(bc["ns"], bc["nr"], bc["k_blocks"], "mean")
+                bkmax = torch.empty(bkv.summary_shape(), dtype=bc["q"].dtype, device=dev)
+                bkmin = torch.empty_like(bkmax)
+                bsel = torch.empty((bc["batch"], bc["Hkv"], bscfg.n_sel), dtype=torch.int32, device=dev)
+                bcnt = torch.empty((bc["batch"], bc["Hkv"]), dtype=torch.int32, device=dev)
+                bws = torch.empty((specpv.specpv_workspace_bytes(bkv, btree, bscfg),), dtype=torch.uint8, device=dev)
+                specpv.specpv_block_summarize(bkv, 0, -1, bkmax, bkmin)
+                specpv.specpv_select_blocks(bkv, btree, bkmax, bkmin, bscfg, bsel, bcnt, None, bws)
+                bsets.append((bc, bkv, btree, bsel, bcnt, torch.empty_like(bc["q"]), bws))
+
+            def batched_partial_step():
+                for (_, bkv, btree, bsel, bcnt, bout, bws) in bsets:
+                    specpv.specpv_partial_verify_attn(bkv, btree, bsel, bcnt, bout, None, bws)
+            bus = timed(batched_partial_step, k2, 3, use_graph) * 1e3 / len(bsets)
+            bbytes, _ = algorithmic_bytes_per_layer(bsets[0][0])
+            extras["batch16_32k_partial_us_per_call"] = round(bus, 2)
+            extras["batch16_32k_partial_GBs"] = round(bbytes / (bus * 1e-6) / 1e9, 1)
+            del bsets
         # what this machine's HBM delivers to plain streaming kernels, next to the published peak: a device
         # copy of 1 GiB (read + write bytes), and the library's own read-only stream (eq. 1 over one
         # layer's K, rotating over the layers so that the 256 MB last-level cache cannot serve it)
