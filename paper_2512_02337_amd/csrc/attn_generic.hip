@@ -87,7 +87,7 @@ __global__ __launch_bounds__(64) void attn_ctx_generic_kernel(Shape s, const int
     }
     const int64_t row = (((int64_t)b * s.Hq + h) * part.nsplit + sp) * s.M + j;
 #pragma unroll
-    for (int x = 0; x < DPL; ++x) __builtin_nontemporal_store(o[x], part.o + row * D + lane + 64 * x);   // written once, read once by the combine
+    for (int x = 0; x < DPL; ++x) __builtin_nontemporal_store(o[x], part.o + row * D + partial_pos(lane + 64 * x, D));   // written once, read once by the combine
     if (lane == 0) { part.ml[row * 2] = m; part.ml[row * 2 + 1] = l; }
 }
 

@@ -569,7 +569,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
         for (int uu = 0; uu < RPW; ++uu) {
             const int j = m0 + wave * RPW + uu;
-            if (j < s.M) store_partial(part.o + (prow0 + j) * 128 + 2 * lane, acc[uu]);
+            if (j < s.M) store_partial(part.o + (prow0 + j) * 128 + partial_pos(2 * lane, 128), acc[uu]);
         }
     }
     if (lane < RPW) {
@@ -886,7 +886,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll 8
     for (int uu = 0; uu < 32; ++uu) {
         const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
-        if (jrow0 + uu < s.M) store_partial(part.o + (prow0 + jrow0 + uu) * 128 + 2 * lane, x);
+        if (jrow0 + uu < s.M) store_partial(part.o + (prow0 + jrow0 + uu) * 128 + partial_pos(2 * lane, 128), x);
     }
     if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
 }

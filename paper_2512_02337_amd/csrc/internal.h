@@ -27,11 +27,18 @@ struct Shape {
 //   part_o  [batch, Hq, nsplit, M, D] fp32   sum_t 2^(z_t - m) v_t   (not normalised)
 //   part_ml [batch, Hq, nsplit, M, 2] fp32   (m, l): m = max_t z_t, l = sum_t 2^(z_t - m),
 // with z = q.k * log2(e)/sqrt(D).  A split without any valid token stores m = -inf, l = 0.
+// Inside a row of part_o with D = 128 the channels are stored in the order the combine kernel
+// reads them (a lane of 16 owns channels 8 i .. 8 i + 7 and fetches them as two 16-byte pieces,
+// each piece dense over the 16 lanes): channel c sits at partial_pos(c).  D = 64: in order.
 struct Partials {
     float *o;
     float *ml;
     int nsplit;
 };
+__host__ __device__ constexpr int partial_pos(int c, int D)
+{
+    return D == 128 ? ((c >> 2) & 1) * 64 + (c >> 3) * 4 + (c & 3) : c;
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
