@@ -561,7 +561,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const float ww = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt[w]), uu));   // uniform: no LDS shuffle
-                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + 2 * lane);
+                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + partial_chan(2 * lane, 128));
                 acc[uu].x = fmaf(ww, x.x, acc[uu].x);
                 acc[uu].y = fmaf(ww, x.y, acc[uu].y);
             }
@@ -569,7 +569,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
         for (int uu = 0; uu < RPW; ++uu) {
             const int j = m0 + wave * RPW + uu;
-            if (j < s.M) store_partial(part.o + (prow0 + j) * 128 + partial_pos(2 * lane, 128), acc[uu]);
+            if (j < s.M) store_partial(part.o + (prow0 + j) * 128 + 2 * lane, acc[uu]);   // positions 2 lane, 2 lane + 1 of the stored order
         }
     }
     if (lane < RPW) {
@@ -885,8 +885,8 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const int jrow0 = m0;
 #pragma unroll 8
     for (int uu = 0; uu < 32; ++uu) {
-        const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
-        if (jrow0 + uu < s.M) store_partial(part.o + (prow0 + jrow0 + uu) * 128 + partial_pos(2 * lane, 128), x);
+        const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + partial_chan(2 * lane, 128));
+        if (jrow0 + uu < s.M) store_partial(part.o + (prow0 + jrow0 + uu) * 128 + 2 * lane, x);   // positions 2 lane, 2 lane + 1 of the stored order
     }
     if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
 }

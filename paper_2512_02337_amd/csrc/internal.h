@@ -39,6 +39,11 @@ __host__ __device__ constexpr int partial_pos(int c, int D)
 {
     return D == 128 ? ((c >> 2) & 1) * 64 + (c >> 3) * 4 + (c & 3) : c;
 }
+// ... and the channel that sits at position p (the inverse)
+__host__ __device__ constexpr int partial_chan(int p, int D)
+{
+    return D == 128 ? ((p & 63) >> 2) * 8 + (p >> 6) * 4 + (p & 3) : p;
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
