@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per specpv_partial_verify_attn call at the default workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE scaled by a plain device copy (profiles/pmc_traffic_llama8b_128k.md); not measurable live.
-MEASURED_TRAFFIC_BYTES = {"llama8b_128k": int((19.9 + 9.9 + 7.6 + 0.47) * 2**20)}
+MEASURED_TRAFFIC_BYTES = {"llama8b_128k": (10223 + 4928) * 2 * 1024 + (7800 + 480) * 1024}   # KiB readings, FETCH x 2.0
 
 
 def parse():
