@@ -147,6 +147,33 @@ def test_long_ranges_take_the_group_kernel(gpu_lib, over, tag):
         _check_attn(run, case, sel, tag + " partial " + layout)
 
 
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("f32", 128), ("bf16", 64)])
+@pytest.mark.parametrize("M,ctx,splits", [(128, [1000], 4), (75, [1000], 7), (128, [1000, 900], 2)])
+def test_few_splits_on_the_vector_alu_path(gpu_lib, dtype, D, M, ctx, splits):
+    """fp32 and head dim 64 take the vector-ALU attention kernel, whose split count falls with the
+    number of query rows: 7, 4 and 2 splits here, so that the merge of the partials runs in each
+    of its register layouts (8, 4 and 2 partials per round) for these element types too (the
+    other cases of this file give them 13 splits or more)."""
+    say("case", dtype, D, M, ctx, "splits", splits)
+    cfg = dict(SMALL)
+    cfg.update(dtype=dtype, D=D, M=M, ctx=ctx, rho=[0.1] * len(ctx), tree="uniform")
+    case = workloads.to_device(workloads.make_case(cfg, seed=23), "cuda")
+    run = GpuRun(gpu_lib, case)
+    # the workspace is sized by the split count: partial O + (m, l) pairs + scores, each rounded up to 256 bytes
+    up = lambda x: (x + 255) & ~255
+    rows = case["batch"] * case["Hq"] * M
+    want = up(rows * splits * D * 4) + up(rows * splits * 8) + up(case["batch"] * case["Hkv"] * case["max_blocks"] * 4)
+    assert run.ws.numel() == want, "the planner no longer gives %d splits here" % splits
+    run.refresh(stale=0)
+    torch.cuda.synchronize()
+    _check_attn(run, case, None, "full")
+    sel = [(run.sel_idx.cpu().numpy()[b], run.sel_count.cpu().numpy()[b]) for b in range(case["batch"])]
+    run.out.zero_()
+    run.attend()
+    torch.cuda.synchronize()
+    _check_attn(run, case, sel, "partial")
+
+
 @pytest.mark.parametrize("reduce,last_node", [("max", 0), ("last", 0), ("last", 5), ("mean", 0)])
 def test_reducers(gpu_lib, reduce, last_node):
     say("reducer", reduce, last_node)
