@@ -25,7 +25,9 @@ typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 // BOUND: the channel-wise bound instead of eq. 2.  Per channel the larger product is q * Kmax
 // where q >= 0 and q * Kmin where q < 0 (Kmax >= Kmin), so the bound is the sum of two inner
 // products as well: max(q, 0) . Kmax + min(q, 0) . Kmin, accumulated into one tile.
-template <bool BOUND>
+// TILES tiles of 32 blocks per workgroup: the query rows are fetched once for all of them (for
+// batches, where the workgroups are many and the repeated query reads are most of the traffic).
+template <bool BOUND, int TILES>
 __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s, const uint16_t *__restrict__ kmax,
                                                                          const uint16_t *__restrict__ kmin, int reduce,
                                                                          int last_node, float *__restrict__ scores)
@@ -33,15 +35,20 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
     // the two summary tiles of this workgroup's 32 blocks: row-major, 256 B per block, the
     // 16-byte pieces of row t stored at piece index p ^ (t & 7) so that the operand reads
     // below (32 lanes, same piece, different rows) spread over all banks
-    __shared__ __attribute__((aligned(1024))) char tile[2][8192];
-    __shared__ float red[kScoreMaxWaves][64];
+    __shared__ __attribute__((aligned(1024))) char tile[2 * TILES][8192];   // [tile][Kmax | Kmin]
+    __shared__ float red[kScoreMaxWaves][64 * TILES];
     const int lane = threadIdx.x & 63, W = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, kg = lane >> 5;
     const int g = blockIdx.y, b = blockIdx.z;
-    const int i0 = blockIdx.x * 32;
+    const int i0 = blockIdx.x * 32 * TILES;
     const int R = s.M * s.G;
-    const int L = s.ctx_len[b];   // only needed at the very end: its latency overlaps with everything else
+    const int L = s.ctx_len[b];   // one sequence: only needed at the very end, its latency overlaps with everything else
+    int nb = L > 0 ? (L + s.B - 1) / s.B : 0;
+    if (nb > s.max_blocks) nb = s.max_blocks;
+    // in a batch the grid covers the longest sequence: workgroups past the end of a shorter one leave
+    // at once (there the wait for the length is cheaper than their reads)
+    if (s.batch > 1 && i0 >= nb) return;
 
     // Summary rows go from memory straight into LDS (16 DMA operations of 1 KiB shared by the
     // wavefronts; operation d brings rows 4*(d&7) .. +3 of Kmax (d < 8) or Kmin, one 256-byte
@@ -50,20 +57,20 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
     {
         const int r4 = lane >> 4, pos = lane & 15;
         const int64_t arr_row0 = ((int64_t)b * s.Hkv + g) * s.max_blocks;
-        for (int d = wave; d < 16; d += W) {
-            const int i = d & 7, row = 4 * i + r4;
-            const int blk = min(i0 + row, s.max_blocks - 1);
-            const char *src = (const char *)(d < 8 ? kmax : kmin) + ((arr_row0 + blk) * 128) * 2 + 16 * (pos ^ (row & 7));
+        for (int d = wave; d < 16 * TILES; d += W) {
+            const int i = d & 7, row = 4 * i + r4, t = d >> 4;
+            const int blk = min(i0 + 32 * t + row, s.max_blocks - 1);
+            const char *src = (const char *)((d & 8) ? kmin : kmax) + ((arr_row0 + blk) * 128) * 2 + 16 * (pos ^ (row & 7));
             __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile[d >> 3] + i * 1024), 16, 0, 2);   // streaming hint: read once
         }
     }
 
-    float acc = reduce == SPECPV_REDUCE_MAX ? -INFINITY : 0.f;
+    float acc[TILES];
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) acc[t] = reduce == SPECPV_REDUCE_MAX ? -INFINITY : 0.f;
     const uint16_t *q = (const uint16_t *)s.q;
-    const char *bxp = tile[0] + n * 256, *bnp = tile[1] + n * 256;
-    bool have_tiles = false;
-    bf16x8 bx[8], bn[8];
-    // query rows r0 .. r0+31 as A operand: lane = row
+    bool landed = false;
+    // query rows r0 .. r0+31 as A operand: lane = row (every wavefront has at least one such block)
     for (int r0 = wave * 32; r0 < R; r0 += W * 32) {
         const int r = min(r0 + n, R - 1);
         const int j = r / s.G, hh = r - j * s.G;
@@ -71,73 +78,81 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
         uint4 qa[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qa[ks] = *(const uint4 *)(qrow + ks * 16);
-        if (!have_tiles) {
-            // summary tiles as B operands: lane = block, channels 16*ks + 8*kg .. +8
+        if (!landed) {
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's DMA operations (and query rows) are in
             __syncthreads();                      // ... and so are everybody else's
+            landed = true;
+        }
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) {
+            // summary tiles as B operands: lane = block, channels 16*ks + 8*kg .. +8
+            const char *bxp = tile[2 * t] + n * 256, *bnp = tile[2 * t + 1] + n * 256;
+            bf16x8 bx[8], bn[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 const int off = (32 * ks + 16 * kg) ^ (16 * (n & 7));
                 bx[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(bxp + off));
                 bn[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(bnp + off));
             }
-            have_tiles = true;
-        }
-        f32x16 sx, sn;
+            f32x16 sx, sn;
 #pragma unroll
-        for (int x = 0; x < 16; ++x) { sx[x] = 0.f; sn[x] = 0.f; }
+            for (int x = 0; x < 16; ++x) { sx[x] = 0.f; sn[x] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            if (BOUND) {
-                // split the packed bf16 pairs by sign: 0xffff in the halves whose sign bit is set
-                uint4 neg, pos;
-                const uint32_t w[4] = {qa[ks].x, qa[ks].y, qa[ks].z, qa[ks].w};
-                uint32_t pw[4], nw[4];
+            for (int ks = 0; ks < 8; ++ks) {
+                if (BOUND) {
+                    // split the packed bf16 pairs by sign: 0xffff in the halves whose sign bit is set
+                    uint4 neg, pos;
+                    const uint32_t w[4] = {qa[ks].x, qa[ks].y, qa[ks].z, qa[ks].w};
+                    uint32_t pw[4], nw[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t m = ((w[e] >> 15) & 0x00010001u) * 0xffffu;
-                    nw[e] = w[e] & m;
-                    pw[e] = w[e] & ~m;
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t m = ((w[e] >> 15) & 0x00010001u) * 0xffffu;
+                        nw[e] = w[e] & m;
+                        pw[e] = w[e] & ~m;
+                    }
+                    pos = make_uint4(pw[0], pw[1], pw[2], pw[3]);
+                    neg = make_uint4(nw[0], nw[1], nw[2], nw[3]);
+                    sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pos), bx[ks], sx, 0, 0, 0);
+                    sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, neg), bn[ks], sx, 0, 0, 0);
+                } else {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, qa[ks]);
+                    sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[ks], sx, 0, 0, 0);
+                    sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bn[ks], sn, 0, 0, 0);
                 }
-                pos = make_uint4(pw[0], pw[1], pw[2], pw[3]);
-                neg = make_uint4(nw[0], nw[1], nw[2], nw[3]);
-                sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pos), bx[ks], sx, 0, 0, 0);
-                sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, neg), bn[ks], sx, 0, 0, 0);
-            } else {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, qa[ks]);
-                sx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bx[ks], sx, 0, 0, 0);
-                sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bn[ks], sn, 0, 0, 0);
             }
-        }
-        // accumulator slot x holds row r0 + (x>>2)*8 + kg*4 + (x&3) of this lane's block
+            // accumulator slot x holds row r0 + (x>>2)*8 + kg*4 + (x&3) of this lane's block
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-            const int row = r0 + (x >> 2) * 8 + kg * 4 + (x & 3);
-            const float sv = BOUND ? sx[x] : fmaxf(sx[x], sn[x]);
-            if (reduce == SPECPV_REDUCE_MAX) {
-                if (row < R) acc = fmaxf(acc, sv);
-            } else if (reduce == SPECPV_REDUCE_MEAN) {
-                if (row < R) acc += sv;
-            } else {
-                if (row < R && row / s.G == last_node) acc += sv;
+            for (int x = 0; x < 16; ++x) {
+                const int row = r0 + (x >> 2) * 8 + kg * 4 + (x & 3);
+                const float sv = BOUND ? sx[x] : fmaxf(sx[x], sn[x]);
+                if (reduce == SPECPV_REDUCE_MAX) {
+                    if (row < R) acc[t] = fmaxf(acc[t], sv);
+                } else if (reduce == SPECPV_REDUCE_MEAN) {
+                    if (row < R) acc[t] += sv;
+                } else {
+                    if (row < R && row / s.G == last_node) acc[t] += sv;
+                }
             }
         }
     }
-    red[wave][lane] = acc;
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) red[wave][64 * t + lane] = acc[t];
     __syncthreads();
-    if (wave != 0) return;
+    if (wave >= TILES) return;
+    // wavefront t finishes tile t
+    const int t = wave;
+    float a = red[0][64 * t + lane];
     for (int w = 1; w < W; ++w) {
-        const float o = red[w][lane];
-        acc = reduce == SPECPV_REDUCE_MAX ? fmaxf(acc, o) : acc + o;
+        const float o = red[w][64 * t + lane];
+        a = reduce == SPECPV_REDUCE_MAX ? fmaxf(a, o) : a + o;
     }
-    const float other = __shfl_xor(acc, 32);
+    const float other = __shfl_xor(a, 32);
     float out;
-    if (reduce == SPECPV_REDUCE_MAX) out = fmaxf(acc, other);
-    else if (reduce == SPECPV_REDUCE_MEAN) out = (acc + other) / (float)R;
-    else out = (acc + other) / (float)s.G;
-    int nb = L > 0 ? (L + s.B - 1) / s.B : 0;
-    if (nb > s.max_blocks) nb = s.max_blocks;
-    if (kg == 0 && i0 + n < nb) scores[((int64_t)b * s.Hkv + g) * s.max_blocks + i0 + n] = out;
+    if (reduce == SPECPV_REDUCE_MAX) out = fmaxf(a, other);
+    else if (reduce == SPECPV_REDUCE_MEAN) out = (a + other) / (float)R;
+    else out = (a + other) / (float)s.G;
+    const int blk = i0 + 32 * t + n;
+    if (kg == 0 && blk < nb) scores[((int64_t)b * s.Hkv + g) * s.max_blocks + blk] = out;
 }
 
 bool score_mfma_supported(const Shape &s, int dtype) { return dtype == SPECPV_BF16 && s.D == 128; }
@@ -145,14 +160,22 @@ bool score_mfma_supported(const Shape &s, int dtype) { return dtype == SPECPV_BF
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
                               int last_node, int kind, float *scores, hipStream_t st)
 {
-    const int tiles = (s.max_blocks + 31) / 32, row_tiles = (s.M * s.G + 31) / 32;
-    dim3 grid(tiles, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
-    if (kind == SPECPV_SCORE_CHANNEL_BOUND)
-        hipLaunchKernelGGL(score_mfma_kernel<true>, grid, block, 0, st, s, (const uint16_t *)kmax,
-                           (const uint16_t *)kmin, reduce, last_node, scores);
-    else
-        hipLaunchKernelGGL(score_mfma_kernel<false>, grid, block, 0, st, s, (const uint16_t *)kmax,
-                           (const uint16_t *)kmin, reduce, last_node, scores);
+    // one wavefront per block of 32 query rows; two tiles per workgroup need two wavefronts to finish them
+    const int row_tiles = (s.M * s.G + 31) / 32;
+    const int tiles1 = (s.max_blocks + 31) / 32;
+    // two tiles per workgroup where the workgroups are many (measured at one 128K sequence, 512
+    // workgroups: 10.3 us against 9.6 with one tile; at four sequences, 2048 workgroups, see the design notes)
+    const bool two = row_tiles >= 2 && (int64_t)tiles1 * s.Hkv * s.batch >= 4 * (int64_t)device_cu_count();
+    dim3 grid(two ? (tiles1 + 1) / 2 : tiles1, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
+#define SPECPV_LAUNCH(BOUND, TILES) \
+    hipLaunchKernelGGL((score_mfma_kernel<BOUND, TILES>), grid, block, 0, st, s, (const uint16_t *)kmax, \
+                       (const uint16_t *)kmin, reduce, last_node, scores)
+    if (kind == SPECPV_SCORE_CHANNEL_BOUND) {
+        if (two) SPECPV_LAUNCH(true, 2); else SPECPV_LAUNCH(true, 1);
+    } else {
+        if (two) SPECPV_LAUNCH(false, 2); else SPECPV_LAUNCH(false, 1);
+    }
+#undef SPECPV_LAUNCH
     return hipGetLastError();
 }
 
