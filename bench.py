@@ -319,7 +319,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if n_layers == cfg["layers"] else None,
-                     "kernel": "attn_ctx_mfma_kernel + combine_kernel = one specpv_partial_verify_attn call (one layer)",
+                     "kernel": "context attention (attn_ctx_mfma_kernel at the default workload; the planner picks by shape) + combine_kernel = one specpv_partial_verify_attn call (one layer)",
                      "algorithmic_bytes_per_launch": bytes_layer, "us_per_launch": round(us_layer, 3),
                      "box_copy_GBs": extras.get("hbm_copy_ceiling_GBs"), "box_read_stream_GBs": extras.get("hbm_read_stream_GBs")},
         "cpu_baseline": cpu,
