@@ -176,3 +176,44 @@ def test_commit_of_all_layers_validates_on_the_host():
     assert call(two, kmax=(0x50000, 0), kmin=(0x70000, 0x80000)) == -1
     assert call(two, kmax=(0x50000, 0x60000), kmin=(0x70000, 0x80000)) == -2
     assert call(two, pending_cap=120) == -3
+
+
+def test_workspace_size_is_a_consistent_split_plan():
+    """specpv_workspace_bytes is host-only and deterministic.  Its value is the layout the calls use:
+    partial O [batch, Hq, splits, M, D] fp32 + (m, l) pairs [batch, Hq, splits, M, 2] fp32 + one score
+    per block, each part rounded up to 256 bytes, for ONE split count between 1 and 64; and a
+    selection can only add to what the full pass needs."""
+    import random
+    lib = specpv.load()
+    up = lambda x: (x + 255) & ~255
+    rnd = random.Random(5)
+
+    def splits_of(total, batch, Hq, Hkv, M, D, nb):
+        sc = up(batch * Hkv * nb * 4)
+        for ns in range(1, 65):
+            if up(batch * Hq * ns * M * D * 4) + up(batch * Hq * ns * M * 8) + sc == total:
+                return ns
+        return None
+
+    for _ in range(300):
+        Hkv = rnd.choice([1, 2, 4, 8])
+        G = rnd.choice([1, 2, 3, 4, 5, 8, 16])
+        D = rnd.choice([64, 128])
+        dtype = rnd.choice([0, 1])
+        B = rnd.choice([7, 16, 32, 64, 128])
+        nb = rnd.choice([1, 3, 17, 64, 500, 2048, 8192])
+        M = rnd.choice([1, 9, 24, 60, 100, 128])
+        batch = rnd.choice([1, 2, 4, 16])
+        kv = _kv(batch=batch, n_kv_heads=Hkv, head_dim=D, block_size=B, max_blocks=nb, dtype=dtype,
+                 stride_t=D, stride_h=nb * B * D, stride_b=Hkv * nb * B * D)
+        tree = _tree(M=M, n_q_heads=Hkv * G)
+        full = lib.specpv_workspace_bytes(ctypes.byref(kv), ctypes.byref(tree), None)
+        assert full == lib.specpv_workspace_bytes(ctypes.byref(kv), ctypes.byref(tree), None)
+        ns_full = splits_of(full, batch, Hkv * G, Hkv, M, D, nb)
+        assert ns_full is not None, (Hkv, G, D, dtype, B, nb, M, batch, full)
+        cfg = _cfg(n_sink_blocks=1, n_recent_blocks=2, k_blocks=rnd.choice([0, 4, 29, 61, 253]))
+        both = lib.specpv_workspace_bytes(ctypes.byref(kv), ctypes.byref(tree), ctypes.byref(cfg))
+        assert both >= full
+        assert splits_of(both, batch, Hkv * G, Hkv, M, D, nb) is not None
+    # no tree: only the per-sequence counters of the summary call
+    assert lib.specpv_workspace_bytes(ctypes.byref(_kv()), None, None) >= 256
