@@ -44,6 +44,18 @@ __host__ __device__ constexpr int partial_chan(int p, int D)
 {
     return D == 128 ? ((p & 63) >> 2) * 8 + (p >> 6) * 4 + (p & 3) : p;
 }
+constexpr bool partial_order_is_a_permutation()
+{
+    for (int D = 64; D <= 128; D += 64)
+        for (int p = 0; p < D; ++p) {
+            const int c = partial_chan(p, D);
+            if (c < 0 || c >= D || partial_pos(c, D) != p) return false;
+            // a lane's 16-byte piece holds four consecutive channels, in order
+            if ((p & 3) != 0 && c != partial_chan(p - 1, D) + 1) return false;
+        }
+    return true;
+}
+static_assert(partial_order_is_a_permutation(), "partial_pos / partial_chan must be inverse permutations of a row");
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
