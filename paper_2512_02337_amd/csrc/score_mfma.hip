@@ -160,20 +160,22 @@ bool score_mfma_supported(const Shape &s, int dtype) { return dtype == SPECPV_BF
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
                               int last_node, int kind, float *scores, hipStream_t st)
 {
-    // one wavefront per block of 32 query rows; two tiles per workgroup need two wavefronts to finish them
+    // one wavefront per block of 32 query rows; T tiles per workgroup need T wavefronts to finish them
     const int row_tiles = (s.M * s.G + 31) / 32;
     const int tiles1 = (s.max_blocks + 31) / 32;
-    // two tiles per workgroup where the workgroups are many (measured at one 128K sequence, 512
-    // workgroups: 10.3 us against 9.6 with one tile; at four sequences, 2048 workgroups, see the design notes)
-    const bool two = row_tiles >= 2 && (int64_t)tiles1 * s.Hkv * s.batch >= 4 * (int64_t)device_cu_count();
-    dim3 grid(two ? (tiles1 + 1) / 2 : tiles1, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
+    // two or four tiles per workgroup where the workgroups are many (measured: at one 128K sequence,
+    // 512 workgroups, 10.3 us with two tiles against 9.6 with one; at four sequences, 2048
+    // workgroups, 46 us with one tile, 33 with two, 29 with four)
+    const int64_t wgs1 = (int64_t)tiles1 * s.Hkv * s.batch, cus = device_cu_count();
+    const int T = (row_tiles >= 4 && wgs1 >= 8 * cus) ? 4 : ((row_tiles >= 2 && wgs1 >= 4 * cus) ? 2 : 1);
+    dim3 grid((tiles1 + T - 1) / T, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
 #define SPECPV_LAUNCH(BOUND, TILES) \
     hipLaunchKernelGGL((score_mfma_kernel<BOUND, TILES>), grid, block, 0, st, s, (const uint16_t *)kmax, \
                        (const uint16_t *)kmin, reduce, last_node, scores)
     if (kind == SPECPV_SCORE_CHANNEL_BOUND) {
-        if (two) SPECPV_LAUNCH(true, 2); else SPECPV_LAUNCH(true, 1);
+        if (T == 4) SPECPV_LAUNCH(true, 4); else if (T == 2) SPECPV_LAUNCH(true, 2); else SPECPV_LAUNCH(true, 1);
     } else {
-        if (two) SPECPV_LAUNCH(false, 2); else SPECPV_LAUNCH(false, 1);
+        if (T == 4) SPECPV_LAUNCH(false, 4); else if (T == 2) SPECPV_LAUNCH(false, 2); else SPECPV_LAUNCH(false, 1);
     }
 #undef SPECPV_LAUNCH
     return hipGetLastError();
