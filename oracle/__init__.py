@@ -124,13 +124,23 @@ def select_blocks(scores, ns, nr, k):
     return sel_idx, sel_count
 
 
-def tree_attention(Q, K, V, Kd, Vd, parent, B, sel_idx=None, sel_count=None):
+def tree_attention(Q, K, V, Kd, Vd, parent, B, sel_idx=None, sel_count=None, n_key_only=0):
     """Tree-masked GQA attention over the kept context blocks plus the draft
     nodes on each node's root path.  sel_idx None = every block (full
-    verification).  Returns (O [M,Hq,D], lse [M,Hq], psum [M,Hq])."""
+    verification).  Returns (O [Mq,Hq,D], lse [Mq,Hq], psum [Mq,Hq]).
+
+    n_key_only: the first n_key_only of the M = len(parent) nodes are keys only (Section 3.2:
+    the partially verified tokens wait in the buffer and are attended by the candidates, but a
+    partial step does not verify them again): they have rows in Kd / Vd and entries in parent,
+    but no query rows; Q holds the Mq = M - n_key_only rows of the other nodes.  The rows of the
+    key-only nodes are computed with zero queries and thrown away."""
     Q, K, V, Kd, Vd = _f64(Q), _f64(K), _f64(V), _f64(Kd), _f64(Vd)
     parent = _i32(parent)
-    M, Hq, D = Q.shape
+    M = parent.shape[0]
+    Mq, Hq, D = Q.shape
+    assert Mq == M - n_key_only and Kd.shape[0] == M and Vd.shape[0] == M
+    if n_key_only:
+        Q = np.ascontiguousarray(np.concatenate([np.zeros((n_key_only, Hq, D)), Q]))
     L, Hkv, _ = K.shape
     assert parent[0] == -1 and all(parent[i] < i for i in range(1, M))
     n_sel = 0
@@ -143,7 +153,7 @@ def tree_attention(Q, K, V, Kd, Vd, parent, B, sel_idx=None, sel_count=None):
     _load().oracle_tree_attention(_p(Q), _p(K), _p(V), _p(Kd), _p(Vd), _p(parent),
                                   M, Hq, Hkv, D, L, B, _p(sel_idx), _p(sel_count),
                                   n_sel, _p(O), _p(lse), _p(psum))
-    return O, lse, psum
+    return O[n_key_only:], lse[n_key_only:], psum[n_key_only:]
 
 
 def full_verify_refresh(Q, K, V, Kd, Vd, parent, B, ns, nr, k, reduce="mean", last_node=0):
@@ -185,17 +195,22 @@ def extend_parents(tree_parent, n_pending):
     return out
 
 
-def commit_accepted(K, V, L, pend_k, pend_v, cand_k, cand_v, accepted, mode, capacity):
+def commit_accepted(K, V, L, pend_k, pend_v, cand_k, cand_v, accepted, mode, capacity, pending_cap=None):
     """Sections 3.2 / 3.3, KV side of PostEvaluate for one sequence.
     K, V [capacity, Hkv, D] cache with L committed tokens; pend_k / pend_v: lists of the
     pending tokens' rows [Hkv, D] (oldest first); cand_k / cand_v [M, Hkv, D] this step's
     candidates; accepted: the candidates on the accepted path.  Returns (L, pend_k, pend_v):
     partial verification keeps the accepted candidates as pending tokens; full verification
     and refresh append the pending tokens and then the accepted candidates to the cache.
-    Everything else of this step's candidates is dropped."""
+    Everything else of this step's candidates is dropped.
+    Storage is finite: the cache holds `capacity` tokens and the buffer `pending_cap` pending
+    tokens (None: unbounded).  Tokens are stored oldest first while there is room; the ones
+    that do not fit are lost, and `commit_dropped` says how many that is."""
     rows_k = list(pend_k) + [cand_k[a] for a in accepted]
     rows_v = list(pend_v) + [cand_v[a] for a in accepted]
     if mode == MODE_PARTIAL:
+        if pending_cap is not None:
+            rows_k, rows_v = rows_k[:pending_cap], rows_v[:pending_cap]
         return L, rows_k, rows_v
     for rk, rv in zip(rows_k, rows_v):
         if L >= capacity:
@@ -204,6 +219,42 @@ def commit_accepted(K, V, L, pend_k, pend_v, cand_k, cand_v, accepted, mode, cap
         V[L] = rv
         L += 1
     return L, [], []
+
+
+def commit_dropped(L, n_pending, n_accepted, mode, capacity, pending_cap=None):
+    """How many of the n_pending + n_accepted tokens `commit_accepted` cannot store."""
+    total = n_pending + n_accepted
+    if mode == MODE_PARTIAL:
+        return 0 if pending_cap is None else max(0, total - pending_cap)
+    return max(0, total - max(0, capacity - L))
+
+
+def extend_lists(sel_idx, sel_count, L_old, L_new, B):
+    """Section 3.3 (after a full verification only the invalid tokens are removed, the local
+    window is updated): the tokens a full verification / refresh commits stay part of the partial
+    cache.  The kept-block lists were built for the length L_old; every block that holds one of
+    the tokens L_old .. L_new - 1 joins each head's list (ascending order is kept: these blocks
+    lie behind every listed one, except that the first of them may already be listed as the
+    ragged last block of the local window).  sel_idx [Hkv, n_sel] (-1 padded), sel_count [Hkv].
+    Returns (sel_idx, sel_count, not_listed): new arrays, and per head the number of blocks for
+    which the row had no free entry."""
+    sel_idx = np.array(sel_idx, dtype=np.int32, copy=True)
+    sel_count = np.array(sel_count, dtype=np.int32, copy=True)
+    Hkv, n_sel = sel_idx.shape
+    not_listed = np.zeros(Hkv, dtype=np.int32)
+    if L_new <= L_old:
+        return sel_idx, sel_count, not_listed
+    first, last = L_old // B, (L_new - 1) // B
+    for g in range(Hkv):
+        for blk in range(first, last + 1):
+            if blk in sel_idx[g, :sel_count[g]].tolist():
+                continue
+            if sel_count[g] >= n_sel:
+                not_listed[g] += 1
+                continue
+            sel_idx[g, sel_count[g]] = blk
+            sel_count[g] += 1
+    return sel_idx, sel_count, not_listed
 
 
 def gather_blocks(K, V, B, sel_idx, sel_count):

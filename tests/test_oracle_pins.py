@@ -516,3 +516,88 @@ def test_gathered_cache_gives_the_same_attention_as_the_lists():
     O2, lse2, _ = oracle.tree_attention(Q, Kg[:rows[0]], Vg[:rows[0]], Kd, Vd, parent, B)
     np.testing.assert_allclose(O1, O2, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(lse1, lse2, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ finite storage, key-only nodes, list upkeep
+def test_commit_with_finite_storage_hand_example():
+    g = json.load(open(os.path.join(GOLD, "commit_hand_example.json")))
+    for name in ("cache_full", "buffer_full"):
+        c = g[name]
+        cap = c.get("capacity", 16)
+        K, V = np.zeros((cap, 1, 1)), np.zeros((cap, 1, 1))
+        K[:c["L"], 0, 0] = np.arange(1, c["L"] + 1)
+        V[:] = -K
+        pk = [np.full((1, 1), x) for x in c["pending"]]
+        pv = [-x for x in pk]
+        ck = np.array(c["candidates"]).reshape(-1, 1, 1)
+        mode = {"refresh": oracle.MODE_REFRESH, "partial": oracle.MODE_PARTIAL}[c["mode"]]
+        L, pk2, pv2 = oracle.commit_accepted(K, V, c["L"], pk, pv, ck, -ck, c["accepted"], mode, cap, c.get("pending_cap"))
+        assert L == c["L_after"]
+        assert [float(x[0, 0]) for x in pk2] == c["pending_after"] and [float(x[0, 0]) for x in pv2] == [-x for x in c["pending_after"]]
+        if "cache_tail_after" in c:
+            assert K[c["L"]:L, 0, 0].tolist() == c["cache_tail_after"] and V[c["L"]:L, 0, 0].tolist() == [-x for x in c["cache_tail_after"]]
+        assert K[:c["L"], 0, 0].tolist() == list(range(1, c["L"] + 1))
+        assert oracle.commit_dropped(c["L"], len(c["pending"]), len(c["accepted"]), mode, cap, c.get("pending_cap")) == c["dropped"]
+
+
+def test_extend_lists_hand_example():
+    g = json.load(open(os.path.join(GOLD, "commit_hand_example.json")))
+    for c in g["extend_lists"]:
+        src = np.array(c["sel_idx"], np.int32)
+        idx, cnt, miss = oracle.extend_lists(src, np.array(c["sel_count"], np.int32), c["L_old"], c["L_new"], c["B"])
+        assert idx.tolist() == c["sel_idx_after"] and cnt.tolist() == c["sel_count_after"] and miss.tolist() == c["not_listed"], c["_note"]
+        assert src.tolist() == c["sel_idx"]      # the input is not written
+
+
+def test_key_only_nodes_are_keys_without_query_rows():
+    """A node without a query row is attended like any other draft node; its own (absent) output does not
+    exist.  Equals the rows of the other nodes when the key-only nodes are given arbitrary queries."""
+    rng = np.random.default_rng(17)
+    Hq, Hkv, D, B, L, n, M = 4, 2, 8, 4, 23, 3, 6
+    K, V = rng.standard_normal((L, Hkv, D)), rng.standard_normal((L, Hkv, D))
+    Kd, Vd = rng.standard_normal((n + M, Hkv, D)), rng.standard_normal((n + M, Hkv, D))
+    Q = rng.standard_normal((M, Hq, D))
+    ext = np.array(oracle.extend_parents(workloads.make_tree(M, "bounded", rng), n), dtype=np.int32)
+    sel, cnt = np.array([[0, 2, 5], [1, 3, 5]], np.int32), np.array([3, 3], np.int32)
+    O1, lse1, ps1 = oracle.tree_attention(Q, K, V, Kd, Vd, ext, B, sel, cnt, n_key_only=n)
+    Qe = np.concatenate([rng.standard_normal((n, Hq, D)), Q])
+    O2, lse2, ps2 = oracle.tree_attention(Qe, K, V, Kd, Vd, ext, B, sel, cnt)
+    assert O1.shape == (M, Hq, D) and np.array_equal(O1, O2[n:]) and np.array_equal(lse1, lse2[n:])
+    np.testing.assert_allclose(ps1, 1.0, rtol=1e-12)
+
+
+@pytest.mark.parametrize("L_old,m", [(37, 6), (40, 3), (38, 11), (43, 1)])
+def test_lists_extended_at_a_commit_keep_every_committed_token(L_old, m):
+    """Section 3.3: what a refresh commits stays in the partial cache.  Before the commit the candidates of the
+    next step would see `kept blocks + the m tokens as pending chain`; after it they must see the same keys
+    through `kept blocks extended by the blocks the m tokens went to` -- no token lost, none gained."""
+    rng = np.random.default_rng(100 + L_old)
+    Hq, Hkv, D, B, M, cap = 4, 2, 8, 4, 7, 64
+    ns, nr, k = 1, 2, 3
+    K, V = np.zeros((cap, Hkv, D)), np.zeros((cap, Hkv, D))
+    K[:L_old], V[:L_old] = rng.standard_normal((L_old, Hkv, D)), rng.standard_normal((L_old, Hkv, D))
+    nb = (L_old + B - 1) // B
+    sc = rng.standard_normal((Hkv, nb))
+    sel, cnt = oracle.select_blocks(sc, ns, nr, k)                 # what the refresh built for L_old
+    sel = np.concatenate([sel, np.full((Hkv, 4), -1, np.int32)], axis=1)   # room for the blocks to come
+    pk, pv = rng.standard_normal((m, Hkv, D)), rng.standard_normal((m, Hkv, D))
+    Q, Kd, Vd = rng.standard_normal((M, Hq, D)), rng.standard_normal((M, Hkv, D)), rng.standard_normal((M, Hkv, D))
+    tree = workloads.make_tree(M, "bounded", rng)
+    ext = np.array(oracle.extend_parents(tree, m), dtype=np.int32)
+    O1, lse1, _ = oracle.tree_attention(Q, K[:L_old], V[:L_old], np.concatenate([pk, Kd]), np.concatenate([pv, Vd]),
+                                        ext, B, sel, cnt, n_key_only=m)
+    L_new, _, _ = oracle.commit_accepted(K, V, L_old, list(pk), list(pv), Kd, Vd, [], oracle.MODE_REFRESH, cap)
+    assert L_new == L_old + m
+    sel2, cnt2, miss = oracle.extend_lists(sel, cnt, L_old, L_new, B)
+    assert not miss.any()
+    for g in range(Hkv):
+        row = sel2[g, :cnt2[g]].tolist()
+        assert row == sorted(set(row)) and row[:cnt[g]] == sel[g, :cnt[g]].tolist()
+        assert set(range(L_old // B, (L_new - 1) // B + 1)) <= set(row)
+    O2, lse2, _ = oracle.tree_attention(Q, K[:L_new], V[:L_new], Kd, Vd, np.array(tree, np.int32), B, sel2, cnt2)
+    np.testing.assert_allclose(O1, O2, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(lse1, lse2, rtol=1e-11, atol=1e-12)
+    # ... whereas the lists as the refresh left them lose the tokens that opened a new block
+    if (L_new - 1) // B > (L_old - 1) // B or L_old % B == 0:
+        O3, _, _ = oracle.tree_attention(Q, K[:L_new], V[:L_new], Kd, Vd, np.array(tree, np.int32), B, sel, cnt)
+        assert np.abs(O3 - O1).max() > 1e-6
