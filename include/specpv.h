@@ -22,9 +22,11 @@
  *    nothing has been enqueued.  Device-side quantities (ctx_len, sel_count,
  *    entries of sel_idx, parent) are bounds-checked inside the kernels: blocks or
  *    tokens outside the sequence are ignored, they are never dereferenced.
- *  - The calls keep no mutable global state and may be issued from several
- *    threads on different streams.  Two calls that share a workspace must be
- *    ordered by the caller (same stream, or events).
+ *  - The calls may be issued from several threads, on different streams and on different
+ *    devices (the device that is current at the call is used).  The only state the library
+ *    keeps is a per-device record of one-time kernel attribute set-up, guarded for concurrent
+ *    first calls.  Two calls that share a workspace must be ordered by the caller (same
+ *    stream, or events).
  *
  * Notation: L_b committed tokens of sequence b, B block size, nb_b = ceil(L_b/B),
  * Hq query heads, Hkv KV heads, G = Hq/Hkv, D head dim, M draft-tree nodes (the
@@ -81,14 +83,20 @@ typedef struct specpv_kv {
 } specpv_kv;
 
 /* The draft tree: the query tokens of this verify step, and their own K/V (the
- * "buffer" part of the partial cache, Section 3.2).  On a refresh step the
- * partially verified tokens are a chain prefix of parent[] (Section 3.3). */
+ * "buffer" part of the partial cache, Section 3.2).  The partially verified
+ * tokens are a chain prefix of parent[] (Section 3.3): on a refresh step they are
+ * verified again, i.e. they are ordinary nodes; on a partial step they are only
+ * attended, i.e. the first n_key_only nodes have K/V rows and parent entries but
+ * NO query rows and no output rows.  Mq = M - n_key_only is the number of query
+ * nodes; query row r belongs to node n_key_only + r. */
 typedef struct specpv_tree {
-    const void *q;         /* [batch, M, Hq, D] contiguous, post-RoPE                    */
+    const void *q;         /* [batch, Mq, Hq, D] contiguous, post-RoPE                   */
     const void *kd, *vd;   /* [batch, M, Hkv, D] contiguous; may be NULL for select      */
     const int32_t *parent; /* device, [batch, M]; parent[0] = -1, parent[i] < i          */
     int32_t M, n_q_heads;
-    int32_t last_node;     /* node whose queries SPECPV_REDUCE_LAST keeps (normally 0)   */
+    int32_t last_node;     /* node whose queries SPECPV_REDUCE_LAST keeps (normally the
+                              tree root: n_key_only); n_key_only <= last_node < M        */
+    int32_t n_key_only;    /* 0 <= n_key_only < M                                        */
 } specpv_tree;
 
 /* Composition of the partial cache in blocks (Section 3.2): always the first
@@ -98,6 +106,8 @@ typedef struct specpv_select_cfg {
     int32_t n_sink_blocks, n_recent_blocks, k_blocks;
     specpv_reduce reduce;
     specpv_score score;    /* SPECPV_SCORE_EQ2 (= 0) is the paper's                        */
+    int32_t n_extra_slots; /* free entries behind the ns + k + nr of a list row, for the blocks
+                              that later commits append (specpv_commit_accepted); >= 0       */
 } specpv_select_cfg;
 
 /* Bytes of workspace that any of the calls below needs for these descriptors
@@ -120,7 +130,7 @@ int specpv_block_summarize(const specpv_kv *kv, int32_t blk_begin, int32_t blk_e
  *   kept = blocks [0, ns) + the k best candidates of [ns, nb_b - nr) by (fp32
  *   score descending, block index ascending) + blocks [nb_b - nr, nb_b);
  *   every block if nb_b <= ns + k + nr.
- * sel_idx   [batch, Hkv, n_sel] int32, n_sel = ns + k + nr, ascending, padded with -1.
+ * sel_idx   [batch, Hkv, n_sel] int32, n_sel = ns + k + nr + n_extra_slots, ascending, padded with -1.
  * sel_count [batch, Hkv] int32.
  * scores    optional [batch, Hkv, max_blocks] fp32 (NULL: kept in the workspace). */
 int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree,
@@ -134,10 +144,11 @@ int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree,
  *          + draft nodes a that are j or an ancestor of j;
  *   out[b, j, h, :] = softmax(q . k / sqrt(D)) . v over those keys (fp32
  *   accumulation, result in the q dtype); lse[b, j, h] = log sum exp (natural log).
+ *   Only the Mq query nodes have rows in q, out and lse (row j - n_key_only).
  * sel_idx == NULL attends over every block (full verification).  The order of
  * sel_idx does not matter; entries < 0 or >= nb_b are ignored; a block listed
  * twice is attended twice.
- * out [batch, M, Hq, D]; lse optional [batch, M, Hq] fp32. */
+ * out [batch, Mq, Hq, D]; lse optional [batch, Mq, Hq] fp32. */
 int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree,
                                const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
                                void *out, float *lse,
@@ -178,8 +189,9 @@ int specpv_gather_blocks(const specpv_kv *kv, const int32_t *sel_idx, const int3
  * rows pending_cap .. pending_cap + M_tree - 1 this step's candidates.  A verify step
  * then passes the rows from pending_cap - n_pending on as kd / vd of a tree with
  * n_pending + M_tree nodes whose parent array is a chain over the pending tokens with the
- * candidates' tree hanging off its end (specpv_extend_parents); in a refresh step the
- * pending tokens are queries as well and their K/V rows have been recomputed by the caller. */
+ * candidates' tree hanging off its end (specpv_extend_parents).  In a partial step the pending
+ * tokens are keys only (tree.n_key_only = n_pending: no query rows); in a refresh step they are
+ * queries as well (n_key_only = 0) and their K/V rows have been recomputed by the caller. */
 typedef enum { SPECPV_MODE_FULL = 0, SPECPV_MODE_PARTIAL = 1, SPECPV_MODE_REFRESH = 2 } specpv_mode;
 
 typedef struct specpv_policy {
@@ -200,37 +212,57 @@ int specpv_select_mode(const specpv_policy *policy, int64_t seq_len, int32_t par
  * above: out[i] = i - 1 for the pending chain, the candidates' roots get n_pending - 1. */
 int specpv_extend_parents(const int32_t *tree_parent, int32_t M_tree, int32_t n_pending, int32_t *out);
 
+/* The kept-block lists of one layer, as specpv_select_blocks / specpv_full_verify_refresh wrote
+ * them: sel_idx [batch, Hkv, n_sel], sel_count [batch, Hkv] (device). */
+typedef struct specpv_lists {
+    int32_t *sel_idx, *sel_count;
+    int32_t n_sel;
+} specpv_lists;
+
 /* Section 3.2 (the buffer: "invalid tokens can be removed once verification is completed")
  * and Section 3.3 ("we remove the invalid tokens from both the partial and the full KV
  * cache").  accepted [batch, max_accept] int32 (device): the candidates on the accepted
  * path as indices 0 .. M_tree-1 in increasing order; n_accepted [batch] (device).
  *   mode PARTIAL: the accepted candidates' K/V rows join the pending tokens (the buffer is
  *     compacted: everything else of this step's candidates is dropped);
- *     n_pending_b += n_accepted_b (clamped to pending_cap).
+ *     n_pending_b += n_accepted_b, at most pending_cap.
  *   mode FULL / REFRESH: the pending tokens' rows, then the accepted candidates' rows, are
- *     appended to the cache at tokens L_b, L_b + 1, ...; L_b grows by their number (clamped to
- *     max_blocks * B), n_pending_b = 0, and the summaries (eq. 1) of every block that
- *     received a token are recomputed (kmax == NULL: skipped).
+ *     appended to the cache at tokens L_b, L_b + 1, ...; L_b grows by their number, at most to
+ *     max_blocks * B; n_pending_b = 0; the summaries (eq. 1) of every block that received a
+ *     token are recomputed (kmax == NULL: skipped); and, Section 3.3 ("the local window is
+ *     updated"), with lists != NULL every block that received a token joins each KV head's
+ *     list behind its last entry unless it is that entry already (the ragged last block of the
+ *     local window), so that the committed tokens stay visible to the partial steps that follow.
+ *     A row of n_sel entries needs n_extra_slots >= ceil((pending_cap + max_accept) / B) + 1
+ *     free ones for that.
+ * Storage is finite: tokens are stored oldest first while the cache (or the buffer) has room.
+ * dropped (device, [batch, 2] int32, may be NULL) receives what did not fit: [b, 0] the number
+ * of tokens of sequence b that were NOT stored, [b, 1] the largest number of blocks that found
+ * no free entry in a list row of sequence b.  Both are 0 unless the caller under-sized the
+ * cache, the buffer or the list rows; a caller that cannot rule that out has to check them.
  * Writes through kv->k, kv->v (rows from L_b on; the allocation must cover max_blocks * B
  * tokens) and kv->ctx_len, n_pending [batch] (device), in stream order.  Workspace: 4 bytes
  * per sequence (specpv_workspace_bytes covers it). */
 int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_t pending_cap, int32_t M_tree,
                            int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
                            int32_t max_accept, specpv_mode mode, void *kmax, void *kmin,
+                           const specpv_lists *lists, int32_t *dropped,
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same for the n_layers layers of a model in one go (the accepted path is the same for every
  * layer of a verify step).  kv, buf_k, buf_v, kmax, kmin: HOST arrays of n_layers descriptors /
- * device pointers (kmax, kmin may be NULL, or arrays of NULLs, to skip the summaries).  All
+ * device pointers (kmax, kmin may be NULL, or arrays of NULLs, to skip the summaries); lists: a
+ * HOST array of n_layers list descriptors with one n_sel, or NULL.  All
  * layers must share one shape, one set of strides, one dtype and ONE ctx_len array; the counters
  * (ctx_len, n_pending) are read by every layer's copies and updated once afterwards, so the
  * result is what specpv_commit_accepted would give per layer on private copies of the counters.
- * 1 <= n_layers <= SPECPV_MAX_LAYERS.  Three launches for up to 32 layers instead of three per layer. */
+ * 1 <= n_layers <= SPECPV_MAX_LAYERS.  A few launches for up to 32 layers instead of a few per layer. */
 #define SPECPV_MAX_LAYERS 256
 int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k, void *const *buf_v,
                                   int32_t n_layers, int32_t pending_cap, int32_t M_tree,
                                   int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
                                   int32_t max_accept, specpv_mode mode, void *const *kmax, void *const *kmin,
+                                  const specpv_lists *lists, int32_t *dropped,
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 const char *specpv_strerror(int status);

@@ -43,7 +43,11 @@ class _KV(ctypes.Structure):
 class _Tree(ctypes.Structure):
     _fields_ = [("q", ctypes.c_void_p), ("kd", ctypes.c_void_p), ("vd", ctypes.c_void_p),
                 ("parent", ctypes.c_void_p), ("M", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
-                ("last_node", ctypes.c_int32)]
+                ("last_node", ctypes.c_int32), ("n_key_only", ctypes.c_int32)]
+
+
+class _Lists(ctypes.Structure):
+    _fields_ = [("sel_idx", ctypes.c_void_p), ("sel_count", ctypes.c_void_p), ("n_sel", ctypes.c_int32)]
 
 
 class _Policy(ctypes.Structure):
@@ -52,7 +56,8 @@ class _Policy(ctypes.Structure):
 
 class _Cfg(ctypes.Structure):
     _fields_ = [("n_sink_blocks", ctypes.c_int32), ("n_recent_blocks", ctypes.c_int32),
-                ("k_blocks", ctypes.c_int32), ("reduce", ctypes.c_int), ("score", ctypes.c_int)]
+                ("k_blocks", ctypes.c_int32), ("reduce", ctypes.c_int), ("score", ctypes.c_int),
+                ("n_extra_slots", ctypes.c_int32)]
 
 
 _lib = None
@@ -90,10 +95,11 @@ def load():
     lib.specpv_extend_parents.restype = ctypes.c_int
     lib.specpv_extend_parents.argtypes = [P(i32), i32, i32, P(i32)]
     lib.specpv_commit_accepted.restype = ctypes.c_int
-    lib.specpv_commit_accepted.argtypes = [P(_KV), vp, vp, i32, i32, vp, vp, vp, i32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.specpv_commit_accepted.argtypes = [P(_KV), vp, vp, i32, i32, vp, vp, vp, i32, ctypes.c_int, vp, vp,
+                                           P(_Lists), vp, vp, sz, vp]
     lib.specpv_commit_accepted_layers.restype = ctypes.c_int
     lib.specpv_commit_accepted_layers.argtypes = [P(P(_KV)), P(vp), P(vp), i32, i32, i32, vp, vp, vp, i32, ctypes.c_int,
-                                                  P(vp), P(vp), vp, sz, vp]
+                                                  P(vp), P(vp), P(_Lists), vp, vp, sz, vp]
     lib.specpv_strerror.restype = ctypes.c_char_p
     lib.specpv_strerror.argtypes = [ctypes.c_int]
     lib.specpv_last_hip_error.restype = ctypes.c_char_p
@@ -163,15 +169,25 @@ class KV:
 
 class Tree:
     """The draft tree of one verify step (descriptor `specpv_tree`).
-    q [batch, M, Hq, D]; kd, vd [batch, M, Hkv, D]; parent int32 [batch, M]."""
+    kd, vd [batch, M, Hkv, D]; parent int32 [batch, M]; q [batch, Mq, Hq, D] with Mq <= M: the
+    first M - Mq nodes are keys only (the partially verified tokens on a partial step)."""
 
-    def __init__(self, q, kd=None, vd=None, parent=None, last_node=0):
+    def __init__(self, q, kd=None, vd=None, parent=None, last_node=None):
         if q.dim() != 4:
-            raise ValueError("q: [batch, M, Hq, D]")
+            raise ValueError("q: [batch, Mq, Hq, D]")
         self.q, self.kd, self.vd, self.parent = q, kd, vd, parent
-        self.batch, self.M, self.Hq, self.D = q.shape
+        self.batch, self.Mq, self.Hq, self.D = q.shape
+        self.M = self.Mq
+        for t in (kd, vd):
+            if t is not None:
+                self.M = t.shape[1]
+        if parent is not None:
+            self.M = parent.shape[1]
+        if self.M < self.Mq:
+            raise ValueError("fewer tree nodes than query rows")
+        self.n_key_only = self.M - self.Mq
         for name, t in (("kd", kd), ("vd", vd)):
-            if t is not None and (t.dtype != q.dtype or t.shape[:2] != q.shape[:2] or t.shape[3] != q.shape[3]):
+            if t is not None and (t.dtype != q.dtype or tuple(t.shape[:2]) != (self.batch, self.M) or t.shape[3] != q.shape[3]):
                 raise ValueError("%s: [batch, M, Hkv, D] in q's dtype" % name)
         if parent is not None and (parent.dtype != torch.int32 or tuple(parent.shape) != (self.batch, self.M)):
             raise ValueError("parent: int32 [batch, M]")
@@ -179,14 +195,15 @@ class Tree:
                        None if kd is None else _ptr(kd, q.dtype, "kd").value,
                        None if vd is None else _ptr(vd, q.dtype, "vd").value,
                        None if parent is None else _ptr(parent, torch.int32, "parent").value,
-                       self.M, self.Hq, int(last_node))
+                       self.M, self.Hq, self.n_key_only if last_node is None else int(last_node), self.n_key_only)
 
 
 class SelectCfg:
-    def __init__(self, n_sink_blocks, n_recent_blocks, k_blocks, reduce="mean", score="eq2"):
+    def __init__(self, n_sink_blocks, n_recent_blocks, k_blocks, reduce="mean", score="eq2", n_extra_slots=0):
         self.ns, self.nr, self.k = int(n_sink_blocks), int(n_recent_blocks), int(k_blocks)
-        self.n_sel = self.ns + self.k + self.nr
-        self.c = _Cfg(self.ns, self.nr, self.k, _REDUCE[reduce], _SCORE[score])
+        self.n_extra = int(n_extra_slots)
+        self.n_sel = self.ns + self.k + self.nr + self.n_extra     # entries per list row
+        self.c = _Cfg(self.ns, self.nr, self.k, _REDUCE[reduce], _SCORE[score], self.n_extra)
 
 
 def _match(kv, tree):
@@ -245,8 +262,8 @@ def specpv_partial_verify_attn(kv, tree, sel_idx, sel_count, out, lse=None, work
         _check_sel(kv, sel_idx, sel_count, n_sel)
     if out.shape != tree.q.shape:
         raise ValueError("out: same shape as q")
-    if lse is not None and tuple(lse.shape) != (tree.batch, tree.M, tree.Hq):
-        raise ValueError("lse: [batch, M, Hq] float32")
+    if lse is not None and tuple(lse.shape) != (tree.batch, tree.Mq, tree.Hq):
+        raise ValueError("lse: [batch, Mq, Hq] float32")
     wp, wb = _ws(workspace)
     _check(load().specpv_partial_verify_attn(ctypes.byref(kv.c), ctypes.byref(tree.c),
                                              _ptr(sel_idx, torch.int32, "sel_idx"),
@@ -264,8 +281,8 @@ def specpv_full_verify_refresh(kv, tree, kmax, kmin, stale_blk_begin, cfg, out, 
     for name, t in (("kmax", kmax), ("kmin", kmin)):
         if tuple(t.shape) != kv.summary_shape():
             raise ValueError("%s: [batch, Hkv, max_blocks, D]" % name)
-    if lse is not None and tuple(lse.shape) != (tree.batch, tree.M, tree.Hq):
-        raise ValueError("lse: [batch, M, Hq] float32")
+    if lse is not None and tuple(lse.shape) != (tree.batch, tree.Mq, tree.Hq):
+        raise ValueError("lse: [batch, Mq, Hq] float32")
     if scores is not None and tuple(scores.shape) != (kv.batch, kv.Hkv, kv.max_blocks):
         raise ValueError("scores: [batch, Hkv, max_blocks] float32")
     wp, wb = _ws(workspace)
@@ -306,10 +323,23 @@ def specpv_extend_parents(tree_parent, n_pending):
     return list(dst)
 
 
+def _lists(kv, sel_idx, sel_count):
+    n_sel = sel_idx.shape[-1]
+    _check_sel(kv, sel_idx, sel_count, n_sel)
+    return _Lists(_ptr(sel_idx, torch.int32, "sel_idx").value, _ptr(sel_count, torch.int32, "sel_count").value, n_sel)
+
+
+def _dropped(kv, dropped):
+    if dropped is not None and tuple(dropped.shape) != (kv.batch, 2):
+        raise ValueError("dropped: int32 [batch, 2]")
+    return _ptr(dropped, torch.int32, "dropped")
+
+
 def specpv_commit_accepted(kv, buf_k, buf_v, pending_cap, M_tree, n_pending, accepted, n_accepted, mode,
-                           kmax=None, kmin=None, workspace=None):
+                           kmax=None, kmin=None, workspace=None, sel_idx=None, sel_count=None, dropped=None):
     """buf_k / buf_v [batch, pending_cap + M_tree, Hkv, D]; n_pending, n_accepted int32 [batch];
-    accepted int32 [batch, max_accept] -- all on the GPU."""
+    accepted int32 [batch, max_accept]; optional sel_idx / sel_count (the layer's kept-block lists, extended
+    by a commit to the cache) and dropped int32 [batch, 2] -- all on the GPU."""
     for name, t in (("buf_k", buf_k), ("buf_v", buf_v)):
         if tuple(t.shape) != (kv.batch, pending_cap + M_tree, kv.Hkv, kv.D):
             raise ValueError("%s: [batch, pending_cap + M_tree, Hkv, D]" % name)
@@ -320,17 +350,19 @@ def specpv_commit_accepted(kv, buf_k, buf_v, pending_cap, M_tree, n_pending, acc
         if t is not None and tuple(t.shape) != kv.summary_shape():
             raise ValueError("%s: [batch, Hkv, max_blocks, D]" % name)
     wp, wb = _ws(workspace)
+    ls = None if sel_idx is None else ctypes.byref(_lists(kv, sel_idx, sel_count))
     _check(load().specpv_commit_accepted(ctypes.byref(kv.c), _ptr(buf_k, kv.dtype, "buf_k"), _ptr(buf_v, kv.dtype, "buf_v"),
                                          int(pending_cap), int(M_tree), _ptr(n_pending, torch.int32, "n_pending"),
                                          _ptr(accepted, torch.int32, "accepted"), _ptr(n_accepted, torch.int32, "n_accepted"),
                                          int(accepted.shape[1]), int(mode), _ptr(kmax, kv.dtype, "kmax"),
-                                         _ptr(kmin, kv.dtype, "kmin"), wp, wb, _stream()))
+                                         _ptr(kmin, kv.dtype, "kmin"), ls, _dropped(kv, dropped), wp, wb, _stream()))
 
 
 def specpv_commit_accepted_layers(kvs, buf_ks, buf_vs, pending_cap, M_tree, n_pending, accepted, n_accepted, mode,
-                                  kmaxs=None, kmins=None, workspace=None):
-    """specpv_commit_accepted for all layers of a model at once: kvs, buf_ks, buf_vs (and kmaxs, kmins)
-    are lists with one entry per layer; the layers share shape, strides, dtype and ONE ctx_len tensor."""
+                                  kmaxs=None, kmins=None, workspace=None, sel_idxs=None, sel_counts=None, dropped=None):
+    """specpv_commit_accepted for all layers of a model at once: kvs, buf_ks, buf_vs (and kmaxs, kmins,
+    sel_idxs, sel_counts) are lists with one entry per layer; the layers share shape, strides, dtype and
+    ONE ctx_len tensor."""
     n = len(kvs)
     if n < 1 or len(buf_ks) != n or len(buf_vs) != n:
         raise ValueError("one kv, buf_k and buf_v per layer")
@@ -355,11 +387,16 @@ def specpv_commit_accepted_layers(kvs, buf_ks, buf_vs, pending_cap, M_tree, n_pe
     km = table(kmaxs, "kmax") if kmaxs is not None else None
     kn = table(kmins, "kmin") if kmins is not None else None
     wp, wb = _ws(workspace)
+    ls = None
+    if sel_idxs is not None:
+        if len(sel_idxs) != n or len(sel_counts) != n:
+            raise ValueError("sel_idxs, sel_counts: one per layer")
+        ls = (_Lists * n)(*[_lists(kv0, a, c) for a, c in zip(sel_idxs, sel_counts)])
     _check(load().specpv_commit_accepted_layers(kv_arr, bk, bv, n, int(pending_cap), int(M_tree),
                                                 _ptr(n_pending, torch.int32, "n_pending"),
                                                 _ptr(accepted, torch.int32, "accepted"),
                                                 _ptr(n_accepted, torch.int32, "n_accepted"), int(accepted.shape[1]),
-                                                int(mode), km, kn, wp, wb, _stream()))
+                                                int(mode), km, kn, ls, _dropped(kv0, dropped), wp, wb, _stream()))
 
 
 def specpv_strerror(status):

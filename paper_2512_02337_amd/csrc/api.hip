@@ -18,14 +18,19 @@ static int fail_hip(hipError_t e)
 
 int device_cu_count()
 {
-    static const int n = [] {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            return 256;
-        return cus;
-    }();
-    return n;
+    // per device, filled on first use; a racing first call writes the same value
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked) {
+        const int c = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
+        if (c > 0) return c;
+    }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+    if (tracked) __atomic_store_n(&cached[dev], cus, __ATOMIC_RELAXED);
+    return cus;
 }
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -49,6 +54,7 @@ static int check_tree(const specpv_kv *kv, const specpv_tree *tree, bool need_dr
 {
     if (!tree || !tree->q) return SPECPV_EINVAL;
     if (tree->M < 1 || tree->n_q_heads < 1) return SPECPV_EINVAL;
+    if (tree->n_key_only < 0 || tree->n_key_only >= tree->M) return SPECPV_EINVAL;
     if (tree->n_q_heads % kv->n_kv_heads) return SPECPV_EINVAL;
     if (tree->M > SPECPV_MAX_M || tree->n_q_heads / kv->n_kv_heads > SPECPV_MAX_G) return SPECPV_ELIMIT;
     if ((uintptr_t)tree->q & 15) return SPECPV_EINVAL;
@@ -65,10 +71,12 @@ static int check_cfg(const specpv_tree *tree, const specpv_select_cfg *cfg)
     if (cfg->n_sink_blocks < 0 || cfg->n_recent_blocks < 0 || cfg->k_blocks < 0) return SPECPV_EINVAL;
     if (cfg->reduce != SPECPV_REDUCE_MEAN && cfg->reduce != SPECPV_REDUCE_MAX && cfg->reduce != SPECPV_REDUCE_LAST)
         return SPECPV_EINVAL;
-    if (cfg->reduce == SPECPV_REDUCE_LAST && (tree->last_node < 0 || tree->last_node >= tree->M))
+    if (cfg->reduce == SPECPV_REDUCE_LAST && (tree->last_node < tree->n_key_only || tree->last_node >= tree->M))
         return SPECPV_EINVAL;
     if (cfg->score != SPECPV_SCORE_EQ2 && cfg->score != SPECPV_SCORE_CHANNEL_BOUND) return SPECPV_EINVAL;
-    if ((int64_t)cfg->n_sink_blocks + cfg->n_recent_blocks + cfg->k_blocks > ((int64_t)1 << 24)) return SPECPV_ELIMIT;
+    if (cfg->n_extra_slots < 0) return SPECPV_EINVAL;
+    if ((int64_t)cfg->n_sink_blocks + cfg->n_recent_blocks + cfg->k_blocks + cfg->n_extra_slots > ((int64_t)1 << 24))
+        return SPECPV_ELIMIT;
     return SPECPV_OK;
 }
 
@@ -83,7 +91,8 @@ static Shape make_shape(const specpv_kv *kv, const specpv_tree *tree)
     s.max_blocks = kv->max_blocks;
     if (tree) {
         s.q = tree->q; s.kd = tree->kd; s.vd = tree->vd; s.parent = tree->parent;
-        s.M = tree->M; s.Hq = tree->n_q_heads; s.G = s.Hq / s.Hkv;
+        s.Mk = tree->M; s.koff = tree->n_key_only; s.M = s.Mk - s.koff;
+        s.Hq = tree->n_q_heads; s.G = s.Hq / s.Hkv;
     }
     return s;
 }
@@ -191,9 +200,12 @@ static int run_select(const Shape &s, int dtype, const specpv_tree *tree, const 
                       const specpv_select_cfg *cfg, int32_t *sel_idx, int32_t *sel_count, float *scores,
                       hipStream_t st)
 {
-    hipError_t e = launch_scores(s, dtype, kmax, kmin, (int)cfg->reduce, tree->last_node, (int)cfg->score, scores, st);
+    // the scoring kernels count query rows: node last_node is row last_node - n_key_only
+    hipError_t e = launch_scores(s, dtype, kmax, kmin, (int)cfg->reduce, tree->last_node - tree->n_key_only,
+                                 (int)cfg->score, scores, st);
     if (e != hipSuccess) return fail_hip(e);
-    e = launch_topk(s, scores, cfg->n_sink_blocks, cfg->n_recent_blocks, cfg->k_blocks, sel_idx, sel_count, st);
+    const int n_row = cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks + cfg->n_extra_slots;
+    e = launch_topk(s, scores, cfg->n_sink_blocks, cfg->n_recent_blocks, cfg->k_blocks, n_row, sel_idx, sel_count, st);
     if (e != hipSuccess) return fail_hip(e);
     return SPECPV_OK;
 }
@@ -212,7 +224,7 @@ size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, cons
     const Shape s = make_shape(kv, tree);
     int nsplit = plan_attention(s, kv->dtype, s.max_blocks).nsplit;
     if (cfg) {
-        const int64_t n_sel = (int64_t)cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks;
+        const int64_t n_sel = (int64_t)cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks + cfg->n_extra_slots;
         const int n2 = plan_attention(s, kv->dtype, n_sel).nsplit;
         if (n2 > nsplit) nsplit = n2;
     }
@@ -298,6 +310,7 @@ int specpv_gather_blocks(const specpv_kv *kv, const int32_t *sel_idx, const int3
     if (!sel_idx || !sel_count || !out_k || !out_v || n_sel < 1) return SPECPV_EINVAL;
     if (((uintptr_t)out_k | (uintptr_t)out_v) & 15) return SPECPV_EINVAL;
     if (n_sel > (1 << 24) || (int64_t)n_sel * kv->block_size > ((int64_t)1 << 30)) return SPECPV_ELIMIT;
+    if (kv->batch > 65535 || kv->n_kv_heads > 65535) return SPECPV_ELIMIT;   // grid limits, before anything is enqueued
     const Shape s = make_shape(kv, nullptr);
     const hipError_t e = launch_gather(s, kv->dtype, sel_idx, sel_count, n_sel, out_k, out_v, out_len, (hipStream_t)stream);
     return e == hipSuccess ? SPECPV_OK : fail_hip(e);
@@ -328,11 +341,14 @@ int specpv_extend_parents(const int32_t *tree_parent, int32_t M_tree, int32_t n_
 int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_t pending_cap, int32_t M_tree,
                            int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
                            int32_t max_accept, specpv_mode mode, void *kmax, void *kmin,
+                           const specpv_lists *lists, int32_t *dropped,
                            void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc = check_kv(kv);
     if (rc != SPECPV_OK) return rc;
     if (!buf_k || !buf_v || !n_pending || !accepted || !n_accepted) return SPECPV_EINVAL;
+    if (lists && (!lists->sel_idx || !lists->sel_count || lists->n_sel < 1)) return SPECPV_EINVAL;
+    if (lists && lists->n_sel > (1 << 24)) return SPECPV_ELIMIT;
     if (pending_cap < 0 || M_tree < 1 || max_accept < 1) return SPECPV_EINVAL;
     if (mode != SPECPV_MODE_FULL && mode != SPECPV_MODE_PARTIAL && mode != SPECPV_MODE_REFRESH) return SPECPV_EINVAL;
     if (((uintptr_t)buf_k | (uintptr_t)buf_v) & 15) return SPECPV_EINVAL;
@@ -343,15 +359,15 @@ int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_
     void *k1 = const_cast<void *>(kv->k), *v1 = const_cast<void *>(kv->v);
     const hipError_t e = launch_commit(s, kv->dtype, 1, &k1, &v1, &buf_k, &buf_v, pending_cap, M_tree, n_pending, accepted,
                                        n_accepted, max_accept, mode != SPECPV_MODE_PARTIAL, &kmax, &kmin,
-                                       (int32_t *)workspace, (hipStream_t)stream);
+                                       lists, dropped, (int32_t *)workspace, (hipStream_t)stream);
     return e == hipSuccess ? SPECPV_OK : fail_hip(e);
 }
 
 int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k, void *const *buf_v, int32_t n_layers,
                                   int32_t pending_cap, int32_t M_tree, int32_t *n_pending, const int32_t *accepted,
                                   const int32_t *n_accepted, int32_t max_accept, specpv_mode mode,
-                                  void *const *kmax, void *const *kmin, void *workspace, size_t workspace_bytes,
-                                  void *stream)
+                                  void *const *kmax, void *const *kmin, const specpv_lists *lists, int32_t *dropped,
+                                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!kv || !buf_k || !buf_v || n_layers < 1 || n_layers > SPECPV_MAX_LAYERS) return SPECPV_EINVAL;
     if (!n_pending || !accepted || !n_accepted) return SPECPV_EINVAL;
@@ -376,6 +392,11 @@ int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k
             if ((kmax[l] != nullptr) != want || (kmin[l] != nullptr) != want) return SPECPV_EINVAL;
             if (((uintptr_t)kmax[l] | (uintptr_t)kmin[l]) & 15) return SPECPV_EINVAL;
         }
+        if (lists) {
+            if (!lists[l].sel_idx || !lists[l].sel_count || lists[l].n_sel < 1 || lists[l].n_sel != lists[0].n_sel)
+                return SPECPV_EINVAL;
+            if (lists[l].n_sel > (1 << 24)) return SPECPV_ELIMIT;
+        }
         kp[l] = const_cast<void *>(x->k);
         vp[l] = const_cast<void *>(x->v);
     }
@@ -383,7 +404,7 @@ int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k
     const Shape s = make_shape(kv[0], nullptr);
     const hipError_t e = launch_commit(s, kv[0]->dtype, n_layers, kp, vp, buf_k, buf_v, pending_cap, M_tree, n_pending,
                                        accepted, n_accepted, max_accept, mode != SPECPV_MODE_PARTIAL, kmax, kmin,
-                                       (int32_t *)workspace, (hipStream_t)stream);
+                                       lists, dropped, (int32_t *)workspace, (hipStream_t)stream);
     return e == hipSuccess ? SPECPV_OK : fail_hip(e);
 }
 
@@ -401,6 +422,6 @@ const char *specpv_strerror(int status)
 
 const char *specpv_last_hip_error(void) { return g_hip_err; }
 
-int specpv_version(void) { return 100; }
+int specpv_version(void) { return 200; }
 
 }  // extern "C"

@@ -941,13 +941,12 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, gl.waves * 32 * kOPitch * (int)sizeof(float));
 #define SPECPV_LAUNCH(KERN, THREADS, LDS)                                                              \
     do {                                                                                               \
-        static bool attr_set = false;                                                                  \
+        static PerDeviceOnce once;   /* one per kernel instantiation */                               \
         auto kern = KERN;                                                                              \
-        if (!attr_set) {                                                                               \
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(LDS)); \
-            if (e != hipSuccess) return e;                                                             \
-            attr_set = true;                                                                           \
-        }                                                                                              \
+        const hipError_t e0 = once.run([&] {                                                           \
+            return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(LDS)); \
+        });                                                                                            \
+        if (e0 != hipSuccess) return e0;                                                               \
         hipLaunchKernelGGL(kern, grid, dim3(THREADS), LDS, st, s, p, a);                                \
     } while (0)
 #define SPECPV_LAUNCH_GROUP(WW)                                                                        \

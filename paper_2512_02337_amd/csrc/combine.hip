@@ -109,9 +109,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
     const int h = g * s.G + (live ? hh : s.G - 1);
 
     // ---- every read whose address is known from the arguments goes out first ----------
-    const int32_t *par = s.parent + (int64_t)b * s.M;
-    const int par0 = lane < s.M ? par[lane] : -1;
-    const int par1 = lane + 64 < s.M ? par[lane + 64] : -1;
+    // the tree has s.Mk nodes; query row j is node j + s.koff (the nodes in front are keys only)
+    const int32_t *par = s.parent + (int64_t)b * s.Mk;
+    const int par0 = lane < s.Mk ? par[lane] : -1;
+    const int par1 = lane + 64 < s.Mk ? par[lane + 64] : -1;
     const int64_t qrow = (((int64_t)b * s.M + j) * s.Hq + h) * D;
     Raw qraw;
     Chan<T, CPL>::load(s.q, qrow + d0, qraw);
@@ -133,8 +134,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
     // ---- root path of node j as a bit set (wave-uniform walk over the parent registers) --
     unsigned long long anc_lo = 0ull, anc_hi = 0ull;
     {
-        int a = j;
-        for (int guard = 0; a >= 0 && guard < s.M; ++guard) {
+        int a = j + s.koff;
+        for (int guard = 0; a >= 0 && guard < s.Mk; ++guard) {
             if (a < 64) anc_lo |= 1ull << a; else anc_hi |= 1ull << (a - 64);
             const int pa = a < 64 ? __builtin_amdgcn_readlane(par0, a) : __builtin_amdgcn_readlane(par1, a - 64);
             a = pa < a ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         a8[u] = pop();
-        const int64_t drow = (((int64_t)b * s.M + max(a8[u], 0)) * s.Hkv + g) * D;
+        const int64_t drow = (((int64_t)b * s.Mk + max(a8[u], 0)) * s.Hkv + g) * D;
         Chan<T, CPL>::load(s.kd, drow + d0, kd8[u]);
         Chan<T, CPL>::load(s.vd, drow + d0, vd8[u]);
     }
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             a[u] = pop();
-            const int64_t drow = (((int64_t)b * s.M + max(a[u], 0)) * s.Hkv + g) * D;
+            const int64_t drow = (((int64_t)b * s.Mk + max(a[u], 0)) * s.Hkv + g) * D;
             Chan<T, CPL>::load(s.kd, drow + d0, kdv[u]);
             Chan<T, CPL>::load(s.vd, drow + d0, vdv[u]);
         }

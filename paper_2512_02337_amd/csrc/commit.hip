@@ -75,7 +75,8 @@ __global__ __launch_bounds__(256) void commit_copy_kernel(Shape s, CommitLayers 
 // One thread per sequence, after the copies: the new lengths (the old committed length goes to
 // old_len for the summary update).
 __global__ void commit_update_kernel(Shape s, int P, int32_t *ctx_len, int32_t *n_pending,
-                                     const int32_t *n_accepted, int max_accept, int to_cache, int32_t *old_len)
+                                     const int32_t *n_accepted, int max_accept, int to_cache, int32_t *old_len,
+                                     int32_t *dropped)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= s.batch) return;
@@ -83,11 +84,49 @@ __global__ void commit_update_kernel(Shape s, int P, int32_t *ctx_len, int32_t *
     const int n = min(max(n_pending[b], 0), P);
     const int a = min(max(n_accepted[b], 0), max_accept);
     old_len[b] = L;
+    int stored;
     if (to_cache) {
-        ctx_len[b] = L + min(n + a, max(0, s.max_blocks * s.B - L));
+        stored = min(n + a, max(0, s.max_blocks * s.B - L));
+        ctx_len[b] = L + stored;
         n_pending[b] = 0;
     } else {
-        n_pending[b] = min(n + a, P);
+        stored = min(n + a, P);
+        n_pending[b] = stored;
+    }
+    if (dropped) {
+        dropped[2 * b] = n + a - stored;   // tokens that found no room
+        dropped[2 * b + 1] = 0;            // list entries that found no room: commit_extend_lists_kernel
+    }
+}
+
+// After a commit to the cache (Section 3.3: the committed tokens stay part of the partial cache):
+// every block that holds one of the tokens old_len .. new length - 1 joins the kept-block list of
+// each KV head, behind the entries it has, unless the block is listed already (the ragged last
+// block of the local window).  One wavefront per (KV head, sequence, layer).
+struct CommitLists {
+    int32_t *idx[kCommitLayers], *cnt[kCommitLayers];
+};
+__global__ __launch_bounds__(64) void commit_extend_lists_kernel(Shape s, CommitLists ls, int n_sel,
+                                                                 const int32_t *old_len, int32_t *dropped)
+{
+    const int g = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const int L = s.ctx_len[b], L0 = old_len[b];
+    if (L <= L0) return;
+    int32_t *row = ls.idx[blockIdx.z] + ((int64_t)b * s.Hkv + g) * n_sel;
+    int32_t *cntp = ls.cnt[blockIdx.z] + (int64_t)b * s.Hkv + g;
+    const int cnt0 = min(max(*cntp, 0), n_sel);
+    const int first = L0 / s.B, last = (L - 1) / s.B;
+    int cnt = cnt0, missed = 0;
+    for (int blk = first; blk <= last; ++blk) {
+        bool here = false;
+        for (int i = lane; i < cnt0; i += 64) here |= row[i] == blk;
+        if (__any(here)) continue;
+        if (cnt < n_sel) { if (lane == 0) row[cnt] = blk; ++cnt; }
+        else ++missed;
+    }
+    if (lane == 0) {
+        *cntp = cnt;
+        if (missed && dropped) atomicMax(&dropped[2 * b + 1], missed);
     }
 }
 
@@ -140,8 +179,8 @@ __global__ __launch_bounds__(64) void summarize_tail_kernel(Shape s, CommitLayer
 hipError_t launch_commit(const Shape &s, int dtype, int n_layers, void *const *k, void *const *v,
                          void *const *buf_k, void *const *buf_v, int P, int Mt,
                          int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
-                         int max_accept, int to_cache, void *const *kmax, void *const *kmin, int32_t *old_len,
-                         hipStream_t st)
+                         int max_accept, int to_cache, void *const *kmax, void *const *kmin,
+                         const specpv_lists *lists, int32_t *dropped, int32_t *old_len, hipStream_t st)
 {
     if (P + max_accept > kCommitMaxRows) return hipErrorInvalidValue;
     const bool summaries = to_cache && kmax && kmin && kmax[0] && kmin[0];
@@ -167,9 +206,21 @@ hipError_t launch_commit(const Shape &s, int dtype, int n_layers, void *const *k
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(commit_update_kernel, dim3((s.batch + 63) / 64), dim3(64), 0, st, s, P,
-                       (int32_t *)s.ctx_len, n_pending, n_accepted, max_accept, to_cache, old_len);
+                       (int32_t *)s.ctx_len, n_pending, n_accepted, max_accept, to_cache, old_len, dropped);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !summaries) return e;
+    if (e != hipSuccess) return e;
+    if (to_cache && lists) {
+        for (int l0 = 0; l0 < n_layers; l0 += kCommitLayers) {
+            const int nl = n_layers - l0 < kCommitLayers ? n_layers - l0 : kCommitLayers;
+            CommitLists ls = {};
+            for (int l = 0; l < nl; ++l) { ls.idx[l] = lists[l0 + l].sel_idx; ls.cnt[l] = lists[l0 + l].sel_count; }
+            hipLaunchKernelGGL(commit_extend_lists_kernel, dim3(s.Hkv, s.batch, nl), dim3(64), 0, st, s, ls,
+                               lists[0].n_sel, old_len, dropped);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    if (!summaries) return hipSuccess;
     // blocks that can have received one of at most P + max_accept tokens
     const int touched = (P + max_accept + s.B - 1) / s.B + 1;
     for (int l0 = 0; l0 < n_layers; l0 += kCommitLayers) {
@@ -261,9 +312,9 @@ __global__ void zero_i32_kernel(int32_t *p, int n)
 hipError_t launch_gather(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count, int n_sel,
                          void *out_k, void *out_v, int32_t *out_len, hipStream_t st)
 {
-    if (out_len) hipLaunchKernelGGL(zero_i32_kernel, dim3((s.batch + 63) / 64), dim3(64), 0, st, out_len, s.batch);
     const dim3 grid(n_sel, s.Hkv, s.batch);
-    if (grid.z > 65535u || grid.y > 65535u) return hipErrorInvalidConfiguration;
+    if (grid.z > 65535u || grid.y > 65535u) return hipErrorInvalidConfiguration;   // before anything is enqueued
+    if (out_len) hipLaunchKernelGGL(zero_i32_kernel, dim3((s.batch + 63) / 64), dim3(64), 0, st, out_len, s.batch);
 #define SPECPV_GATHER(T, DD) \
     hipLaunchKernelGGL((gather_blocks_kernel<T, DD>), grid, dim3(256), 0, st, s, sel_idx, sel_count, n_sel, (T *)out_k, (T *)out_v, out_len)
     if (dtype == SPECPV_BF16) {

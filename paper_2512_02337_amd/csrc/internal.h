@@ -18,9 +18,13 @@ struct Shape {
     int64_t sb, sh, st;           // element strides of k / v: batch, head, token
     const int32_t *ctx_len;       // [batch]
     const void *q;                // [batch, M, Hq, D]
-    const void *kd, *vd;          // [batch, M, Hkv, D]
-    const int32_t *parent;        // [batch, M]
+    const void *kd, *vd;          // [batch, Mk, Hkv, D]
+    const int32_t *parent;        // [batch, Mk]
     int batch, Hkv, Hq, G, D, B, M, max_blocks;
+    // M counts the QUERY nodes (rows of q, out, the partials).  The tree has Mk >= M nodes: its
+    // first koff = Mk - M nodes are keys only (partially verified tokens on a partial step);
+    // query row r is node koff + r.
+    int Mk, koff;
 };
 
 // Split-KV partial results of the context part, one per (b, h, split, node):
@@ -121,7 +125,8 @@ hipError_t launch_summarize(const Shape &s, int dtype, int blk_begin, int blk_en
 // kind: SPECPV_SCORE_EQ2 or SPECPV_SCORE_CHANNEL_BOUND
 hipError_t launch_scores(const Shape &s, int dtype, const void *kmax, const void *kmin,
                          int reduce, int last_node, int kind, float *scores, hipStream_t st);
-hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k,
+// n_row: entries per list row (>= ns + k + nr; the rest is padding for later commits)
+hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k, int n_row,
                        int32_t *sel_idx, int32_t *sel_count, hipStream_t st);
 hipError_t launch_attn_ctx_generic(const Shape &s, int dtype, const int32_t *sel_idx,
                                    const int32_t *sel_count, int n_sel, Partials p, hipStream_t st);
@@ -143,15 +148,35 @@ hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, floa
 // to_cache != 0: pending + accepted rows go to the cache tail (lengths, summaries updated);
 // otherwise the accepted rows join the pending rows of the buffer.  old_len: [batch] scratch.
 // n_layers layers that share shape, strides and counters are committed together.
+// lists (n_layers entries, or nullptr): kept-block lists that take in the blocks a commit to the
+// cache touches.  dropped ([batch, 2], or nullptr): tokens not stored, list entries not found.
 hipError_t launch_commit(const Shape &s, int dtype, int n_layers, void *const *k, void *const *v,
                          void *const *buf_k, void *const *buf_v, int P, int Mt,
                          int32_t *n_pending, const int32_t *accepted, const int32_t *n_accepted,
-                         int max_accept, int to_cache, void *const *kmax, void *const *kmin, int32_t *old_len,
+                         int max_accept, int to_cache, void *const *kmax, void *const *kmin,
+                         const specpv_lists *lists, int32_t *dropped, int32_t *old_len,
                          hipStream_t st);
 
 hipError_t launch_gather(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count, int n_sel,
                          void *out_k, void *out_v, int32_t *out_len, hipStream_t st);
 
-int device_cu_count();
+int device_cu_count();   // of the current device
+
+// One-time set-up per (kernel, device): `fn` runs once for each device it is asked for, also when
+// several threads make their first call at the same moment.  Devices beyond 63 run it every time.
+struct PerDeviceOnce {
+    unsigned long long done = 0;   // bit d: fn has succeeded on device d (accessed atomically)
+    template <typename F> hipError_t run(F fn)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool tracked = dev >= 0 && dev < 64;
+        if (tracked && ((__atomic_load_n(&done, __ATOMIC_ACQUIRE) >> dev) & 1ull)) return hipSuccess;
+        e = fn();   // idempotent: two threads that race here both set the same attribute
+        if (e == hipSuccess && tracked) __atomic_fetch_or(&done, 1ull << dev, __ATOMIC_RELEASE);
+        return e;
+    }
+};
 
 }  // namespace specpv

@@ -123,7 +123,7 @@ __device__ __forceinline__ unsigned long long select_key(float score, int idx)
 }
 
 __global__ __launch_bounds__(256) void topk_kernel(const float *scores, const int32_t *ctx_len, int B,
-                                                   int max_blocks, int Hkv, int ns, int nr, int k,
+                                                   int max_blocks, int Hkv, int ns, int nr, int k, int n_row,
                                                    int32_t *sel_idx, int32_t *sel_count)
 {
     __shared__ uint32_t hist[256];
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *scores, const in
     int nb = L > 0 ? (L + B - 1) / B : 0;
     if (nb > max_blocks) nb = max_blocks;
     const float *sc = scores + ((int64_t)b * Hkv + g) * max_blocks;
-    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_sel;
+    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_row;   // n_row >= n_sel entries per row
     const bool all = nb <= n_sel;
     const int lo = ns, hi = nb - nr;
     unsigned long long thresh = ~0ull;
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *scores, const in
         __syncthreads();
     }
     if (base > n_sel) base = n_sel;
-    for (int c = base + tid; c < n_sel; c += 256) out[c] = -1;
+    for (int c = base + tid; c < n_row; c += 256) out[c] = -1;
     if (tid == 0) sel_count[(int64_t)b * Hkv + g] = base;
 }
 
@@ -276,7 +276,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *wave_tot, int &t
 
 template <int P>
 __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, const int32_t *ctx_len, int B,
-                                                        int max_blocks, int Hkv, int ns, int nr, int k,
+                                                        int max_blocks, int Hkv, int ns, int nr, int k, int n_row,
                                                         int32_t *sel_idx, int32_t *sel_count)
 {
     __shared__ uint32_t hist[256];
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
     const int g = blockIdx.x, b = blockIdx.y;
     const int n_sel = ns + k + nr;
     const float *sc = scores + ((int64_t)b * Hkv + g) * max_blocks;
-    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_sel;
+    int32_t *out = sel_idx + ((int64_t)b * Hkv + g) * n_row;   // n_row >= n_sel entries per row
 
     const int i0 = tid * P;
     // the scores are requested before the context length is known (any block below max_blocks
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(256) void topk_fast_kernel(const float *scores, con
             ++pos;
         }
     if (total > n_sel) total = n_sel;
-    for (int c = total + tid; c < n_sel; c += 256) out[c] = -1;
+    for (int c = total + tid; c < n_row; c += 256) out[c] = -1;
     if (tid == 0) sel_count[(int64_t)b * Hkv + g] = total;
 }
 
@@ -408,12 +408,12 @@ hipError_t launch_scores(const Shape &s, int dtype, const void *kmax, const void
     return launch_scores_generic(s, dtype, kmax, kmin, reduce, last_node, kind, scores, st);
 }
 
-hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k,
+hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k, int n_row,
                        int32_t *sel_idx, int32_t *sel_count, hipStream_t st)
 {
     dim3 grid(s.Hkv, s.batch), block(256);
 #define SPECPV_TOPK(KERN)                                                                        \
-    hipLaunchKernelGGL(KERN, grid, block, 0, st, scores, s.ctx_len, s.B, s.max_blocks, s.Hkv, ns, nr, k, \
+    hipLaunchKernelGGL(KERN, grid, block, 0, st, scores, s.ctx_len, s.B, s.max_blocks, s.Hkv, ns, nr, k, n_row, \
                        sel_idx, sel_count)
     if (s.max_blocks <= 256 * 4) SPECPV_TOPK(topk_fast_kernel<4>);
     else if (s.max_blocks <= 256 * 8) SPECPV_TOPK(topk_fast_kernel<8>);

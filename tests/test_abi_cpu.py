@@ -36,13 +36,13 @@ def _kv(**over):
 
 
 def _tree(**over):
-    d = dict(q=0x4000, kd=0x5000, vd=0x6000, parent=0x7000, M=60, n_q_heads=32, last_node=0)
+    d = dict(q=0x4000, kd=0x5000, vd=0x6000, parent=0x7000, M=60, n_q_heads=32, last_node=0, n_key_only=0)
     d.update(over)
     return binding._Tree(**d)
 
 
 def _cfg(**over):
-    d = dict(n_sink_blocks=1, n_recent_blocks=2, k_blocks=4, reduce=0, score=0)
+    d = dict(n_sink_blocks=1, n_recent_blocks=2, k_blocks=4, reduce=0, score=0, n_extra_slots=0)
     d.update(over)
     return binding._Cfg(**d)
 
@@ -74,6 +74,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.specpv_partial_verify_attn(B(_kv(n_kv_heads=1)), B(_tree(n_q_heads=32)), *args) == -3
     assert lib.specpv_partial_verify_attn(B(_kv()), B(_tree(kd=None)), *args) == -1
     assert lib.specpv_partial_verify_attn(B(_kv()), B(_tree(parent=None)), *args) == -1
+    assert lib.specpv_partial_verify_attn(B(_kv()), B(_tree(n_key_only=-1)), *args) == -1
+    assert lib.specpv_partial_verify_attn(B(_kv()), B(_tree(n_key_only=60)), *args) == -1   # no query node left
     # workspace
     assert lib.specpv_partial_verify_attn(B(_kv()), B(_tree()), vp(0x100), vp(0x200), 7, vp(0x300), None,
                                           vp(0x8000), 16, None) == -2
@@ -87,6 +89,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg(reduce=9)), *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg(score=2)), *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree(last_node=60)), vp(16), vp(32), B(_cfg(reduce=2)), *sel) == -1
+    assert lib.specpv_select_blocks(B(_kv()), B(_tree(last_node=3, n_key_only=4)), vp(16), vp(32), B(_cfg(reduce=2)), *sel) == -1
+    assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg(n_extra_slots=-1)), *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), None, *sel) == -1
     assert lib.specpv_select_blocks(B(_kv()), B(_tree()), vp(16), vp(32), B(_cfg()), vp(0x100), vp(0x200), None,
                                     None, 0, None) == -2
@@ -137,7 +141,8 @@ def test_mode_policy_and_extended_parents_on_the_host():
     # commit: fake pointers, never dereferenced
     vp = ctypes.c_void_p
     B = ctypes.byref
-    ok_args = (vp(0x100), vp(0x200), 28, 60, vp(0x300), vp(0x400), vp(0x500), 8, 1, None, None, vp(0x8000), 4096, None)
+    ok_args = (vp(0x100), vp(0x200), 28, 60, vp(0x300), vp(0x400), vp(0x500), 8, 1, None, None, None, None,
+               vp(0x8000), 4096, None)
     assert lib.specpv_commit_accepted(None, *ok_args) == -1
     a = list(ok_args); a[0] = None
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -1
@@ -145,8 +150,12 @@ def test_mode_policy_and_extended_parents_on_the_host():
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -1          # unknown mode
     a = list(ok_args); a[2] = 125
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -3          # buffer beyond the limits
-    a = list(ok_args); a[12] = 2
+    a = list(ok_args); a[14] = 2
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -2          # workspace too small
+    a = list(ok_args); a[11] = B(binding._Lists(0x900, None, 70))
+    assert lib.specpv_commit_accepted(B(_kv()), *a) == -1          # lists without counts
+    a = list(ok_args); a[11] = B(binding._Lists(0x900, 0xA00, 0))
+    assert lib.specpv_commit_accepted(B(_kv()), *a) == -1          # empty list rows
 
 
 def test_commit_of_all_layers_validates_on_the_host():
@@ -162,7 +171,7 @@ def test_commit_of_all_layers_validates_on_the_host():
         km = (vp * len(kmax))(*kmax) if kmax is not None else None
         kn = (vp * len(kmin))(*kmin) if kmin is not None else None
         return lib.specpv_commit_accepted_layers(arr, bk, bv, n, pending_cap, 60, vp(0x100), vp(0x200), vp(0x300), 8, 1,
-                                                 km, kn, None, 0, None)
+                                                 km, kn, None, None, None, 0, None)
     two = [_kv(), _kv(k=0x9000, v=0xA000)]
     assert call(two) == -2                                    # everything valid up to the (missing) workspace
     assert call(two, n=0) == -1
@@ -217,3 +226,30 @@ def test_workspace_size_is_a_consistent_split_plan():
         assert splits_of(both, batch, Hkv * G, Hkv, M, D, nb) is not None
     # no tree: only the per-sequence counters of the summary call
     assert lib.specpv_workspace_bytes(ctypes.byref(_kv()), None, None) >= 256
+
+
+def test_two_threads_may_call_at_once():
+    """Host-only calls and host-side validation from two threads at the same time (fake pointers, nothing
+    launched): the only state the library keeps is per-device set-up that is guarded for this."""
+    import threading
+    lib = specpv.load()
+    B, vp = ctypes.byref, ctypes.c_void_p
+    errs = []
+
+    def work(seed):
+        try:
+            for i in range(300):
+                kv, tree, cfg = _kv(max_blocks=16 + (i + seed) % 7), _tree(), _cfg()
+                n = lib.specpv_workspace_bytes(B(kv), B(tree), B(cfg))
+                assert n > 0 and n == lib.specpv_workspace_bytes(B(kv), B(tree), B(cfg))
+                assert lib.specpv_partial_verify_attn(B(kv), B(tree), vp(0x100), vp(0x200), 7, vp(0x300), None,
+                                                      vp(0x8000), 16, None) == -2
+                assert lib.specpv_select_mode(B(binding._Policy(100, 3)), 500, 1, 4) == specpv.MODE_REFRESH
+        except Exception as e:   # noqa: BLE001
+            errs.append(e)
+    ts = [threading.Thread(target=work, args=(s,)) for s in (0, 1)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert not errs, errs

@@ -76,8 +76,10 @@ def test_llama8b_128k_partial_step(gpu_lib, layer):
     margin = topk_margin(sc, case["ns"], case["nr"], case["k_blocks"])
     say("   top-k margins", np.array2string(margin, precision=4))
     got_idx, got_cnt = run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy()
-    exact = check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "128k lists")
-    say("   kept lists bit-exact:", exact)
+    check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "128k lists")
+    # inputs and kernels are deterministic: at the graded size the lists are pinned bit for bit
+    # (also where a margin is below the near-tie band that the random-shape tests allow)
+    assert np.array_equal(got_idx, idx) and np.array_equal(got_cnt, cnt), "kept lists differ from the oracle's"
     if layer == 0:
         # the full verification itself at 128K (the launch configuration bench.py times for the refresh)
         qh, O, lse = _oracle_attention_on_heads(case, 0, [6])
@@ -101,6 +103,7 @@ def test_qwen8b_full_verify_refresh_64k(gpu_lib):
     got_idx, got_cnt = run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy()
     say("   top-k margins", np.array2string(topk_margin(sc, case["ns"], case["nr"], case["k_blocks"]), precision=4))
     check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "64k refresh lists")
+    assert np.array_equal(got_idx, idx) and np.array_equal(got_cnt, cnt), "kept lists differ from the oracle's"
     qh, O, lse = _oracle_attention_on_heads(case, 0, [5])
     _compare(run, case, 0, qh, O, lse, "full verification, KV head 5")
 
@@ -115,9 +118,10 @@ def test_qwen14b_ragged_batch(gpu_lib):
     for b in range(case["batch"]):
         kmax, kmin, sc, idx, cnt = _oracle_scores_and_lists(case, b)
         got_idx, got_cnt = run.sel_idx[b].cpu().numpy(), run.sel_count[b].cpu().numpy()
-        exact = check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "seq %d" % b)
-        say("   seq %d (L=%d): lists bit-exact: %s, min margin %.4f" % (
-            b, int(case["ctx_len"][b]), exact, topk_margin(sc, case["ns"], case["nr"], case["k_blocks"]).min()))
+        check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "seq %d" % b)
+        say("   seq %d (L=%d): min margin %.4f" % (
+            b, int(case["ctx_len"][b]), topk_margin(sc, case["ns"], case["nr"], case["k_blocks"]).min()))
+        assert np.array_equal(got_idx, idx) and np.array_equal(got_cnt, cnt), "seq %d: kept lists differ from the oracle's" % b
         lists.append((got_idx, got_cnt))
     run.attend()
     torch.cuda.synchronize()
@@ -143,8 +147,8 @@ def test_paper_default_geometry(gpu_lib):
     torch.cuda.synchronize()
     kmax, kmin, sc, idx, cnt = _oracle_scores_and_lists(case, 0)
     got_idx, got_cnt = run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy()
-    exact = check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "paper default")
-    say("   lists bit-exact:", exact)
+    check_selection(got_idx, got_cnt, idx, cnt, sc, case["ns"], case["nr"], case["k_blocks"], "paper default")
+    assert np.array_equal(got_idx, idx) and np.array_equal(got_cnt, cnt), "kept lists differ from the oracle's"
     run.attend()
     torch.cuda.synchronize()
     qh, O, lse = _oracle_attention_on_heads(case, 0, [1, 6], (got_idx, got_cnt))
@@ -169,6 +173,7 @@ def test_paper_budgets(gpu_lib, budget):
     idx, cnt = oracle.select_blocks(sc, ns, nr, kb)
     got_idx, got_cnt = run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy()
     exact = check_selection(got_idx, got_cnt, idx, cnt, sc, ns, nr, kb, "budget %d" % budget)
+    assert np.array_equal(got_idx, idx) and np.array_equal(got_cnt, cnt), "kept lists differ from the oracle's"
     assert (got_cnt == ns + nr + kb).all()
     run.attend()
     torch.cuda.synchronize()

@@ -1,12 +1,14 @@
 """Full-KV offload (Section 3.3): the full cache in pinned host memory, one layer staged on
 the device at a time with the next one prefetched; the partial cache (gathered kept blocks)
-stays on the device.  The offloaded pipeline must give exactly what the resident one gives."""
+stays on the device.  The offloaded pipeline is checked against the fp64 oracle (full verification,
+kept lists, partial step of every layer) and must give exactly what the resident path gives."""
 import numpy as np
 import pytest
 import torch
 
+import oracle
 import workloads
-from helpers import ATOL, GpuRun, say
+from helpers import ATOL, GpuRun, check_selection, oracle_select, say
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +57,16 @@ def test_offloaded_refresh_and_partial_steps_match_the_resident_path(gpu_lib):
         torch.cuda.synchronize()
         assert torch.equal(run.out, ref[l][0]), "full verification differs at layer %d" % l
         assert torch.equal(run.sel_idx, ref[l][1]) and torch.equal(run.sel_count, ref[l][2])
+        # ... and against the oracle: output of the full verification, and the refreshed lists
+        o, kmax, kmin, sc, idx, cnt = oracle_select(c, 0)
+        O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], CFG["B"])
+        err = np.abs(run.out[0].float().cpu().numpy() - O).max()
+        say("   offloaded full verification vs oracle: max abs err %.3g" % err)
+        assert err <= ATOL["bf16"]
+        np.testing.assert_allclose(run.lse[0].cpu().numpy(), LSE, atol=2e-3, rtol=1e-5)
+        check_selection(run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy(), idx, cnt, sc,
+                        CFG["ns"], CFG["nr"], CFG["k"], "offloaded refresh, layer %d" % l)
+        assert np.array_equal(run.sel_idx[0].cpu().numpy(), idx), "kept lists differ from the oracle's"
     pf.synchronize()
 
     # partial steps touch only device-resident data: the gathered segments
@@ -67,6 +79,12 @@ def test_offloaded_refresh_and_partial_steps_match_the_resident_path(gpu_lib):
         torch.cuda.synchronize()
         err = (out.float() - ref[l][3].float()).abs().max().item()
         say("layer", l, "partial step on the gathered cache vs in place: max abs diff", err)
+        assert err <= ATOL["bf16"]
+        o = workloads.oracle_views(cases[l], 0)
+        O, _, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], CFG["B"],
+                                        run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy())
+        err = np.abs(out[0].float().cpu().numpy() - O).max()
+        say("layer", l, "partial step on the gathered cache vs oracle: max abs err %.3g" % err)
         assert err <= ATOL["bf16"]
 
 

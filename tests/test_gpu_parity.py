@@ -321,3 +321,46 @@ def test_runs_on_a_side_stream_and_is_deterministic(gpu_lib):
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
     o, kmax, kmin, sc, idx, cnt = oracle_select(case, 0)
     _check_attn(run, case, [(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0])], "side stream")
+
+
+@pytest.mark.parametrize("name,seed,n_key,Mq", [("llama8b_16k", 3, 16, 60), ("llama8b_16k", 3, 20, 100),
+                                                ("tiny_f32", 2, 5, 16), ("tiny_f32", 2, 1, 16)])
+def test_key_only_nodes(gpu_lib, name, seed, n_key, Mq):
+    """Section 3.2 (the buffer) on a partial step: the partially verified tokens are a chain of n_key nodes
+    in front of the candidates' tree that are attended but have no query rows.  Attention, scores (all
+    three reducers count query rows only) and lists against the oracle; full verification too."""
+    sp = gpu_lib
+    base = workloads.make_case(name, seed=seed, M=Mq)
+    gen = torch.Generator().manual_seed(7 + n_key)
+    dt = base["q"].dtype
+    pk = torch.randn((1, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
+    pv = torch.randn((1, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
+    ext = np.array([oracle.extend_parents(base["parent"][0].tolist(), n_key)], dtype=np.int32)
+    case = dict(base)
+    case["kd"], case["vd"] = torch.cat([pk, base["kd"]], 1), torch.cat([pv, base["vd"]], 1)
+    case["parent"] = torch.from_numpy(ext)
+    case = workloads.to_device(case, "cuda")
+    for reduce in ("mean", "max", "last"):
+        run = GpuRun(sp, case, reduce=reduce, last_node=n_key + 2)
+        assert run.tree.n_key_only == n_key and run.tree.Mq == Mq
+        run.summarize(); run.select(); run.attend()
+        torch.cuda.synchronize()
+        o = workloads.oracle_views(case, 0)
+        kmax, kmin = oracle.block_summarize(o["K"], case["B"])
+        sc = oracle.block_scores(o["Q"], kmax, kmin, reduce, 2)          # the oracle's rows are the query nodes
+        np.testing.assert_allclose(run.scores.cpu().numpy()[0], sc, rtol=2e-5, atol=2e-5)
+        idx, cnt = oracle.select_blocks(sc, case["ns"], case["nr"], case["k_blocks"])
+        check_selection(run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0], idx, cnt, sc,
+                        case["ns"], case["nr"], case["k_blocks"], "%s key-only %s" % (name, reduce))
+        gi, gc = run.sel_idx.cpu().numpy()[0], run.sel_count.cpu().numpy()[0]
+        O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"], gi, gc,
+                                          n_key_only=n_key)
+        err = np.abs(_to_np(run.out)[0] - O).max()
+        say("   %s, %d key-only + %d query nodes, %s: attention max-abs err %.3g" % (name, n_key, Mq, reduce, err))
+        assert err <= ATOL[case["dtype"]]
+        np.testing.assert_allclose(_to_np(run.lse)[0], LSE, atol=2e-5 if case["dtype"] == "f32" else 2e-3, rtol=1e-5)
+    run.out.zero_()
+    run.attend(None, None)   # every block
+    torch.cuda.synchronize()
+    O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"], n_key_only=n_key)
+    assert np.abs(_to_np(run.out)[0] - O).max() <= ATOL[case["dtype"]]
