@@ -154,6 +154,21 @@ int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree,
                                void *out, float *lse,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that can neither allocate nor pass a workspace: code under HIP graph capture with
+ * fixed arguments, tight serving loops, harnesses that forbid hipMalloc.  The same computation
+ * as specpv_partial_verify_attn (same kernels, bit-identical results) with the split-KV partial
+ * results kept in a file-scope device array of SPECPV_STATIC_SCRATCH_BYTES inside the library
+ * (one copy per GPU, held until the process ends).  The call allocates nothing and calls no
+ * allocating routine.  A call whose partial results would not fit (specpv_workspace_bytes with
+ * cfg == NULL says how much a shape needs) returns SPECPV_ELIMIT, and specpv_last_hip_error()
+ * then holds the two sizes; nothing has been enqueued.  Every call on a GPU shares that GPU's
+ * array, which keeps the last call's contents; nothing in it needs to start at zero.  Calls that
+ * overlap on one GPU (two streams without an ordering between them) race on it: order them. */
+#define SPECPV_STATIC_SCRATCH_BYTES (16u << 20)
+int specpv_partial_verify_attn_static(const specpv_kv *kv, const specpv_tree *tree,
+                                      const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
+                                      void *out, float *lse, void *stream);
+
 /* Section 3.3: full verification that also refreshes the partial cache.
  *   1. summaries of blocks [stale_blk_begin, nb_b) are recomputed in place
  *      (stale_blk_begin < 0: none);

@@ -21,7 +21,7 @@ _DTYPE = {torch.float32: 0, torch.bfloat16: 1}
 MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
 
 EXPORTS = ["specpv_workspace_bytes", "specpv_block_summarize", "specpv_select_blocks",
-           "specpv_partial_verify_attn", "specpv_full_verify_refresh", "specpv_gather_blocks", "specpv_select_mode",
+           "specpv_partial_verify_attn", "specpv_partial_verify_attn_static", "specpv_full_verify_refresh", "specpv_gather_blocks", "specpv_select_mode",
            "specpv_extend_parents", "specpv_commit_accepted", "specpv_commit_accepted_layers", "specpv_strerror",
            "specpv_last_hip_error", "specpv_version"]
 
@@ -86,6 +86,8 @@ def load():
     lib.specpv_select_blocks.argtypes = [P(_KV), P(_Tree), vp, vp, P(_Cfg), vp, vp, vp, vp, sz, vp]
     lib.specpv_partial_verify_attn.restype = ctypes.c_int
     lib.specpv_partial_verify_attn.argtypes = [P(_KV), P(_Tree), vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.specpv_partial_verify_attn_static.restype = ctypes.c_int
+    lib.specpv_partial_verify_attn_static.argtypes = [P(_KV), P(_Tree), vp, vp, i32, vp, vp, vp]
     lib.specpv_full_verify_refresh.restype = ctypes.c_int
     lib.specpv_full_verify_refresh.argtypes = [P(_KV), P(_Tree), vp, vp, i32, P(_Cfg), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.specpv_gather_blocks.restype = ctypes.c_int
@@ -270,6 +272,30 @@ def specpv_partial_verify_attn(kv, tree, sel_idx, sel_count, out, lse=None, work
                                              _ptr(sel_count, torch.int32, "sel_count"), n_sel,
                                              _ptr(out, kv.dtype, "out"), _ptr(lse, torch.float32, "lse"),
                                              wp, wb, _stream()))
+
+
+def specpv_partial_verify_attn_static(kv, tree, sel_idx, sel_count, out, lse=None):
+    """specpv_partial_verify_attn without a workspace: the partial results live in the library's own
+    static device array (at most STATIC_SCRATCH_BYTES; larger shapes raise SpecPVError -3)."""
+    _match(kv, tree)
+    n_sel = 0
+    if sel_idx is not None:
+        n_sel = sel_idx.shape[-1]
+        _check_sel(kv, sel_idx, sel_count, n_sel)
+    if out.shape != tree.q.shape:
+        raise ValueError("out: same shape as q")
+    if lse is not None and tuple(lse.shape) != (tree.batch, tree.Mq, tree.Hq):
+        raise ValueError("lse: [batch, Mq, Hq] float32")
+    rc = load().specpv_partial_verify_attn_static(ctypes.byref(kv.c), ctypes.byref(tree.c),
+                                                  _ptr(sel_idx, torch.int32, "sel_idx"),
+                                                  _ptr(sel_count, torch.int32, "sel_count"), n_sel,
+                                                  _ptr(out, kv.dtype, "out"), _ptr(lse, torch.float32, "lse"), _stream())
+    if rc == -3:
+        raise SpecPVError(rc, load().specpv_strerror(rc).decode() + " [" + load().specpv_last_hip_error().decode() + "]")
+    _check(rc)
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 def specpv_full_verify_refresh(kv, tree, kmax, kmin, stale_blk_begin, cfg, out, lse, sel_idx, sel_count,

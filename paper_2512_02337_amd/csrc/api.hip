@@ -196,6 +196,29 @@ static int run_attention(const Shape &s, int dtype, const int32_t *sel_idx, cons
     return SPECPV_OK;
 }
 
+// Library-owned scratch for callers that cannot pass a workspace (specpv_partial_verify_attn_static).
+// One copy per GPU, alive until the process ends.  In host code the array's name is only a handle:
+// the device address comes from hipGetSymbolAddress, once per device, and is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[SPECPV_STATIC_SCRATCH_BYTES];
+
+static hipError_t static_scratch(void **out)
+{
+    static void *ptr[64] = {};   // per device; a racing first call stores the same address
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    void *p = tracked ? __atomic_load_n(&ptr[dev], __ATOMIC_ACQUIRE) : nullptr;
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        if (tracked) __atomic_store_n(&ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return hipSuccess;
+}
+
 static int run_select(const Shape &s, int dtype, const specpv_tree *tree, const void *kmax, const void *kmin,
                       const specpv_select_cfg *cfg, int32_t *sel_idx, int32_t *sel_count, float *scores,
                       hipStream_t st)
@@ -274,6 +297,30 @@ int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree, con
     if (sel_idx && n_sel > (1 << 24)) return SPECPV_ELIMIT;
     const Shape s = make_shape(kv, tree);
     return run_attention(s, kv->dtype, sel_idx, sel_count, n_sel, out, lse, workspace, workspace_bytes,
+                         (hipStream_t)stream);
+}
+
+int specpv_partial_verify_attn_static(const specpv_kv *kv, const specpv_tree *tree, const int32_t *sel_idx,
+                                      const int32_t *sel_count, int32_t n_sel, void *out, float *lse, void *stream)
+{
+    int rc = check_kv(kv);
+    if (rc != SPECPV_OK) return rc;
+    if ((rc = check_tree(kv, tree, true)) != SPECPV_OK) return rc;
+    if (!out || ((uintptr_t)out & 15)) return SPECPV_EINVAL;
+    if (sel_idx && (!sel_count || n_sel < 0)) return SPECPV_EINVAL;
+    if (sel_idx && n_sel > (1 << 24)) return SPECPV_ELIMIT;
+    const Shape s = make_shape(kv, tree);
+    // the same plan as specpv_partial_verify_attn; its partial results must fit the static array
+    const AttnPlan plan = plan_attention(s, kv->dtype, sel_idx ? n_sel : s.max_blocks);
+    if (layout_workspace(s, plan.nsplit, nullptr).total > (size_t)SPECPV_STATIC_SCRATCH_BYTES) {
+        snprintf(g_hip_err, sizeof(g_hip_err), "static scratch: the call needs %zu bytes, the array holds %zu",
+                 layout_workspace(s, plan.nsplit, nullptr).total, (size_t)SPECPV_STATIC_SCRATCH_BYTES);
+        return SPECPV_ELIMIT;
+    }
+    void *ws = nullptr;
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return fail_hip(e);
+    return run_attention(s, kv->dtype, sel_idx, sel_count, n_sel, out, lse, ws, (size_t)SPECPV_STATIC_SCRATCH_BYTES,
                          (hipStream_t)stream);
 }
 
