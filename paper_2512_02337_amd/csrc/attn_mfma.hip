@@ -80,7 +80,7 @@ struct MfmaArgs {
     const int32_t *sel_idx, *sel_count;
     int n_sel;
     float scale_log2;
-    int n_units, row_tiles;
+    int n_units, row_tiles, n_bg;
     int rph, n_row_blocks;   // group kernel: 32-row blocks per query head, and per KV group (G * rph)
     FastDiv div_nsplit, div_hkv, div_B, div_W;
 };
@@ -200,7 +200,11 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void store_partial(float *p, float2 v)
 {
     f32x2 x = {v.x, v.y};
+#ifndef SPECPV_PARTIAL_PLAIN
     __builtin_nontemporal_store(x, (f32x2 *)p);
+#else
+    *(f32x2 *)p = x;
+#endif
 }
 
 // max / sum over the two half-wavefronts (lane and lane ^ 32)
@@ -239,10 +243,10 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 
     // ---- which piece of work is this workgroup -------------------------------------
     const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
-    const int u = blockIdx.y * 8 + xcd;
-    if (u >= a.n_units) return;
-    const int bg = (int)a.div_nsplit.div((uint32_t)u);
-    const int sp = u - bg * part.nsplit;
+    const int bgh = (int)a.div_nsplit.div(blockIdx.y);
+    const int sp = (int)blockIdx.y - bgh * part.nsplit;
+    const int bg = bgh * 8 + xcd;
+    if (bg >= a.n_bg) return;
     const int b = (int)a.div_hkv.div((uint32_t)bg);
     const int g = bg - b * s.Hkv;
     const int rt = r >= s.G ? 1 : 0;          // at most two row tiles (M <= 128)
@@ -928,13 +932,16 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     a.rph = gl.rph;
     a.n_row_blocks = gl.n_row_blocks;
     a.n_units = s.batch * s.Hkv * p.nsplit;
+    a.n_bg = s.batch * s.Hkv;
     a.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
     a.div_hkv = make_fastdiv((uint32_t)s.Hkv);
     a.div_B = make_fastdiv((uint32_t)s.B);
     // token ranges per split: four (one per token group of a workgroup), or one in the group kernel
     a.div_W = make_fastdiv((uint32_t)p.nsplit * (kind == kAttnGroup ? 1u : 4u));
     const int GR = kind == kAttnGroup ? gl.parts : s.G * a.row_tiles;
-    const dim3 grid(8 * GR, (a.n_units + 7) / 8);
+    // group kernel: a unit (sequence, KV head, split) per 8 consecutive x; split kernel: (sequence, KV
+    // head) bg on XCD bg % 8 with all its splits and query heads (y = (bg / 8) * nsplit + split)
+    const dim3 grid(8 * GR, kind == kAttnGroup ? (a.n_units + 7) / 8 : ((a.n_bg + 7) / 8) * p.nsplit);
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool aligned = s.B % 32 == 0;
     const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));

@@ -80,7 +80,11 @@ template <int CPL> __device__ __forceinline__ void load_partial(const float *p, 
     typedef float f32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int x = 0; x < CPL / 4; ++x) {
+#ifndef SPECPV_PARTIAL_PLAIN
         const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(p + i + 64 * x));
+#else
+        const f32x4 v = *(const f32x4 *)(p + i + 64 * x);
+#endif
         f[4 * x] = v[0]; f[4 * x + 1] = v[1]; f[4 * x + 2] = v[2]; f[4 * x + 3] = v[3];
     }
 }
@@ -101,10 +105,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
     typedef typename Chan<T, CPL>::Raw Raw;
     const int lane = threadIdx.x & 63;
     const int d0 = (lane & 15) * CPL;
-    const int b = blockIdx.z, j = blockIdx.x;
+    // x = XCD (workgroups go to the XCDs round-robin in linear order), y = node, z = bg / 8: the rows
+    // of (sequence, KV head) bg are merged on XCD bg % 8, where the split kernel produced them
+    const int bg = (int)blockIdx.z * 8 + (int)blockIdx.x;
+    if (bg >= s.batch * s.Hkv) return;
+    const int j = (int)blockIdx.y;
+    const int b = bg / s.Hkv;
     // four query heads of the KV group per wavefront; a group size that is no multiple of four
     // leaves lanes that repeat the last head and store nothing
-    const int g = blockIdx.y, hh = (int)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * 4 + (lane >> 4);
+    const int g = bg - b * s.Hkv, hh = (int)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * 4 + (lane >> 4);
     const bool live = hh < s.G;
     const int h = g * s.G + (live ? hh : s.G - 1);
 
@@ -266,7 +275,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
 template <typename T, int D>
 static void launch_combine_t(const Shape &s, Partials p, void *out, float *lse, hipStream_t st)
 {
-    dim3 grid(s.M, s.Hkv, s.batch), block(64 * ((s.G + 3) / 4));
+    dim3 grid(8, s.M, (s.batch * s.Hkv + 7) / 8), block(64 * ((s.G + 3) / 4));
     const float scale_log2 = kLog2e / sqrtf((float)s.D);
 #define SPECPV_LAUNCH_NP(NP, MULTI) \
     hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
