@@ -94,7 +94,7 @@ def main():
                   out_full=torch.empty_like(case["q"]))
         layers.append(st)
     ws_bytes = max(specpv.specpv_workspace_bytes(l["kv"], l["tree"], l["cfg"]) for l in layers)
-    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)
+    ws = torch.zeros((ws_bytes,), dtype=torch.uint8, device=dev)   # zero-filled once: the arrival words
     for l in layers:   # untimed: the refresh that produces the kept-block lists
         specpv.specpv_full_verify_refresh(l["kv"], l["tree"], l["kmax"], l["kmin"], 0, l["cfg"], l["out_full"], None,
                                           l["sel_idx"], l["sel_count"], None, ws)
@@ -264,7 +264,7 @@ def main():
                 bkmin = torch.empty_like(bkmax)
                 bsel = torch.empty((bc["batch"], bc["Hkv"], bscfg.n_sel), dtype=torch.int32, device=dev)
                 bcnt = torch.empty((bc["batch"], bc["Hkv"]), dtype=torch.int32, device=dev)
-                bws = torch.empty((specpv.specpv_workspace_bytes(bkv, btree, bscfg),), dtype=torch.uint8, device=dev)
+                bws = torch.zeros((specpv.specpv_workspace_bytes(bkv, btree, bscfg),), dtype=torch.uint8, device=dev)
                 specpv.specpv_block_summarize(bkv, 0, -1, bkmax, bkmin)
                 specpv.specpv_select_blocks(bkv, btree, bkmax, bkmin, bscfg, bsel, bcnt, None, bws)
                 bsets.append((bc, bkv, btree, bsel, bcnt, torch.empty_like(bc["q"]), bws))

@@ -112,7 +112,12 @@ typedef struct specpv_select_cfg {
 
 /* Bytes of workspace that any of the calls below needs for these descriptors
  * (host-only computation; 0 on invalid descriptors).  cfg may be NULL if only
- * specpv_block_summarize is used. */
+ * specpv_block_summarize is used.
+ * A workspace must be ZERO-FILLED ONCE before its first use (hipMemset, torch.zeros): its first
+ * 64 KiB hold the arrival words through which the workgroups of the single-kernel route of
+ * specpv_partial_verify_attn (specpv_debug_set_route) find out which of them finishes a row tile.  Every call leaves them zero again, so one fill at
+ * allocation is enough, whatever shapes use the workspace afterwards.  A call that is given
+ * words that are not zero computes garbage (it cannot notice). */
 size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, const specpv_select_cfg *cfg);
 
 /* Section 3.2, eq. 1.  For every sequence b, KV head g and block i in
@@ -279,6 +284,25 @@ int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k
                                   int32_t max_accept, specpv_mode mode, void *const *kmax, void *const *kmin,
                                   const specpv_lists *lists, int32_t *dropped,
                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* Testing and measuring aid, process-wide (not per thread, not per stream): how
+ * specpv_partial_verify_attn runs the shapes that its eight-wavefront kernel takes (bf16, head dim
+ * 128, short token ranges).
+ *   0  the library's choice (currently two kernels)
+ *   1  two kernels: context attention, then the log-sum-exp combine with the draft-tree segment
+ *   2  one kernel: the draft-tree segment is one more partial, and the last workgroup of a row
+ *      tile to arrive merges the tile's partials out of its XCD's L2 (no workgroup waits for another)
+ *   3  as 2, and the last workgroup of every tile takes the route that is otherwise only taken when
+ *      workgroups of a tile ran on different XCDs: it recomputes the tile by itself
+ * All give results within the documented bars.  Returns SPECPV_OK or SPECPV_EINVAL. */
+int specpv_debug_set_route(int route);
+
+/* Measuring aid, process-wide.  A library built with -DSPECPV_TIMELINE (see paper_2512_02337_amd/build.py:
+ * SPECPV_EXTRA_HIPCC_FLAGS) makes every workgroup of the partial-verify attention kernel store 16
+ * 64-bit readings of the 100 MHz real-time counter at fixed points of its course to
+ * buf[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + i] (device memory, NULL = off).  A regular build
+ * stores nothing.  profiles/ says what the points are. */
+int specpv_debug_set_timeline(void *buf);
 
 const char *specpv_strerror(int status);
 /* Text of the HIP error behind the calling thread's last SPECPV_EHIP. */

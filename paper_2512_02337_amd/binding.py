@@ -23,7 +23,7 @@ MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
 EXPORTS = ["specpv_workspace_bytes", "specpv_block_summarize", "specpv_select_blocks",
            "specpv_partial_verify_attn", "specpv_partial_verify_attn_static", "specpv_full_verify_refresh", "specpv_gather_blocks", "specpv_select_mode",
            "specpv_extend_parents", "specpv_commit_accepted", "specpv_commit_accepted_layers", "specpv_strerror",
-           "specpv_last_hip_error", "specpv_version"]
+           "specpv_last_hip_error", "specpv_version", "specpv_debug_set_route", "specpv_debug_set_timeline"]
 
 
 class SpecPVError(RuntimeError):
@@ -102,6 +102,8 @@ def load():
     lib.specpv_commit_accepted_layers.restype = ctypes.c_int
     lib.specpv_commit_accepted_layers.argtypes = [P(P(_KV)), P(vp), P(vp), i32, i32, i32, vp, vp, vp, i32, ctypes.c_int,
                                                   P(vp), P(vp), P(_Lists), vp, vp, sz, vp]
+    lib.specpv_debug_set_route.restype = ctypes.c_int
+    lib.specpv_debug_set_route.argtypes = [ctypes.c_int]
     lib.specpv_strerror.restype = ctypes.c_char_p
     lib.specpv_strerror.argtypes = [ctypes.c_int]
     lib.specpv_last_hip_error.restype = ctypes.c_char_p
@@ -423,6 +425,18 @@ def specpv_commit_accepted_layers(kvs, buf_ks, buf_vs, pending_cap, M_tree, n_pe
                                                 _ptr(accepted, torch.int32, "accepted"),
                                                 _ptr(n_accepted, torch.int32, "n_accepted"), int(accepted.shape[1]),
                                                 int(mode), km, kn, ls, _dropped(kv0, dropped), wp, wb, _stream()))
+
+
+def specpv_debug_set_timeline(buf):
+    """buf: int64 GPU tensor of 16 entries per workgroup, or None."""
+    lib = load()
+    lib.specpv_debug_set_timeline.argtypes = [ctypes.c_void_p]
+    lib.specpv_debug_set_timeline.restype = ctypes.c_int
+    _check(lib.specpv_debug_set_timeline(None if buf is None else ctypes.c_void_p(buf.data_ptr())))
+
+
+def specpv_debug_set_route(route):
+    _check(load().specpv_debug_set_route(int(route)))
 
 
 def specpv_strerror(status):

@@ -18,6 +18,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 def build(verbose=False, jobs=8):
     """Compile every HIP source to an object (in parallel) and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = os.environ.get("SPECPV_EXTRA_HIPCC_FLAGS", "").split()   # for experiments: e.g. -DNAME
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs = []
@@ -25,7 +26,7 @@ def build(verbose=False, jobs=8):
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         while sum(p.poll() is None for _, p in procs) >= jobs:
             procs[0][1].wait() if procs[0][1].poll() is None else None

@@ -159,7 +159,10 @@ static AttnPlan plan_attention(const Shape &s, int dtype, int64_t n_blocks)
     return plan;
 }
 
+// Workspace layout: [arrival words, kArriveBytes, zero between calls][partial O][(m, l) pairs][scores],
+// the partial arrays sized for nsplit + 1 slots (the context splits and the draft-tree segment).
 struct Workspace {
+    unsigned long long *arrive;
     float *part_o, *part_ml, *scores;
     size_t total;
 };
@@ -167,16 +170,23 @@ struct Workspace {
 static Workspace layout_workspace(const Shape &s, int nsplit, void *base)
 {
     Workspace w;
-    const size_t po = align_up((size_t)s.batch * s.Hq * nsplit * s.M * s.D * sizeof(float));
-    const size_t pm = align_up((size_t)s.batch * s.Hq * nsplit * s.M * 2 * sizeof(float));
+    const size_t slots = (size_t)nsplit + 1;
+    const size_t po = align_up((size_t)s.batch * s.Hq * slots * s.M * s.D * sizeof(float));
+    const size_t pm = align_up((size_t)s.batch * s.Hq * slots * s.M * 2 * sizeof(float));
     const size_t sc = align_up((size_t)s.batch * s.Hkv * s.max_blocks * sizeof(float));
     char *p = (char *)base;
-    w.part_o = (float *)p;
-    w.part_ml = (float *)(p + po);
-    w.scores = (float *)(p + po + pm);
-    w.total = po + pm + sc;
+    w.arrive = (unsigned long long *)p;
+    w.part_o = (float *)(p + kArriveBytes);
+    w.part_ml = (float *)(p + kArriveBytes + po);
+    w.scores = (float *)(p + kArriveBytes + po + pm);
+    w.total = kArriveBytes + po + pm + sc;
     return w;
 }
+
+// Process-wide choice of how specpv_partial_verify_attn runs shapes that the eight-wavefront kernel
+// takes (a testing aid, see specpv_debug_set_route).
+static int g_route = 0;
+static unsigned long long *g_timeline = nullptr;   // where instrumented builds (-DSPECPV_TIMELINE) put their time stamps
 
 static int run_attention(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count,
                          int n_sel, void *out, float *lse, void *workspace, size_t workspace_bytes,
@@ -186,9 +196,21 @@ static int run_attention(const Shape &s, int dtype, const int32_t *sel_idx, cons
     const int nsplit = plan.nsplit;
     const Workspace w = layout_workspace(s, nsplit, workspace);
     if (!workspace || workspace_bytes < w.total) return SPECPV_EWORKSPACE;
-    Partials p{w.part_o, w.part_ml, nsplit};
+    const int route = __atomic_load_n(&g_route, __ATOMIC_RELAXED);
+    // The single-kernel route is correct but measured slower than two launches (the last workgroup of a
+    // tile reads all of the tile's partials through one CU): it runs only on request.
+    const bool fused = plan.kind == kAttnSplit && route >= 2 && nsplit <= 64 &&
+                       (size_t)s.batch * s.Hq * 2 * sizeof(unsigned long long) <= kArriveBytes;
     hipError_t e;
-    if (plan.kind != kAttnGeneric) e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, plan.kind, st);
+    if (fused) {
+        Partials p{w.part_o, w.part_ml, nsplit + 1};
+        const FusedArgs f{out, lse, w.arrive, route == 3 ? 1 : 0, g_timeline};
+        e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, nsplit, plan.kind, f, st);
+        return e == hipSuccess ? SPECPV_OK : fail_hip(e);
+    }
+    Partials p{w.part_o, w.part_ml, nsplit};
+    const FusedArgs none{nullptr, nullptr, nullptr, 0, g_timeline};
+    if (plan.kind != kAttnGeneric) e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, nsplit, plan.kind, none, st);
     else e = launch_attn_ctx_generic(s, dtype, sel_idx, sel_count, n_sel, p, st);
     if (e != hipSuccess) return fail_hip(e);
     e = launch_combine(s, dtype, p, out, lse, st);
@@ -242,7 +264,7 @@ extern "C" {
 size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, const specpv_select_cfg *cfg)
 {
     if (check_kv(kv) != SPECPV_OK) return 0;
-    if (!tree) { const size_t n = align_up((size_t)kv->batch * sizeof(int32_t)); return n > 256 ? n : 256; }
+    if (!tree) return kArriveBytes + align_up((size_t)kv->batch * sizeof(int32_t));
     if (check_tree(kv, tree, false) != SPECPV_OK) return 0;
     const Shape s = make_shape(kv, tree);
     int nsplit = plan_attention(s, kv->dtype, s.max_blocks).nsplit;
@@ -278,9 +300,10 @@ int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree, const voi
     if (((uintptr_t)kmax | (uintptr_t)kmin) & 15) return SPECPV_EINVAL;
     const Shape s = make_shape(kv, tree);
     if (!scores) {
-        const size_t need = align_up((size_t)s.batch * s.Hkv * s.max_blocks * sizeof(float));
+        // behind the arrival words, which stay zero
+        const size_t need = kArriveBytes + align_up((size_t)s.batch * s.Hkv * s.max_blocks * sizeof(float));
         if (!workspace || workspace_bytes < need) return SPECPV_EWORKSPACE;
-        scores = (float *)workspace;
+        scores = (float *)((char *)workspace + kArriveBytes);
     }
     return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores, (hipStream_t)stream);
 }
@@ -401,7 +424,8 @@ int specpv_commit_accepted(const specpv_kv *kv, void *buf_k, void *buf_v, int32_
     if (((uintptr_t)buf_k | (uintptr_t)buf_v) & 15) return SPECPV_EINVAL;
     if ((kmax || kmin) && (!kmax || !kmin || (((uintptr_t)kmax | (uintptr_t)kmin) & 15))) return SPECPV_EINVAL;
     if ((int64_t)pending_cap + max_accept > 128 || (int64_t)pending_cap + M_tree > SPECPV_MAX_M) return SPECPV_ELIMIT;
-    if (!workspace || workspace_bytes < (size_t)kv->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
+    if (!workspace || workspace_bytes < kArriveBytes + (size_t)kv->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
+    workspace = (char *)workspace + kArriveBytes;   // the arrival words stay zero
     const Shape s = make_shape(kv, nullptr);
     void *k1 = const_cast<void *>(kv->k), *v1 = const_cast<void *>(kv->v);
     const hipError_t e = launch_commit(s, kv->dtype, 1, &k1, &v1, &buf_k, &buf_v, pending_cap, M_tree, n_pending, accepted,
@@ -447,7 +471,8 @@ int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k
         kp[l] = const_cast<void *>(x->k);
         vp[l] = const_cast<void *>(x->v);
     }
-    if (!workspace || workspace_bytes < (size_t)kv[0]->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
+    if (!workspace || workspace_bytes < kArriveBytes + (size_t)kv[0]->batch * sizeof(int32_t)) return SPECPV_EWORKSPACE;
+    workspace = (char *)workspace + kArriveBytes;   // the arrival words stay zero
     const Shape s = make_shape(kv[0], nullptr);
     const hipError_t e = launch_commit(s, kv[0]->dtype, n_layers, kp, vp, buf_k, buf_v, pending_cap, M_tree, n_pending,
                                        accepted, n_accepted, max_accept, mode != SPECPV_MODE_PARTIAL, kmax, kmin,
@@ -468,6 +493,19 @@ const char *specpv_strerror(int status)
 }
 
 const char *specpv_last_hip_error(void) { return g_hip_err; }
+
+int specpv_debug_set_timeline(void *buf)
+{
+    g_timeline = (unsigned long long *)buf;
+    return SPECPV_OK;
+}
+
+int specpv_debug_set_route(int route)
+{
+    if (route < 0 || route > 3) return SPECPV_EINVAL;
+    __atomic_store_n(&g_route, route, __ATOMIC_RELAXED);
+    return SPECPV_OK;
+}
 
 int specpv_version(void) { return 200; }
 

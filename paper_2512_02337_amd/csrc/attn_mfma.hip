@@ -220,10 +220,73 @@ __device__ __forceinline__ float sum_xor32(float x)
 }
 
 
-// grid: x = r * 8 + xcd   (r = query head within the group + G * row tile),  y = unit / 8
-// with unit = ((b * Hkv + g) * nsplit + split).  Workgroups are handed to the 8 XCDs
-// round-robin in linear order and gridDim.x is a multiple of 8, so a unit (and the G
-// query heads that share its K/V bytes) stays on XCD unit % 8.
+__device__ __forceinline__ float max_xor16(float x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xor16(float x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// Sum over the 16 lanes of a DPP row, result in every lane of the row: lane ^ 1, lane ^ 2, then the
+// mirrors inside 8 and 16 lanes.
+template <int CTRL> __device__ __forceinline__ float dpp_row_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_row_f32<0xB1>(x);
+    x += dpp_row_f32<0x4E>(x);
+    x += dpp_row_f32<0x141>(x);
+    x += dpp_row_f32<0x140>(x);
+    return x;
+}
+// max / sum over the 8 lanes 8 u .. 8 u + 7 (lane ^ 1, lane ^ 2, mirror inside 8)
+__device__ __forceinline__ float oct_max(float x)
+{
+    x = fmaxf(x, dpp_row_f32<0xB1>(x));
+    x = fmaxf(x, dpp_row_f32<0x4E>(x));
+    x = fmaxf(x, dpp_row_f32<0x141>(x));
+    return x;
+}
+__device__ __forceinline__ float oct_sum(float x)
+{
+    x += dpp_row_f32<0xB1>(x);
+    x += dpp_row_f32<0x4E>(x);
+    x += dpp_row_f32<0x141>(x);
+    return x;
+}
+// The root path of tree node j as a bit set; par0 / par1 hold parent[lane] / parent[lane + 64].
+// Everything is wave-uniform (scalar registers).
+__device__ __forceinline__ void root_path(int j, int n_nodes, int par0, int par1, unsigned long long &lo,
+                                          unsigned long long &hi)
+{
+    int aa = j;
+    for (int guard = 0; aa >= 0 && guard < n_nodes; ++guard) {
+        if (aa < 64) lo |= 1ull << aa; else hi |= 1ull << (aa - 64);
+        const int pa = aa < 64 ? __builtin_amdgcn_readlane(par0, aa) : __builtin_amdgcn_readlane(par1, aa - 64);
+        aa = pa < aa ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
+    }
+}
+// lowest node of the set (removed from it), or -1
+__device__ __forceinline__ int pop_node(unsigned long long &lo, unsigned long long &hi)
+{
+    int aa = -1;
+    if (lo) { aa = __builtin_ctzll(lo); lo &= lo - 1; }
+    else if (hi) { aa = 64 + __builtin_ctzll(hi); hi &= hi - 1; }
+    return aa;
+}
+
+// ---- eight-wavefront kernel: one query head, one tile of up to 64 nodes, one KV split ----------
+// grid: x = r * 8 + xcd   (r = query head within the group + G * row tile),
+//       y = (bg / 8) * nsplit + split   with bg = b * Hkv + g and xcd = bg % 8.
+// Workgroups are handed to the 8 XCDs round-robin in linear order and gridDim.x is a multiple of
+// 8, so a (sequence, KV head) stays on XCD bg % 8 with all its splits and query heads: the K/V
+// bytes of a split come from HBM once and from that XCD's L2 for the other query heads, and the
+// split-KV partials of a head meet in one L2.
 //
 // Workgroup = 8 wavefronts = 4 token groups x 2 row blocks.  Wavefronts tg and tg + 4
 // sit on the same SIMD, work on the same chunks (rows 0..31 and 32..63 of the tile)
@@ -231,22 +294,55 @@ __device__ __forceinline__ float sum_xor32(float x)
 // rows.  Two workgroup barriers per chunk order "DMA landed -> both read" and "both
 // read -> stage may be refilled".  Every wavefront runs the same number of iterations
 // (the largest chunk count in the workgroup), so the barriers always match up.
-template <bool ALIGNED>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
+//
+// FUSED: the whole call in this one kernel.
+//  * The draft-tree segment (a node attends itself and its ancestors, tree decode of Algorithm 1)
+//    is one more partial per row, in slot `nctx` behind the context splits: the workgroup of
+//    split sp computes it for the rows r = sp (mod nctx) of its tile on the vector ALU, one row
+//    per wavefront, while its first K/V chunks are on their way.
+//  * Partials are stored with ordinary stores (they stay in this XCD's L2), then the workgroup
+//    adds itself to the tile's arrival word (one 64-bit atomic add: arrival count in the top byte,
+//    7 bits of count per hardware XCC id below).  No workgroup ever waits for another one.
+//  * The workgroup whose add completes the count merges the nctx + 1 partials of its tile by their
+//    log-sum-exp weights, normalises, stores out / lse and zeroes the word.  It reads the
+//    others' partials from L2, which is only right if they were written through the SAME L2: if
+//    the XCC ids in the word say that any workgroup of the tile ran elsewhere (never seen; the
+//    dispatcher's round-robin is not a documented guarantee), the last workgroup recomputes the
+//    tile from scratch instead -- every split and the draft segment, merged in its own registers --
+//    so the result never depends on where workgroups run.
+constexpr int kXccBits = 7;
+#ifdef SPECPV_TIMELINE
+#define SPECPV_STAMP(i)                                                                                       \
+    do {                                                                                                      \
+        if (f.timeline && threadIdx.x == 0 && !REDO)                                                          \
+            f.timeline[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (i)] = __builtin_amdgcn_s_memrealtime(); \
+    } while (0)
+#else
+#define SPECPV_STAMP(i) do {} while (0)
+#endif        // per-XCC arrival count (splits <= 64)
+
+// One pass over the token ranges of split `sp0` of `ns_eff` splits.  REDO = false: the ordinary pass of
+// a workgroup (ns_eff = nctx); returns true if this workgroup, the last of its tile, has to take the
+// recompute route.  REDO = true: that route -- the pass runs as the only split of one (sp0 = 0, ns_eff = 1).
+// Everything, the argument-dependent reads included, is done again in the second pass, so that it keeps
+// no register of the first one alive.
+template <bool ALIGNED, bool FUSED, bool REDO>
+__device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a, FusedArgs f, const int nctx,
+                                              const int sp0, const int ns_eff, char *lds_raw)
 {
-    extern __shared__ char lds_raw[];
     float *ms = (float *)lds_raw;            // [4 token groups][64 rows]
     float *ls = ms + 4 * 64;                 // [4][64]
     char *ring = lds_raw + 2048;             // [4 pairs][kStages][K 8 KiB | V 8 KiB]
     float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
+    constexpr bool redo = REDO;
+    const int sp = sp0;
+    SPECPV_STAMP(0);   // entry
 
     // ---- which piece of work is this workgroup -------------------------------------
     const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
     const int bgh = (int)a.div_nsplit.div(blockIdx.y);
-    const int sp = (int)blockIdx.y - bgh * part.nsplit;
     const int bg = bgh * 8 + xcd;
-    if (bg >= a.n_bg) return;
+    if (bg >= a.n_bg) return false;
     const int b = (int)a.div_hkv.div((uint32_t)bg);
     const int g = bg - b * s.Hkv;
     const int rt = r >= s.G ? 1 : 0;          // at most two row tiles (M <= 128)
@@ -261,26 +357,18 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 
     // Everything whose address only depends on the kernel arguments is requested up
     // front, so that the cold-miss latencies of these small reads overlap: context
-    // length, list length, the kept-block ids this wavefront will most likely need
-    // (assuming a full list), and the query rows.
+    // length, list length, the kept-block list (up to 256 entries, lane t: entries t, t + 64, ..),
+    // the query rows, and for the draft segment the parents and this wavefront's first row.
     const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
-    const int W = part.nsplit * 4, wsid = sp * 4 + tg;
     const uint32_t Bu = (uint32_t)s.B;
     const int L = s.ctx_len[b];
     const int cnt_raw = sel ? a.sel_count[bg] : 0;
-    // chunks of a list that precede the share of token group w; shares differ by at most one
-    auto first_chunk = [&](uint32_t chunks, int w) -> int {
-        const uint32_t base = a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
-        return (int)((uint32_t)w * base + min((uint32_t)w, rem));
-    };
-    // lane t: the kept-block id that chunk t of this wavefront falls into, if the list is full
-    // (its length is not known yet; the usual case)
-    uint32_t spec_C = 0u;
-    int spec_blk = -1;
-    if (ALIGNED && sel) {
-        spec_C = ((uint32_t)a.n_sel * Bu + 31u) >> 5;
-        const uint32_t slot = a.div_B.div((uint32_t)(first_chunk(spec_C, wsid) + lane) * 32u);
-        spec_blk = slot < (uint32_t)a.n_sel ? sel[slot] : -1;
+    const bool list_in_regs = ALIGNED && sel && a.n_sel <= 256;
+    int idv[4] = {-1, -1, -1, -1};
+    if (list_in_regs) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            if (lane + 64 * x < a.n_sel) idv[x] = sel[lane + 64 * x];
     }
     uint4 qraw[8];
     {
@@ -289,6 +377,16 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qraw[ks] = *(const uint4 *)(qrow + ks * 16);
     }
+    const int rows_tile = min(64, s.M - m0);            // >= 1
+    int par0 = -1, par1 = -1;
+    uint4 qd_first = make_uint4(0u, 0u, 0u, 0u);
+    if (FUSED) {
+        const int32_t *par = s.parent + (int64_t)b * s.Mk;
+        if (lane < s.Mk) par0 = par[lane];
+        if (lane + 64 < s.Mk) par1 = par[lane + 64];
+        const int r0 = min(sp0 + ns_eff * wave, rows_tile - 1);
+        qd_first = *(const uint4 *)((const uint16_t *)s.q + (((int64_t)b * s.M + m0 + r0) * s.Hq + h) * 128 + (lane & 15) * 8);
+    }
 
     int nb = L > 0 ? (int)a.div_B.div((uint32_t)(L + s.B - 1)) : 0;
     if (nb > s.max_blocks) nb = s.max_blocks;
@@ -296,9 +394,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
     const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;   // host guarantees max_blocks * B <= 2^30
     const uint32_t C = (T + 31u) >> 5;
-    const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
-    const int nch = c1 - c0;
-    const int nch_max = first_chunk(C, sp * 4 + 1) - first_chunk(C, sp * 4);   // token group 0 has the most
 
     // uniform slab bases; per-lane byte offsets inside a slab fit 32 bits (host-checked)
     const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
@@ -310,12 +405,31 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     // K tile in LDS: row-major, 256 B per token, the 16-byte pieces of row t stored at
     // piece index (p ^ (t & 7)) so that the operand reads below (32 lanes, same piece,
     // different rows) spread over all banks.  Operand piece of k-step ks: 2*ks + kg.
-    uint32_t kread[8];
+    uint32_t kread[4];   // + stage * kStageBytes; k-step ks + 4 is 128 bytes behind k-step ks
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < 4; ++ks)
         kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u)));
     const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
                            32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
+
+    bf16x8 qf[8];   // Q fragments (B operand of S^T = K . Q^T): row = lane & 31
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
+
+    const int r4 = lane >> 4, pos = lane & 15;
+    const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+    const uint32_t lane_row_off = (uint32_t)r4 * st2;
+    constexpr int RPW = 8;  // rows each wavefront finishes in the epilogue
+
+    const int W = ns_eff * 4, wsid = sp * 4 + tg;
+    // chunks of a list that precede the share of token group w; shares differ by at most one
+    auto first_chunk = [&](uint32_t chunks, int w) -> int {
+        const uint32_t base = redo ? (chunks >> 2) : a.div_W.div(chunks), rem = chunks - base * (uint32_t)W;
+        return (int)((uint32_t)w * base + min((uint32_t)w, rem));
+    };
+    const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
+    const int nch = c1 - c0;
+    const int nch_max = first_chunk(C, sp * 4 + 1) - first_chunk(C, sp * 4);   // token group 0 has the most
 
     // ---- chunk -> token rows ------------------------------------------------------------
     // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive.  The
@@ -342,6 +456,18 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         // joins behind it carries no pending load (and no wait on the DMA prefetch)
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     };
+    // the first 64 chunks: the list sits in registers (lane t: entries t, t + 64, ...), so this is a
+    // cross-lane read and no second trip to memory
+    auto fill_rows_first = [&]() {
+        if (!list_in_regs) { fill_rows(0); return; }
+        const uint32_t p0 = (uint32_t)(c0 + lane) * 32u;
+        const uint32_t slot = a.div_B.div(p0);
+        const int src = (int)(slot & 63u);
+        const int e0 = __shfl(idv[0], src), e1 = __shfl(idv[1], src), e2 = __shfl(idv[2], src), e3 = __shfl(idv[3], src);
+        const int q4 = (int)(slot >> 6);
+        const int blk = q4 == 0 ? e0 : (q4 == 1 ? e1 : (q4 == 2 ? e2 : e3));
+        row0vec = lane < nch ? encode_row(blk, p0, slot) : -1;   // p0 < T there: the slot is < cnt
+    };
     // general case: this lane's token (t = lane & 31) of chunk ci, or -1
     auto lane_row = [&](int ci) -> int {
         const uint32_t p = (uint32_t)(c0 + ci) * 32u + (uint32_t)n;
@@ -358,9 +484,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     // Request this wavefront's half of chunk ci: 8 DMA operations of 1 KiB (one 256-byte row per
     // 16 lanes).  rb == 0: the K rows, operation i brings rows 4i .. 4i+3, pieces swizzled by
     // row & 7.  rb == 1: the V rows, operation i brings rows i, i+8, i+16, i+24 into piece i.
-    const int r4 = lane >> 4, pos = lane & 15;
-    const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-    const uint32_t lane_row_off = (uint32_t)r4 * st2;
     auto issue = [&](int ci) {
         const int stg = ci & (kStages - 1);
         char *dst = my_ring + stg * kStageBytes;
@@ -421,18 +544,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         }
     };
 
-    // ---- Q fragments (B operand of S^T = K . Q^T): row = lane & 31 ------------------
-    bf16x8 qf[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
-    if (ALIGNED && nch > 0) {
-        if (sel && C == spec_C) {   // the usual case: the speculative ids are the right ones
-            const uint32_t p0 = (uint32_t)(c0 + lane) * 32u;
-            row0vec = lane < nch ? encode_row(spec_blk, p0, a.div_B.div(p0)) : -1;
-        } else {
-            fill_rows(0);
-        }
-    }
+    if (ALIGNED && nch > 0) fill_rows_first();
     // every load above has been consumed here: from now on the only vector-memory
     // operations of this wavefront in flight are its own DMA groups (8 operations each)
     // (as an instruction the compiler knows, not inline assembly: otherwise it assumes that the
@@ -440,6 +552,87 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
     // i.e. for the prefetch just issued, at the first use of Q in every iteration)
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt untouched
     asm volatile("" ::: "memory");
+    SPECPV_STAMP(1);   // arguments, lengths, list, query rows, parents are in
+
+    // ---- draft-tree segment of this workgroup's rows (FUSED) --------------------------------
+    // Row r of the tile (node koff + m0 + r) is handled by the workgroup with sp = r mod ns_eff, there
+    // by wavefront (r / ns_eff) mod 8.  Sixteen lanes per draft node (a lane owns 8 adjacent
+    // channels), four nodes of the root path at a time; the result goes to slot nctx of the
+    // partial arrays like any other partial.  For a wavefront's first row the first two rounds of
+    // K / V rows (8 path nodes) are requested in front of the first context chunks.
+    auto draft_row = [&](int row, bool live, bool with_chunks) {
+        const int jn = s.koff + m0 + row;
+        unsigned long long anc_lo = 0ull, anc_hi = 0ull;
+        root_path(jn, s.Mk, par0, par1, anc_lo, anc_hi);
+        const int n0 = pop_node(anc_lo, anc_hi), n1 = pop_node(anc_lo, anc_hi), n2 = pop_node(anc_lo, anc_hi),
+                  n3 = pop_node(anc_lo, anc_hi), n4 = pop_node(anc_lo, anc_hi), n5 = pop_node(anc_lo, anc_hi),
+                  n6 = pop_node(anc_lo, anc_hi), n7 = pop_node(anc_lo, anc_hi);
+        const int na = r4 == 0 ? n0 : (r4 == 1 ? n1 : (r4 == 2 ? n2 : n3));
+        const int nb2 = r4 == 0 ? n4 : (r4 == 1 ? n5 : (r4 == 2 ? n6 : n7));
+        auto drow = [&](const void *base, int node) -> const uint16_t * {
+            return (const uint16_t *)base + (((int64_t)b * s.Mk + max(node, 0)) * s.Hkv + g) * 128 + pos * 8;
+        };
+        uint4 qd = qd_first;
+        if (!with_chunks) qd = *(const uint4 *)((const uint16_t *)s.q + (((int64_t)b * s.M + m0 + row) * s.Hq + h) * 128 + pos * 8);
+        // requested in front of the first context chunks; the compiler places the wait (it waits for the
+        // chunks as well: in-flight registers that it does not know about are not safe to hold)
+        const uint4 ka = *(const uint4 *)drow(s.kd, na), va = *(const uint4 *)drow(s.vd, na);
+        const uint4 kb2 = *(const uint4 *)drow(s.kd, nb2), vb2 = *(const uint4 *)drow(s.vd, nb2);
+        if (with_chunks) {
+            if (nch > 0) issue(0);
+            if (nch > 1) issue(1);
+        }
+        float qv[8];
+        Elem<bf16_t>::unpack(qd, qv);
+        float md = -INFINITY, ld = 0.f, od[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) od[x] = 0.f;
+        auto one = [&](int node, const uint4 &kraw, const uint4 &vraw) {
+            float kf[8], vf[8];
+            Elem<bf16_t>::unpack(kraw, kf);
+            Elem<bf16_t>::unpack(vraw, vf);
+            float dot = 0.f;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) dot = fmaf(qv[x], kf[x], dot);
+            const float z = node >= 0 ? row16_sum(dot) * a.scale_log2 : -INFINITY;
+            const float m_new = fmaxf(md, z);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(md - m_use);   // 0 while nothing has been seen
+            const float pe = __builtin_amdgcn_exp2f(z - m_use);      // 0 for an empty slot
+            ld = fmaf(ld, alpha, pe);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) od[x] = fmaf(od[x], alpha, pe * vf[x]);
+            md = m_new;
+        };
+        one(na, ka, va);
+        one(nb2, kb2, vb2);
+        while (anc_lo | anc_hi) {   // root paths longer than 8 nodes (these reads queue behind the chunks)
+            const int c0n = pop_node(anc_lo, anc_hi), c1n = pop_node(anc_lo, anc_hi), c2n = pop_node(anc_lo, anc_hi),
+                      c3n = pop_node(anc_lo, anc_hi);
+            const int nc = r4 == 0 ? c0n : (r4 == 1 ? c1n : (r4 == 2 ? c2n : c3n));
+            const uint4 kc = *(const uint4 *)drow(s.kd, nc), vc = *(const uint4 *)drow(s.vd, nc);
+            one(nc, kc, vc);
+        }
+        // the four lane groups hold disjoint parts of the path: merge them (lanes ^16, ^32)
+        const float m_all = max_xor32(max_xor16(md));          // finite: the node itself is on its path
+        const float wgt = __builtin_amdgcn_exp2f(md - m_all);   // 0 for a group without a node
+        ld = sum_xor32(sum_xor16(ld * wgt));
+#pragma unroll
+        for (int x = 0; x < 8; ++x) od[x] = sum_xor32(sum_xor16(od[x] * wgt));
+        if (live && r4 == 0) {
+            // channels 8 pos .. 8 pos + 7 sit at positions 4 pos .. + 3 and 64 + 4 pos .. + 3 of the stored order
+            const int64_t prow = ((int64_t)(b * s.Hq + h) * part.nsplit + nctx) * s.M + m0 + row;
+            float *po = part.o + prow * 128;
+            *(float4 *)(po + 4 * pos) = make_float4(od[0], od[1], od[2], od[3]);
+            *(float4 *)(po + 64 + 4 * pos) = make_float4(od[4], od[5], od[6], od[7]);
+            if (pos == 0) *(float2 *)(part.ml + prow * 2) = make_float2(m_all, ld);
+        }
+    };
+    auto draft_rows = [&]() {
+        const int rr0 = sp + ns_eff * wave;
+        draft_row(min(rr0, rows_tile - 1), rr0 < rows_tile, true);      // requests chunks 0 and 1 on its way
+        for (int rr = rr0 + ns_eff * 8; rr < rows_tile; rr += ns_eff * 8) draft_row(rr, true, false);
+    };
 
     f32x16 O[4];
     float m_ref = -INFINITY, l_run = 0.f;
@@ -449,8 +642,13 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         for (int i = 0; i < 16; ++i) O[j][i] = 0.f;
 
     // ---- main loop ---------------------------------------------------------------------
-    if (nch > 0) issue(0);
-    if (nch > 1) issue(1);
+    if (FUSED) {
+        draft_rows();
+    } else {
+        if (nch > 0) issue(0);
+        if (nch > 1) issue(1);
+    }
+    SPECPV_STAMP(2);   // first chunks requested, draft rows done
     for (int i = 0; i < nch_max; ++i) {
         const bool active = i < nch;
         const int stg = i & 1;
@@ -458,12 +656,15 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
         if (i + 1 < nch) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();          // ... and so has the partner's half
+        if (i < 4) SPECPV_STAMP(3 + i);   // chunk i has landed
         uint4 kf[8];
         uint2 v[16];
         const uint32_t vmask = vmask_st[stg];
         if (active) {
-            if (stg) lds_read_k<kStageBytes>(kread, kf); else lds_read_k<0>(kread, kf);
-            lds_read_v(vread + stg * kStageBytes, v);
+            const uint32_t soff = (uint32_t)stg * kStageBytes;
+            const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
+            lds_read_k4(ka, kf);
+            lds_read_v(vread + soff, v);
         }
         __builtin_amdgcn_s_barrier();          // both wavefronts of the pair hold chunk i in registers
         if (i + 2 < nch) issue(i + 2);
@@ -522,6 +723,7 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
             }
     }
     __syncthreads();   // every wavefront is done with the rings: the epilogue reuses that LDS
+    SPECPV_STAMP(7);   // main loop done
 
     // ---- merge the four token groups ---------------------------------------------------
     {
@@ -540,7 +742,6 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
                 *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) = make_float4(O[j][4 * q], O[j][4 * q + 1], O[j][4 * q + 2], O[j][4 * q + 3]);
     }
     __syncthreads();
-    constexpr int RPW = 8;  // rows each wavefront finishes
     const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
     // weights of the four token groups for the rows this wavefront finishes (lane -> row)
     float wgt[4], m_row = -INFINITY, l_row = 0.f;
@@ -573,12 +774,173 @@ void attn_ctx_mfma_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
         for (int uu = 0; uu < RPW; ++uu) {
             const int j = m0 + wave * RPW + uu;
-            if (j < s.M) store_partial(part.o + (prow0 + j) * 128 + 2 * lane, acc[uu]);   // positions 2 lane, 2 lane + 1 of the stored order
+            if (j < s.M) {   // positions 2 lane, 2 lane + 1 of the stored order
+                if (FUSED) *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc[uu];   // stays in this XCD's L2
+                else store_partial(part.o + (prow0 + j) * 128 + 2 * lane, acc[uu]);
+            }
         }
     }
     if (lane < RPW) {
         const int j = m0 + wave * RPW + lane;
         if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
+    }
+    SPECPV_STAMP(8);   // partial stores issued
+    if (!FUSED) return false;
+
+    // ---- arrival; the last workgroup of the tile finishes it (FUSED) ------------------------
+    unsigned long long *word = f.arrive + ((int64_t)(b * s.Hq + h) * 2 + rt);
+    unsigned long long *sh_word = (unsigned long long *)lds_raw;   // ms / ls are dead
+    int nslots, slot_step;
+    if (!redo) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's partial stores have reached L2
+        __syncthreads();                      // ... and everybody else's
+        SPECPV_STAMP(9);   // partial stores acknowledged
+        if (threadIdx.x == 0) {
+            const unsigned xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7u;   // XCC_ID, 4 bits
+            const unsigned long long inc = (1ull << 56) | (1ull << (kXccBits * xcc));
+            const unsigned long long now = __hip_atomic_fetch_add(word, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + inc;
+            // all arrivals through this XCC's L2?
+            const bool here = ((now >> (kXccBits * xcc)) & ((1ull << kXccBits) - 1ull)) == (unsigned long long)nctx;
+            sh_word[0] = now >> 56;
+            sh_word[1] = (here && !f.force_recompute) ? 1ull : 0ull;
+        }
+        __syncthreads();
+        SPECPV_STAMP(10);  // arrival known
+        if ((int)sh_word[0] != nctx) return false;      // not the last one: done
+        if (sh_word[1] == 0ull) {
+            __syncthreads();                  // sh_word has been read by all
+            return true;                      // recompute route: everything of this tile once more, here
+        }
+        nslots = nctx + 1; slot_step = 1;
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        nslots = 2; slot_step = nctx;        // this pass's partial (slot 0) and its draft segment (slot nctx)
+    }
+    if (threadIdx.x == 0) __hip_atomic_exchange(word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // Merge.  Lane 8 u + x owns the (m, l) pairs of row u of this wavefront's 8 rows for the slots
+    // x, x + 8, ...; the weights pass through LDS (a wavefront's own corner: its LDS operations are
+    // executed in order, no barrier).  Every lane accumulates positions 2 lane, 2 lane + 1 of the
+    // stored order -- two adjacent channels -- over the slots; the rows go in two batches of four,
+    // each batch with up to 4 x 16 reads in flight, the first one requested before the weights
+    // are worked out.
+    {
+        constexpr int kMaxSlots = 80;   // 64 splits + the draft segment, rounded up to a multiple of 16
+        float *ww = (float *)(lds_raw + 2048) + (size_t)wave * (RPW * kMaxSlots);   // [8 rows][kMaxSlots]
+        const int u8 = lane >> 3, x8 = lane & 7;
+        const int jrow = m0 + wave * RPW + u8;
+        const int64_t pbase = (int64_t)(b * s.Hq + h) * part.nsplit * s.M;
+        const int64_t slot_rows = (int64_t)slot_step * s.M;     // rows between consecutive slots
+        const int jmax = s.M - 1;
+        const int chan = partial_chan(2 * lane, 128);
+        auto ml_of = [&](int sl) -> float2 {
+            float2 ml = make_float2(-INFINITY, 0.f);
+            if (sl < nslots && jrow < s.M) ml = *(const float2 *)(part.ml + (pbase + sl * slot_rows + jrow) * 2);
+            return ml;
+        };
+        // rows u0 .. u0 + 3, slots sl0 .. sl0 + 15 (those below nslots): two adjacent values per lane
+        auto fetch = [&](int u0, int sl0, float2 (&x)[4][16]) {
+#pragma unroll
+            for (int xi = 0; xi < 16; ++xi) {
+                if (sl0 + xi < nslots) {   // uniform
+#pragma unroll
+                    for (int uu = 0; uu < 4; ++uu) {
+                        const int j = min(m0 + wave * RPW + u0 + uu, jmax);   // rows past M repeat row M-1; never stored
+                        x[uu][xi] = *(const float2 *)(part.o + (pbase + (sl0 + xi) * slot_rows + j) * 128 + 2 * lane);
+                    }
+                } else {
+#pragma unroll
+                    for (int uu = 0; uu < 4; ++uu) x[uu][xi] = make_float2(0.f, 0.f);
+                }
+            }
+        };
+        auto accumulate = [&](int u0, int sl0, const float2 (&x)[4][16], float2 (&acc)[4]) {
+#pragma unroll
+            for (int uu = 0; uu < 4; ++uu) {
+                const float *wrow = ww + (u0 + uu) * kMaxSlots + sl0;
+#pragma unroll
+                for (int x4 = 0; x4 < 4; ++x4) {
+                    const float4 w4 = *(const float4 *)(wrow + 4 * x4);
+                    const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                    for (int xi = 0; xi < 4; ++xi) {
+                        acc[uu].x = fmaf(wv[xi], x[uu][4 * x4 + xi].x, acc[uu].x);
+                        acc[uu].y = fmaf(wv[xi], x[uu][4 * x4 + xi].y, acc[uu].y);
+                    }
+                }
+            }
+        };
+        const float2 ml0 = ml_of(x8), ml1 = ml_of(x8 + 8);
+        float2 xa[4][16];
+        fetch(0, 0, xa);
+        // weights of the slots and the denominator of each row
+        float m_all = fmaxf(ml0.y > 0.f ? ml0.x : -INFINITY, ml1.y > 0.f ? ml1.x : -INFINITY);
+        for (int sl = x8 + 16; sl < nslots; sl += 8) {   // more than 16 slots: rare
+            const float2 ml = ml_of(sl);
+            m_all = fmaxf(m_all, ml.y > 0.f ? ml.x : -INFINITY);
+        }
+        m_all = oct_max(m_all);
+        const float m_use = m_all == -INFINITY ? 0.f : m_all;
+        float den = 0.f;
+        {
+            const float w0 = ml0.y > 0.f ? __builtin_amdgcn_exp2f(ml0.x - m_use) : 0.f;   // 0 for a slot without a valid token
+            const float w1 = ml1.y > 0.f ? __builtin_amdgcn_exp2f(ml1.x - m_use) : 0.f;
+            den = fmaf(ml0.y, w0, fmaf(ml1.y, w1, 0.f));
+            ww[u8 * kMaxSlots + x8] = w0;
+            ww[u8 * kMaxSlots + x8 + 8] = w1;
+        }
+        const int nslots16 = (nslots + 15) & ~15;
+        for (int sl = x8 + 16; sl < nslots16; sl += 8) {
+            const float2 ml = ml_of(sl);                  // (-inf, 0) past the last slot
+            const float w = ml.y > 0.f ? __builtin_amdgcn_exp2f(ml.x - m_use) : 0.f;
+            den = fmaf(ml.y, w, den);
+            ww[u8 * kMaxSlots + sl] = w;
+        }
+        den = oct_sum(den);
+        const float inv = 1.f / den;   // den > 0: a node attends itself
+#pragma unroll 1
+        for (int u0 = 0; u0 < RPW; u0 += 4) {
+            float2 acc[4];
+#pragma unroll
+            for (int uu = 0; uu < 4; ++uu) acc[uu] = make_float2(0.f, 0.f);
+            if (u0 > 0) fetch(u0, 0, xa);
+            accumulate(u0, 0, xa, acc);
+#pragma unroll 1
+            for (int sl0 = 16; sl0 < nslots; sl0 += 16) {
+                fetch(u0, sl0, xa);
+                accumulate(u0, sl0, xa, acc);
+            }
+#pragma unroll
+            for (int uu = 0; uu < 4; ++uu) {
+                const int j = m0 + wave * RPW + u0 + uu;
+                const float iv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inv), (u0 + uu) * 8));
+                const uint32_t packed = (uint32_t)float_to_bf16_bits(acc[uu].x * iv) | ((uint32_t)float_to_bf16_bits(acc[uu].y * iv) << 16);
+                if (j < s.M)
+                    __builtin_nontemporal_store(packed, (uint32_t *)((uint16_t *)f.out + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + chan));
+            }
+        }
+        if (f.lse && x8 == 0 && jrow < s.M)
+            f.lse[((int64_t)b * s.M + jrow) * s.Hq + h] = (m_all + __builtin_amdgcn_logf(den)) * kLn2;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    SPECPV_STAMP(11);  // merged and stored (last workgroup of a tile only)
+    return false;
+}
+
+template <bool ALIGNED, bool FUSED>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, const int32_t *a_ctx_len,
+                          const void *a_q, int a_n_sel, int a_M, int a_Hq, int a_nctx,
+                          Shape s, Partials part, MfmaArgs a, FusedArgs f)
+{
+    // the leading scalar arguments repeat what the first round of reads needs: they arrive in registers
+    s.ctx_len = a_ctx_len; s.q = a_q; s.M = a_M; s.Hq = a_Hq;
+    a.sel_idx = a_sel_idx; a.sel_count = a_sel_count; a.n_sel = a_n_sel;
+    extern __shared__ char lds_raw[];
+    const int sp0 = (int)blockIdx.y - (int)a.div_nsplit.div(blockIdx.y) * a_nctx;
+    if (attn_ctx_pass<ALIGNED, FUSED, false>(s, part, a, f, a_nctx, sp0, a_nctx, lds_raw)) {
+        if (FUSED) attn_ctx_pass<ALIGNED, true, true>(s, part, a, f, a_nctx, 0, 1, lds_raw);
     }
 }
 
@@ -919,9 +1281,12 @@ static GroupLayout group_layout(const Shape &s)
 int attn_group_parts(const Shape &s) { return group_layout(s).parts; }
 
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
-                                int n_sel, Partials p, int kind, hipStream_t st)
+                                int n_sel, Partials p, int nctx, int kind, const FusedArgs &f, hipStream_t st)
 {
     if (kind != kAttnSplit && kind != kAttnGroup) return hipErrorInvalidValue;
+    const bool fused = f.out != nullptr;
+    if (fused && (kind != kAttnSplit || nctx > 64 || p.nsplit != nctx + 1)) return hipErrorInvalidValue;
+    if (!fused && p.nsplit != nctx) return hipErrorInvalidValue;
     const GroupLayout gl = group_layout(s);
     MfmaArgs a;
     a.sel_idx = sel_idx;
@@ -931,35 +1296,40 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     a.row_tiles = (s.M + 63) / 64;
     a.rph = gl.rph;
     a.n_row_blocks = gl.n_row_blocks;
-    a.n_units = s.batch * s.Hkv * p.nsplit;
+    a.n_units = s.batch * s.Hkv * nctx;
     a.n_bg = s.batch * s.Hkv;
-    a.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
+    a.div_nsplit = make_fastdiv((uint32_t)nctx);
     a.div_hkv = make_fastdiv((uint32_t)s.Hkv);
     a.div_B = make_fastdiv((uint32_t)s.B);
     // token ranges per split: four (one per token group of a workgroup), or one in the group kernel
-    a.div_W = make_fastdiv((uint32_t)p.nsplit * (kind == kAttnGroup ? 1u : 4u));
+    a.div_W = make_fastdiv((uint32_t)nctx * (kind == kAttnGroup ? 1u : 4u));
     const int GR = kind == kAttnGroup ? gl.parts : s.G * a.row_tiles;
     // group kernel: a unit (sequence, KV head, split) per 8 consecutive x; split kernel: (sequence, KV
-    // head) bg on XCD bg % 8 with all its splits and query heads (y = (bg / 8) * nsplit + split)
-    const dim3 grid(8 * GR, kind == kAttnGroup ? (a.n_units + 7) / 8 : ((a.n_bg + 7) / 8) * p.nsplit);
+    // head) bg on XCD bg % 8 with all its splits and query heads (y = (bg / 8) * nctx + split)
+    const dim3 grid(8 * GR, kind == kAttnGroup ? (a.n_units + 7) / 8 : ((a.n_bg + 7) / 8) * nctx);
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool aligned = s.B % 32 == 0;
     const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
     const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, gl.waves * 32 * kOPitch * (int)sizeof(float));
-#define SPECPV_LAUNCH(KERN, THREADS, LDS)                                                              \
-    do {                                                                                               \
+#define SPECPV_SET_LDS(KERN, LDS)                                                                      \
         static PerDeviceOnce once;   /* one per kernel instantiation */                               \
         auto kern = KERN;                                                                              \
         const hipError_t e0 = once.run([&] {                                                           \
             return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(LDS)); \
         });                                                                                            \
-        if (e0 != hipSuccess) return e0;                                                               \
-        hipLaunchKernelGGL(kern, grid, dim3(THREADS), LDS, st, s, p, a);                                \
-    } while (0)
+        if (e0 != hipSuccess) return e0
 #define SPECPV_LAUNCH_GROUP(WW)                                                                        \
     do {                                                                                               \
-        if (aligned) SPECPV_LAUNCH((attn_ctx_mfma_group_kernel<true, WW>), 64 * WW, lds_group);         \
-        else SPECPV_LAUNCH((attn_ctx_mfma_group_kernel<false, WW>), 64 * WW, lds_group);                \
+        if (aligned) { SPECPV_SET_LDS((attn_ctx_mfma_group_kernel<true, WW>), lds_group);               \
+                       hipLaunchKernelGGL(kern, grid, dim3(64 * WW), lds_group, st, s, p, a); }         \
+        else { SPECPV_SET_LDS((attn_ctx_mfma_group_kernel<false, WW>), lds_group);                      \
+               hipLaunchKernelGGL(kern, grid, dim3(64 * WW), lds_group, st, s, p, a); }                 \
+    } while (0)
+#define SPECPV_LAUNCH_SPLIT(AL, FU)                                                                    \
+    do {                                                                                               \
+        SPECPV_SET_LDS((attn_ctx_mfma_kernel<AL, FU>), lds_split);                                      \
+        hipLaunchKernelGGL(kern, grid, dim3(512), lds_split, st, sel_idx, sel_count, s.ctx_len, s.q,    \
+                           n_sel, s.M, s.Hq, nctx, s, p, a, f);                                         \
     } while (0)
     if (kind == kAttnGroup) {
         switch (gl.waves) {
@@ -968,12 +1338,14 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
         case 6: SPECPV_LAUNCH_GROUP(6); break;
         default: SPECPV_LAUNCH_GROUP(8); break;
         }
+    } else if (fused) {
+        if (aligned) SPECPV_LAUNCH_SPLIT(true, true); else SPECPV_LAUNCH_SPLIT(false, true);
     } else {
-        if (aligned) SPECPV_LAUNCH(attn_ctx_mfma_kernel<true>, 512, lds_split);
-        else SPECPV_LAUNCH(attn_ctx_mfma_kernel<false>, 512, lds_split);
+        if (aligned) SPECPV_LAUNCH_SPLIT(true, false); else SPECPV_LAUNCH_SPLIT(false, false);
     }
+#undef SPECPV_LAUNCH_SPLIT
 #undef SPECPV_LAUNCH_GROUP
-#undef SPECPV_LAUNCH
+#undef SPECPV_SET_LDS
     return hipGetLastError();
 }
 

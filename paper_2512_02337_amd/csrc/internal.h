@@ -140,8 +140,20 @@ struct AttnPlan {
     int nsplit;
     int kind;
 };
+// The whole call in the eight-wavefront kernel (kAttnSplit only): the draft-tree segment as one more
+// partial (slot nctx of nctx + 1), arrival words, the last workgroup of a tile merges and stores.
+// out == nullptr: the kernel only writes partials and launch_combine finishes.
+struct FusedArgs {
+    void *out;                     // [batch, M, Hq, 128] bf16
+    float *lse;                    // optional [batch, M, Hq]
+    unsigned long long *arrive;    // [batch, Hq, 2] arrival words, zero between calls
+    int force_recompute;           // test hook: the last workgroup of a tile takes the recompute route
+    unsigned long long *timeline;  // builds with -DSPECPV_TIMELINE: 16 time stamps per workgroup (else unused)
+};
+constexpr size_t kArriveBytes = 64 << 10;   // head of every workspace: 8192 arrival words
+// p.nsplit: slots per (sequence, head) in the partial arrays = nctx, or nctx + 1 when fused
 hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const int32_t *sel_count,
-                                int n_sel, Partials p, int kind, hipStream_t st);
+                                int n_sel, Partials p, int nctx, int kind, const FusedArgs &f, hipStream_t st);
 // workgroups per (sequence, KV head, split) of the kAttnGroup kernel
 int attn_group_parts(const Shape &s);
 hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st);

@@ -41,7 +41,7 @@ class GpuRun:
         self.lse = torch.zeros(case["q"].shape[:3], dtype=torch.float32, device=dev)
         nbytes = specpv.specpv_workspace_bytes(self.kv, self.tree, self.cfg)
         assert nbytes > 0
-        self.ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+        self.ws = torch.zeros((nbytes,), dtype=torch.uint8, device=dev)
 
     def summarize(self, lo=0, hi=-1):
         self.sp.specpv_block_summarize(self.kv, lo, hi, self.kmax, self.kmin)

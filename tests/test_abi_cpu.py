@@ -142,7 +142,7 @@ def test_mode_policy_and_extended_parents_on_the_host():
     vp = ctypes.c_void_p
     B = ctypes.byref
     ok_args = (vp(0x100), vp(0x200), 28, 60, vp(0x300), vp(0x400), vp(0x500), 8, 1, None, None, None, None,
-               vp(0x8000), 4096, None)
+               vp(0x8000), 1 << 17, None)
     assert lib.specpv_commit_accepted(None, *ok_args) == -1
     a = list(ok_args); a[0] = None
     assert lib.specpv_commit_accepted(B(_kv()), *a) == -1
@@ -189,9 +189,9 @@ def test_commit_of_all_layers_validates_on_the_host():
 
 def test_workspace_size_is_a_consistent_split_plan():
     """specpv_workspace_bytes is host-only and deterministic.  Its value is the layout the calls use:
-    partial O [batch, Hq, splits, M, D] fp32 + (m, l) pairs [batch, Hq, splits, M, 2] fp32 + one score
-    per block, each part rounded up to 256 bytes, for ONE split count between 1 and 64; and a
-    selection can only add to what the full pass needs."""
+    64 KiB of arrival words + partial O [batch, Hq, splits + 1, M, D] fp32 + (m, l) pairs
+    [batch, Hq, splits + 1, M, 2] fp32 + one score per block, each part rounded up to 256 bytes, for ONE
+    split count between 1 and 64; and a selection can only add to what the full pass needs."""
     import random
     lib = specpv.load()
     up = lambda x: (x + 255) & ~255
@@ -199,8 +199,8 @@ def test_workspace_size_is_a_consistent_split_plan():
 
     def splits_of(total, batch, Hq, Hkv, M, D, nb):
         sc = up(batch * Hkv * nb * 4)
-        for ns in range(1, 65):
-            if up(batch * Hq * ns * M * D * 4) + up(batch * Hq * ns * M * 8) + sc == total:
+        for ns in range(1, 65):   # ns context splits + one slot for the draft-tree segment, behind 64 KiB of arrival words
+            if 65536 + up(batch * Hq * (ns + 1) * M * D * 4) + up(batch * Hq * (ns + 1) * M * 8) + sc == total:
                 return ns
         return None
 
@@ -225,7 +225,7 @@ def test_workspace_size_is_a_consistent_split_plan():
         assert both >= full
         assert splits_of(both, batch, Hkv * G, Hkv, M, D, nb) is not None
     # no tree: only the per-sequence counters of the summary call
-    assert lib.specpv_workspace_bytes(ctypes.byref(_kv()), None, None) >= 256
+    assert lib.specpv_workspace_bytes(ctypes.byref(_kv()), None, None) >= 65536 + 4
 
 
 def test_two_threads_may_call_at_once():

@@ -177,7 +177,7 @@ def test_list_rows_that_are_too_short_are_reported(gpu_lib):
     sel_idx = big[:, :Hkv]
     sel_count = torch.from_numpy(cnts[None].copy()).to(dev)
     dropped = torch.zeros((1, 2), dtype=torch.int32, device=dev)
-    ws = torch.zeros((256,), dtype=torch.uint8, device=dev)
+    ws = torch.zeros((sp.specpv_workspace_bytes(kv),), dtype=torch.uint8, device=dev)
     sp.specpv_commit_accepted(kv, buf_k, buf_v, P, M, n_pending, acc, n_acc, sp.MODE_REFRESH, None, None, ws,
                               sel_idx=sel_idx, sel_count=sel_count, dropped=dropped)
     torch.cuda.synchronize()
@@ -217,7 +217,7 @@ def test_gathered_partial_cache(gpu_lib, name, seed):
     kv2 = sp.KV(gk, gv, glen, B, n_sel)
     out2 = torch.zeros_like(run.out)
     lse2 = torch.zeros_like(run.lse)
-    ws2 = torch.empty((sp.specpv_workspace_bytes(kv2, run.tree, run.cfg),), dtype=torch.uint8, device=dev)
+    ws2 = torch.zeros((sp.specpv_workspace_bytes(kv2, run.tree, run.cfg),), dtype=torch.uint8, device=dev)
     sp.specpv_partial_verify_attn(kv2, run.tree, None, None, out2, lse2, ws2)
     torch.cuda.synchronize()
     d = np.abs(_f64(out2[0]) - _f64(run.out[0])).max()
@@ -249,7 +249,7 @@ def test_commit_of_all_layers_at_once(gpu_lib, mode_name):
     accepted = torch.tensor([[0, 2, 5, 9], [1, 3, 0, 0]], dtype=torch.int32, device=dev)
     n_acc = torch.tensor([4, 2], dtype=torch.int32, device=dev)
     max_blocks = T // B
-    ws = torch.empty((256,), dtype=torch.uint8, device=dev)
+    ws = torch.zeros((1 << 17,), dtype=torch.uint8, device=dev)
     # kept-block lists per layer: [0, l % 3 + 1, the block in front of the last one], five free entries
     lists0 = []
     for l in range(n_layers):

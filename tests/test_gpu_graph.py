@@ -112,7 +112,7 @@ def test_commit_graph_replays_match_eager(gpu_lib):
     a, b = state(), state()
     accepted = torch.zeros((batch, 4), dtype=torch.int32, device=dev)
     n_accepted = torch.zeros((batch,), dtype=torch.int32, device=dev)
-    ws = torch.empty((4096,), dtype=torch.uint8, device=dev)
+    ws = torch.zeros((1 << 17,), dtype=torch.uint8, device=dev)
 
     def commit(st):
         sp.specpv_commit_accepted_layers(st["kv"], st["bk"], st["bv"], P, M, st["n_pending"], accepted, n_accepted,

@@ -74,7 +74,7 @@ def test_offloaded_refresh_and_partial_steps_match_the_resident_path(gpu_lib):
         n_sel = run.cfg.n_sel
         gkv = gpu_lib.KV(gk, gv, glen, CFG["B"], n_sel)
         out = torch.zeros_like(run.out)
-        ws = torch.empty((gpu_lib.specpv_workspace_bytes(gkv, run.tree, run.cfg),), dtype=torch.uint8, device=gk.device)
+        ws = torch.zeros((gpu_lib.specpv_workspace_bytes(gkv, run.tree, run.cfg),), dtype=torch.uint8, device=gk.device)
         gpu_lib.specpv_partial_verify_attn(gkv, run.tree, None, None, out, None, ws)   # the whole segment, no list
         torch.cuda.synchronize()
         err = (out.float() - ref[l][3].float()).abs().max().item()

@@ -159,10 +159,12 @@ def test_few_splits_on_the_vector_alu_path(gpu_lib, dtype, D, M, ctx, splits):
     cfg.update(dtype=dtype, D=D, M=M, ctx=ctx, rho=[0.1] * len(ctx), tree="uniform")
     case = workloads.to_device(workloads.make_case(cfg, seed=23), "cuda")
     run = GpuRun(gpu_lib, case)
-    # the workspace is sized by the split count: partial O + (m, l) pairs + scores, each rounded up to 256 bytes
+    # the workspace is sized by the split count: 64 KiB of arrival words + partial O + (m, l) pairs (one slot
+    # more than splits) + scores, each rounded up to 256 bytes
     up = lambda x: (x + 255) & ~255
     rows = case["batch"] * case["Hq"] * M
-    want = up(rows * splits * D * 4) + up(rows * splits * 8) + up(case["batch"] * case["Hkv"] * case["max_blocks"] * 4)
+    want = 65536 + up(rows * (splits + 1) * D * 4) + up(rows * (splits + 1) * 8) + \
+        up(case["batch"] * case["Hkv"] * case["max_blocks"] * 4)
     assert run.ws.numel() == want, "the planner no longer gives %d splits here" % splits
     run.refresh(stale=0)
     torch.cuda.synchronize()
