@@ -23,9 +23,16 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per specpv_partial_verify_attn call at the default workload, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE scaled by a plain device copy (profiles/pmc_traffic_llama8b_128k.md); not measurable live.
-MEASURED_TRAFFIC_BYTES = {"llama8b_128k": (10223 + 4928) * 2 * 1024 + (7800 + 480) * 1024}   # KiB readings, FETCH x 2.0
+# RECORDED, not live: HBM bytes per specpv_partial_verify_attn call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (KiB per dispatch, FETCH scaled by 2.0 as a plain device copy calibrates it), and the per-kernel durations of a
+# rocprofv3 --kernel-trace --stats run, as committed under profiles/.  They describe the launch plan named here
+# (kernels and split count); the line carries them only while the library still plans the call that way.
+RECORDED = {"llama8b_128k": {
+    "plan": {"kernels": ["attn_ctx_mfma_kernel", "combine_kernel"], "splits": 8},
+    "traffic_bytes": (10216 + 4928) * 2 * 1024 + (7800 + 480) * 1024,
+    "traffic_source": "profiles/pmc_traffic_llama8b_128k.md",
+    "kernels": [{"name": "attn_ctx_mfma_kernel", "us": 14.1}, {"name": "combine_kernel", "us": 4.6}],
+    "kernels_source": "profiles/kernel_durations_llama8b_128k.md"}}
 
 
 def parse():
@@ -41,6 +48,8 @@ def parse():
     ap.add_argument("--no-offload", action="store_true", help="skip the host-offload leg of the extras (2 GiB of pinned memory)")
     ap.add_argument("--no-batch", action="store_true", help="skip the 16-sequence leg of the extras (4 GiB of K / V)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--settle", type=float, default=0.3,
+                    help="seconds of untimed replays during set-up, before the W warm-up steps, to bring the box to its working clocks")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run 4 plain device copies of 256 MiB (read 256 MiB + write 256 MiB each) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -116,7 +125,7 @@ def main():
             specpv.specpv_full_verify_refresh(l["kv"], l["tree"], l["kmax"], l["kmin"], -1, l["cfg"], l["out_full"],
                                               None, l["sel_idx"], l["sel_count"], None, ws)
 
-    def timed(fn, steps, warmup, graph):
+    def timed(fn, steps, warmup, graph, per_step=None, settle_s=0.0):
         """ms per step over `steps` steps, after `warmup` untimed ones, with HIP events on
         the stream the library launches on."""
         stream = torch.cuda.Stream()
@@ -130,6 +139,15 @@ def main():
                 with torch.cuda.graph(g, stream=stream):
                     fn()
                 run = g.replay
+            if settle_s > 0:
+                # part of the set-up, not of the W warm-up steps: a fresh box needs a few hundred milliseconds of
+                # load before its clocks and the graph's first replays have settled (20 steps right after 5
+                # warm-up steps otherwise read about 4 % slower than every later step)
+                t_end = time.time() + settle_s
+                while time.time() < t_end:
+                    for _ in range(20):
+                        run()
+                    stream.synchronize()
             for _ in range(warmup):
                 run()
             stream.synchronize()
@@ -140,7 +158,19 @@ def main():
                 run()
             e1.record(stream)
             torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / steps
+            ms = e0.elapsed_time(e1) / steps
+            if per_step is not None:
+                # a second pass with an event between the steps: median and minimum of single steps
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(per_step + 1)]
+                ev[0].record(stream)
+                for i in range(per_step):
+                    run()
+                    ev[i + 1].record(stream)
+                torch.cuda.synchronize()
+                each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(per_step))
+                timed.last_per_step = {"n": per_step, "median_us": round(each[len(each) // 2] * 1e3, 2),
+                                       "min_us": round(each[0] * 1e3, 2), "max_us": round(each[-1] * 1e3, 2)}
+            return ms
 
     if args.copy_calib:
         src = torch.empty((256 << 20,), dtype=torch.uint8, device=dev).random_(0, 255)
@@ -151,7 +181,8 @@ def main():
         del src, dst
 
     use_graph = not args.no_graph
-    ms = timed(partial_step, args.steps, args.warmup, use_graph)
+    ms = timed(partial_step, args.steps, args.warmup, use_graph, per_step=max(100, args.steps), settle_s=args.settle)
+    per_step_stats = timed.last_per_step
     us_step = ms * 1e3
     bytes_layer, kv_bytes_layer = algorithmic_bytes_per_layer(layers[0]["case"])
     us_layer = us_step / n_layers
@@ -277,6 +308,56 @@ def main():
             extras["batch16_32k_partial_us_per_call"] = round(bus, 2)
             extras["batch16_32k_partial_GBs"] = round(bbytes / (bus * 1e-6) / 1e9, 1)
             del bsets
+        # Section 3.2's buffer on a partial step: 16 partially verified tokens wait in front of the 60
+        # candidates.  They are keys only (no query rows), so the step costs what it costs without them
+        # plus 16 more draft K / V rows in the tree segment.
+        if args.workload == "llama8b_128k":
+            import numpy as np
+            n_pend = 16
+            pl = []
+            for l in layers:
+                c = l["case"]
+                g = torch.Generator(device=dev).manual_seed(1234)
+                pk = torch.randn((c["batch"], n_pend, c["Hkv"], c["D"]), generator=g, device=dev).to(c["q"].dtype)
+                pv = torch.randn((c["batch"], n_pend, c["Hkv"], c["D"]), generator=g, device=dev).to(c["q"].dtype)
+                par = specpv.specpv_extend_parents(c["parent"][0].tolist(), n_pend)
+                ptree = specpv.Tree(c["q"], torch.cat([pk, c["kd"]], 1).contiguous(), torch.cat([pv, c["vd"]], 1).contiguous(),
+                                    torch.tensor([par] * c["batch"], dtype=torch.int32, device=dev))
+                pl.append(ptree)
+
+            pout = torch.empty_like(layers[0]["out"])
+
+            def pending_step():
+                for l, ptree in zip(layers, pl):
+                    specpv.specpv_partial_verify_attn(l["kv"], ptree, l["sel_idx"], l["sel_count"], pout, None, ws)
+            extras["partial_16_pending_us_per_step"] = round(timed(pending_step, k2, 3, use_graph) * 1e3, 2)
+            del pl
+        # the Qwen3-14B-shaped ragged batch (40 / 8 heads, G = 5, contexts 32K + 64K + 96K + 128K): one layer's
+        # partial step and one layer's full verification + refresh, per call
+        if args.workload == "llama8b_128k" and not args.no_batch:
+            rc = workloads.make_case("qwen14b_batch4", seed=args.seed, device=dev)
+            rkv = specpv.KV(rc["k"], rc["v"], rc["ctx_len"], rc["B"], rc["max_blocks"])
+            rtree = specpv.Tree(rc["q"], rc["kd"], rc["vd"], rc["parent"])
+            rcfg = specpv.SelectCfg(rc["ns"], rc["nr"], rc["k_blocks"], "mean")
+            rkmax = torch.empty(rkv.summary_shape(), dtype=rc["q"].dtype, device=dev)
+            rkmin = torch.empty_like(rkmax)
+            rsel = torch.empty((rc["batch"], rc["Hkv"], rcfg.n_sel), dtype=torch.int32, device=dev)
+            rcnt = torch.empty((rc["batch"], rc["Hkv"]), dtype=torch.int32, device=dev)
+            rout = torch.empty_like(rc["q"])
+            rws = torch.zeros((specpv.specpv_workspace_bytes(rkv, rtree, rcfg),), dtype=torch.uint8, device=dev)
+            specpv.specpv_full_verify_refresh(rkv, rtree, rkmax, rkmin, 0, rcfg, rout, None, rsel, rcnt, None, rws)
+            rp = timed(lambda: specpv.specpv_partial_verify_attn(rkv, rtree, rsel, rcnt, rout, None, rws), k2, 3, use_graph) * 1e3
+            rf2 = timed(lambda: specpv.specpv_full_verify_refresh(rkv, rtree, rkmax, rkmin, -1, rcfg, rout, None, rsel, rcnt,
+                                                                   None, rws), max(3, k2 // 4), 1, use_graph) * 1e3
+            rs = timed(lambda: specpv.specpv_select_blocks(rkv, rtree, rkmax, rkmin, rcfg, rsel, rcnt, None, rws), k2, 3, use_graph) * 1e3
+            rbytes, _ = algorithmic_bytes_per_layer(rc)
+            rfull = sum(int(x) for x in rc["ctx_len"]) * rc["Hkv"] * rc["D"] * 2 * 2
+            extras["qwen14b_batch4_partial_us_per_call"] = round(rp, 2)
+            extras["qwen14b_batch4_partial_GBs"] = round(rbytes / (rp * 1e-6) / 1e9, 1)
+            extras["qwen14b_batch4_full_refresh_us_per_call"] = round(rf2, 2)
+            extras["qwen14b_batch4_full_refresh_kv_GBs"] = round(rfull / (rf2 * 1e-6) / 1e9, 1)
+            extras["qwen14b_batch4_select_us_per_call"] = round(rs, 2)
+            del rc, rkv, rtree, rkmax, rkmin, rws
         # what this machine's HBM delivers to plain streaming kernels, next to the published peak: a device
         # copy of 1 GiB (read + write bytes), and the library's own read-only stream (eq. 1 over one
         # layer's K, rotating over the layers so that the 256 MB last-level cache cannot serve it)
@@ -298,6 +379,19 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(layers)
 
+    # the recorded counter / trace figures only describe the launch plan they were taken with: 8 context splits
+    # (read off the workspace size: 64 KiB of arrival words + (splits + 1) x (partial O + (m, l) pairs) + scores)
+    rec = RECORDED.get(args.workload) if n_layers == cfg["layers"] else None
+    if rec is not None:
+        c0 = layers[0]["case"]
+        up = lambda x: (x + 255) & ~255
+        rows = c0["batch"] * c0["Hq"] * c0["M"]
+        part_only = specpv.specpv_workspace_bytes(specpv.KV(c0["k"][:, :, :c0["n_sel"] * c0["B"]], c0["v"][:, :, :c0["n_sel"] * c0["B"]],
+                                                            c0["ctx_len"], c0["B"], c0["n_sel"]), layers[0]["tree"])
+        if part_only != 65536 + up(rows * (rec["plan"]["splits"] + 1) * c0["D"] * 4) + up(rows * (rec["plan"]["splits"] + 1) * 8) + \
+                up(c0["batch"] * c0["Hkv"] * c0["n_sel"] * 4):
+            rec = None   # the planner has moved on: the recorded figures no longer describe this build
+
     line = {
         "metric": "partial_verify_attention_us_per_step",
         "value": round(us_step, 2),
@@ -314,13 +408,17 @@ def main():
         "config": {"workload": args.workload, "layers": n_layers, "context": [int(x) for x in layers[0]["case"]["ctx_len"]],
                    "block": layers[0]["case"]["B"], "kept_blocks": layers[0]["case"]["n_sel"], "tree_nodes": layers[0]["case"]["M"],
                    "q_heads": layers[0]["case"]["Hq"], "kv_heads": layers[0]["case"]["Hkv"], "head_dim": layers[0]["case"]["D"],
-                   "launch": "hip_graph" if use_graph else "eager"},
+                   "launch": "hip_graph" if use_graph else "eager", "settle_s_before_warmup": args.settle},
         "achieved_hbm_GBs": round(achieved, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if n_layers == cfg["layers"] else None,
+                     "traffic": rec["traffic_bytes"] if rec else None,
+                     "traffic_is": "recorded (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, %s), not measured by this run" % rec["traffic_source"] if rec else None,
                      "kernel": "context attention (attn_ctx_mfma_kernel at the default workload; the planner picks by shape) + combine_kernel = one specpv_partial_verify_attn call (one layer)",
+                     "kernels": [dict(k, frac=round(bytes_layer / (k["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                      source="recorded: " + rec["kernels_source"]) for k in rec["kernels"]] if rec else None,
                      "algorithmic_bytes_per_launch": bytes_layer, "us_per_launch": round(us_layer, 3),
+                     "us_per_step_single_replays": per_step_stats,
                      "box_copy_GBs": extras.get("hbm_copy_ceiling_GBs"), "box_read_stream_GBs": extras.get("hbm_read_stream_GBs")},
         "cpu_baseline": cpu,
         "extras": extras,
@@ -329,11 +427,15 @@ def main():
 
 
 def cpu_baseline(layers):
-    """The fp64 oracle, as it stands, on the host's cores: the attention-only partial step over
-    every layer of the same workload (one whole step, about ten seconds of CPU work)."""
+    """The fp64 oracle, as it stands (built -O3 -march=native for this leg, same source, no fast-math), on the
+    host's cores: the attention-only partial step over every layer of the same workload (one whole step,
+    about ten seconds of CPU work), then the full verification of ONE layer at the full context (a bounded
+    sample: the whole step would be 32 times that), and the CPU's full / partial ratio per layer -- the
+    paper's premise that verification cost follows the attended tokens (Section 3.2, Figure 1)."""
     import numpy as np
     import torch
     import oracle
+    oracle.use_native_build()
     total, err0 = 0.0, None
     for li, layer in enumerate(layers):
         case = layer["case"]
@@ -354,9 +456,27 @@ def cpu_baseline(layers):
         total += time.time() - t0
         if li == 0:
             err0 = float(np.abs(layer["out"][0].float().cpu().numpy() - O).max())
+    # full verification of layer 0 over the whole context
+    case = layers[0]["case"]
+    L = int(case["ctx_len"][0])
+    K = case["k"][0, :, :L].permute(1, 0, 2).contiguous().cpu()
+    V = case["v"][0, :, :L].permute(1, 0, 2).contiguous().cpu()
+    t0 = time.time()
+    Of, _, _ = oracle.tree_attention(case["q"][0].cpu(), K, V, case["kd"][0].cpu(), case["vd"][0].cpu(),
+                                     case["parent"][0].cpu().numpy(), case["B"])
+    full_s = time.time() - t0
+    errf = float(np.abs(layers[0]["out_full"][0].float().cpu().numpy() - Of).max())
+    partial_layer_s = total / len(layers)
     return {"value": round(total * 1e6, 1), "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "one whole step: partial-verify attention of all %d layers, fp64, %.2f s" % (len(layers), total),
-            "gpu_vs_oracle_max_abs_err_layer0": round(err0, 6)}
+            "sample": "one whole step: partial-verify attention of all %d layers, fp64, %.2f s; full verification: one "
+                      "layer at %d tokens, %.2f s" % (len(layers), total, L, full_s),
+            "build": "gcc -O3 -march=native -fopenmp (the parity tests use -O2 generic; same source)",
+            "full_verification_us_per_layer": round(full_s * 1e6, 1),
+            "partial_verification_us_per_layer": round(partial_layer_s * 1e6, 1),
+            "full_over_partial": round(full_s / partial_layer_s, 2),
+            "attended_tokens_full_over_partial": round((L + case["M"]) / (case["n_sel"] * case["B"] + case["M"]), 2),
+            "gpu_vs_oracle_max_abs_err_layer0": round(err0, 6),
+            "gpu_vs_oracle_max_abs_err_full_layer0": round(errf, 6)}
 
 
 if __name__ == "__main__":

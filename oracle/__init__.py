@@ -23,16 +23,30 @@ REDUCE_MEAN, REDUCE_MAX, REDUCE_LAST = 0, 1, 2
 _REDUCE = {"mean": 0, "max": 1, "last": 2, 0: 0, 1: 1, 2: 2}
 
 
+_FLAGS = ["-O2"]   # generic x86-64, no -ffast-math: the build the parity tests and the pins use
+
+
 def build(force=False):
     """Compile specpv_oracle.c with gcc (no -ffast-math, generic x86-64)."""
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB
     tmp = _LIB + ".tmp%d" % os.getpid()
-    subprocess.run(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall",
+    subprocess.run(["gcc"] + _FLAGS + ["-fopenmp", "-shared", "-fPIC", "-Wall",
                     "-o", tmp, _SRC, "-lm"], check=True)
     os.replace(tmp, _LIB)
     return _LIB
+
+
+def use_native_build():
+    """Switch this process to a second build of the same source with -O3 -march=native (still no
+    -ffast-math: the arithmetic and its order are unchanged), for timing the oracle as a CPU
+    baseline on the machine at hand.  The tests keep the generic build."""
+    global _LIB, _FLAGS, _lib
+    _LIB = os.path.join(_HERE, "libspecpv_oracle_native.so")
+    _FLAGS = ["-O3", "-march=native"]
+    _lib = None
+    build(force=True)   # -march=native must match the machine that runs it
 
 
 _lib = None
