@@ -93,7 +93,10 @@ template <int CPL> __device__ __forceinline__ void load_partial(const float *p, 
 // the registers, and with them the resident wavefronts of a batch, in proportion).
 // MULTI: more splits than NP (the many splits of a full verification): rounds of NP, each round's
 // reads requested before the previous round is merged.  Without it the split count is at most NP.
-template <typename T, int D, int NP, bool MULTI>
+// NB: path nodes whose draft K / V rows are requested in the first go: 8 (a tree of candidates alone), or 24
+// when partially verified tokens stand in front of the tree as keys (every candidate's path then starts with
+// that whole chain; more registers, so only then).
+template <typename T, int D, int NP, bool MULTI, int NB>
 __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
                                                     const float *a_pml, int a_M, int a_Hq, int a_G, int a_nsplit,
                                                     Shape s, Partials part, void *out, float *lse, float scale_log2)
@@ -157,10 +160,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
         else if (anc_hi) { a = 64 + __builtin_ctzll(anc_hi); anc_hi &= anc_hi - 1; }
         return a;
     };
-    int a8[8];
-    Raw kd8[8], vd8[8];
+    int a8[NB];
+    Raw kd8[NB], vd8[NB];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < NB; ++u) {
         a8[u] = pop();
         const int64_t drow = (((int64_t)b * s.Mk + max(a8[u], 0)) * s.Hkv + g) * D;
         Chan<T, CPL>::load(s.kd, drow + d0, kd8[u]);
@@ -244,18 +247,19 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
         m = m_new;
     };
     four(a8, kd8, vd8);
-    if (a8[4] >= 0) four(a8 + 4, kd8 + 4, vd8 + 4);
-    while (anc_lo | anc_hi) {   // paths longer than 8 nodes
-        int a[4];
-        Raw kdv[4], vdv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            a[u] = pop();
-            const int64_t drow = (((int64_t)b * s.Mk + max(a[u], 0)) * s.Hkv + g) * D;
-            Chan<T, CPL>::load(s.kd, drow + d0, kdv[u]);
-            Chan<T, CPL>::load(s.vd, drow + d0, vdv[u]);
+    for (int u = 4; u < NB; u += 4)
+        if (a8[u] >= 0) four(a8 + u, kd8 + u, vd8 + u);
+    while (anc_lo | anc_hi) {   // paths longer than 8 nodes (partially verified tokens in front of the tree): 8 per trip
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            a8[u] = pop();
+            const int64_t drow = (((int64_t)b * s.Mk + max(a8[u], 0)) * s.Hkv + g) * D;
+            Chan<T, CPL>::load(s.kd, drow + d0, kd8[u]);
+            Chan<T, CPL>::load(s.vd, drow + d0, vd8[u]);
         }
-        four(a, kdv, vdv);
+        four(a8, kd8, vd8);
+        if (a8[4] >= 0) four(a8 + 4, kd8 + 4, vd8 + 4);
     }
 
     // ---- merge the two and store ---------------------------------------------------------
@@ -277,8 +281,15 @@ static void launch_combine_t(const Shape &s, Partials p, void *out, float *lse, 
 {
     dim3 grid(8, s.M, (s.batch * s.Hkv + 7) / 8), block(64 * ((s.G + 3) / 4));
     const float scale_log2 = kLog2e / sqrtf((float)s.D);
-#define SPECPV_LAUNCH_NP(NP, MULTI) \
-    hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
+#define SPECPV_LAUNCH_NP(NP, MULTI)                                                                                          \
+    do {                                                                                                                    \
+        if (s.koff > 0)                                                                                                     \
+            hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI, 24>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, \
+                               (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2);                  \
+        else                                                                                                                \
+            hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI, 8>), grid, block, 0, st, s.parent, s.q, (const float *)p.o,  \
+                               (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2);                  \
+    } while (0)
     if (p.nsplit <= 2) SPECPV_LAUNCH_NP(2, false);
     else if (p.nsplit <= 4) SPECPV_LAUNCH_NP(4, false);
     else if (p.nsplit <= 8) SPECPV_LAUNCH_NP(8, false);
