@@ -785,7 +785,26 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
     }
     SPECPV_STAMP(8);   // partial stores issued
-    if (!FUSED) return false;
+    if (!FUSED) {
+        // The combine kernel that follows reads the tree's parents and, one trip later, its K / V rows: nobody
+        // has touched those in this call yet.  Ask for them here, on the way out (nothing waits for the data):
+        // they are then in this XCD's L2, where that kernel's workgroups of the same KV head run.
+        if (wave == 0 && s.kd && s.vd && s.parent) {
+            const int nw = s.G * nctx, w = hh * nctx + sp;
+            const char *base = (lane & 16) ? (const char *)s.vd : (const char *)s.kd;
+            for (int node = w; node < s.Mk; node += nw) {
+                uint32_t tmp;
+                const char *p = base + (((int64_t)b * s.Mk + node) * s.Hkv + g) * 256 + (lane & 15) * 16;
+                if (lane < 32) asm volatile("global_load_dword %0, %1, off" : "=v"(tmp) : "v"(p) : "memory");
+            }
+            if (w == 0 && lane < 2) {
+                uint32_t tmp;
+                const char *p = (const char *)(s.parent + (int64_t)b * s.Mk) + lane * 256;
+                if (lane * 64 < s.Mk) asm volatile("global_load_dword %0, %1, off" : "=v"(tmp) : "v"(p) : "memory");
+            }
+        }
+        return false;
+    }
 
     // ---- arrival; the last workgroup of the tile finishes it (FUSED) ------------------------
     unsigned long long *word = f.arrive + ((int64_t)(b * s.Hq + h) * 2 + rt);
