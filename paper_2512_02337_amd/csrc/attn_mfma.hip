@@ -196,6 +196,13 @@ __device__ __forceinline__ void lds_read_v(uint32_t addr, uint2 (&v)[16])
 // other CUs (and mostly other XCDs): stored with the streaming hint they do not linger in this
 // XCD's L2 as dirty lines that the end of the kernel has to write back (measured: 3.6 % of the
 // partial-verify step).
+// Two values of a split's normalised result as fp16 (clamped to fp16's range), one streaming 4-byte store.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_partial_half(float *row, int lane, float a, float b)
+{
+    const f16x2 hv = {(_Float16)__builtin_amdgcn_fmed3f(a, -65504.f, 65504.f), (_Float16)__builtin_amdgcn_fmed3f(b, -65504.f, 65504.f)};
+    __builtin_nontemporal_store(__builtin_bit_cast(uint32_t, hv), (uint32_t *)row + lane);
+}
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void store_partial(float *p, float2 v)
 {
@@ -758,6 +765,10 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         }
     }
     {
+        // fp32 partials (single-kernel route): positions 2 lane, 2 lane + 1 of the stored order; fp16 partials:
+        // channels 2 lane, 2 lane + 1, normalised by the row's l
+        const int chan0 = FUSED ? partial_chan(2 * lane, 128) : 2 * lane;
+        const float il = l_row > 0.f ? 1.f / l_row : 0.f;
         float2 acc[RPW];
 #pragma unroll
         for (int uu = 0; uu < RPW; ++uu) {
@@ -766,7 +777,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const float ww = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt[w]), uu));   // uniform: no LDS shuffle
-                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + partial_chan(2 * lane, 128));
+                const float2 x = *(const float2 *)(obuf + ((size_t)w * 64 + row) * kOPitch + chan0);
                 acc[uu].x = fmaf(ww, x.x, acc[uu].x);
                 acc[uu].y = fmaf(ww, x.y, acc[uu].y);
             }
@@ -774,9 +785,13 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
 #pragma unroll
         for (int uu = 0; uu < RPW; ++uu) {
             const int j = m0 + wave * RPW + uu;
-            if (j < s.M) {   // positions 2 lane, 2 lane + 1 of the stored order
-                if (FUSED) *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc[uu];   // stays in this XCD's L2
-                else store_partial(part.o + (prow0 + j) * 128 + 2 * lane, acc[uu]);
+            if (j < s.M) {
+                if (FUSED) {
+                    *(float2 *)(part.o + (prow0 + j) * 128 + 2 * lane) = acc[uu];   // stays in this XCD's L2
+                } else {
+                    const float ilu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(il), uu));
+                    store_partial_half(part.o + (prow0 + j) * 64, lane, acc[uu].x * ilu, acc[uu].y * ilu);   // 128 halves per row
+                }
             }
         }
     }
@@ -1266,12 +1281,15 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             for (int q = 0; q < 4; ++q)
                 *(float4 *)(dst + 32 * j + 8 * q + 4 * kg) = make_float4(O[j][4 * q], O[j][4 * q + 1], O[j][4 * q + 2], O[j][4 * q + 3]);
     }
-    // a wavefront reads back only what it wrote itself: no barrier
+    // a wavefront reads back only what it wrote itself: no barrier.  fp16 partials: channels 2 lane, 2 lane + 1
+    // of the row's normalised result (lane uu < 32 holds row uu's l)
     const int jrow0 = m0;
+    const float il = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll 8
     for (int uu = 0; uu < 32; ++uu) {
-        const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + partial_chan(2 * lane, 128));
-        if (jrow0 + uu < s.M) store_partial(part.o + (prow0 + jrow0 + uu) * 128 + 2 * lane, x);   // positions 2 lane, 2 lane + 1 of the stored order
+        const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
+        const float ilu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(il), uu));
+        if (jrow0 + uu < s.M) store_partial_half(part.o + (prow0 + jrow0 + uu) * 64, lane, x.x * ilu, x.y * ilu);
     }
     if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
 }

@@ -89,6 +89,19 @@ template <int CPL> __device__ __forceinline__ void load_partial(const float *p, 
     }
 }
 
+// The same for the fp16 form of the partials: the lane's CPL channels (adjacent, in order) of a row of D
+// halves whose first element has index i.
+template <int CPL> __device__ __forceinline__ void load_partial_half(const float *p, int64_t i, int lane16, float *f)
+{
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+    const f16x4 *src = (const f16x4 *)((const _Float16 *)p + i + lane16 * CPL);
+#pragma unroll
+    for (int x = 0; x < CPL / 4; ++x) {
+        const f16x4 v = __builtin_nontemporal_load(src + x);
+        f[4 * x] = (float)v[0]; f[4 * x + 1] = (float)v[1]; f[4 * x + 2] = (float)v[2]; f[4 * x + 3] = (float)v[3];
+    }
+}
+
 // NP: context partials fetched per round (the smallest of 2, 4, 8 that covers the split count keeps
 // the registers, and with them the resident wavefronts of a batch, in proportion).
 // MULTI: more splits than NP (the many splits of a full verification): rounds of NP, each round's
@@ -96,7 +109,8 @@ template <int CPL> __device__ __forceinline__ void load_partial(const float *p, 
 // NB: path nodes whose draft K / V rows are requested in the first go: 8 (a tree of candidates alone), or 24
 // when partially verified tokens stand in front of the tree as keys (every candidate's path then starts with
 // that whole chain; more registers, so only then).
-template <typename T, int D, int NP, bool MULTI, int NB>
+// HALF: the partials' O rows are fp16 and normalised (see Partials); else fp32 sums.
+template <typename T, int D, int NP, bool MULTI, int NB, bool HALF>
 __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
                                                     const float *a_pml, int a_M, int a_Hq, int a_G, int a_nsplit,
                                                     Shape s, Partials part, void *out, float *lse, float scale_log2)
@@ -137,7 +151,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
         for (int u = 0; u < NP; ++u) {
             const int64_t prow = prow0 + (int64_t)min(sp0 + u, part.nsplit - 1) * s.M;
             r.ml[u] = *(const float2 *)(part.ml + prow * 2);
-            load_partial<CPL>(part.o, prow * D + 4 * (lane & 15), r.po[u]);
+            if (HALF) load_partial_half<CPL>(part.o, prow * D, lane & 15, r.po[u]);
+            else load_partial<CPL>(part.o, prow * D + 4 * (lane & 15), r.po[u]);
         }
     };
     Round ra;
@@ -188,8 +203,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
         for (int u = 0; u < NP; ++u) {
             const float w = (sp0 + u < part.nsplit && r.ml[u].y > 0.f) ? exp2f(r.ml[u].x - m_use) : 0.f;
             l_ctx = fmaf(r.ml[u].y, w, l_ctx);
+            const float wo = HALF ? w * r.ml[u].y : w;   // a normalised partial weighs in with its l
 #pragma unroll
-            for (int x = 0; x < CPL; ++x) o[x] = fmaf(w, r.po[u][x], o[x]);
+            for (int x = 0; x < CPL; ++x) o[x] = fmaf(wo, r.po[u][x], o[x]);
         }
         m_ctx = m_new;
     };
@@ -281,20 +297,20 @@ static void launch_combine_t(const Shape &s, Partials p, void *out, float *lse, 
 {
     dim3 grid(8, s.M, (s.batch * s.Hkv + 7) / 8), block(64 * ((s.G + 3) / 4));
     const float scale_log2 = kLog2e / sqrtf((float)s.D);
-#define SPECPV_LAUNCH_NP(NP, MULTI)                                                                                          \
-    do {                                                                                                                    \
-        if (s.koff > 0)                                                                                                     \
-            hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI, 24>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, \
-                               (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2);                  \
-        else                                                                                                                \
-            hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI, 8>), grid, block, 0, st, s.parent, s.q, (const float *)p.o,  \
-                               (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2);                  \
+#define SPECPV_LAUNCH_K(NP, MULTI, NB, HALF)                                                                              \
+    hipLaunchKernelGGL((combine_kernel<T, D, NP, MULTI, NB, HALF>), grid, block, 0, st, s.parent, s.q, (const float *)p.o, \
+                       (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
+#define SPECPV_LAUNCH_NP(NP, MULTI)                                                                                      \
+    do {                                                                                                                \
+        if (s.koff > 0) { if (p.o_half) SPECPV_LAUNCH_K(NP, MULTI, 24, true); else SPECPV_LAUNCH_K(NP, MULTI, 24, false); } \
+        else { if (p.o_half) SPECPV_LAUNCH_K(NP, MULTI, 8, true); else SPECPV_LAUNCH_K(NP, MULTI, 8, false); }           \
     } while (0)
     if (p.nsplit <= 2) SPECPV_LAUNCH_NP(2, false);
     else if (p.nsplit <= 4) SPECPV_LAUNCH_NP(4, false);
     else if (p.nsplit <= 8) SPECPV_LAUNCH_NP(8, false);
     else SPECPV_LAUNCH_NP(8, true);
 #undef SPECPV_LAUNCH_NP
+#undef SPECPV_LAUNCH_K
 }
 
 hipError_t launch_combine(const Shape &s, int dtype, Partials p, void *out, float *lse, hipStream_t st)

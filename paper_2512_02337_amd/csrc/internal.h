@@ -28,16 +28,23 @@ struct Shape {
 };
 
 // Split-KV partial results of the context part, one per (b, h, split, node):
-//   part_o  [batch, Hq, nsplit, M, D] fp32   sum_t 2^(z_t - m) v_t   (not normalised)
 //   part_ml [batch, Hq, nsplit, M, 2] fp32   (m, l): m = max_t z_t, l = sum_t 2^(z_t - m),
 // with z = q.k * log2(e)/sqrt(D).  A split without any valid token stores m = -inf, l = 0.
-// Inside a row of part_o with D = 128 the channels are stored in the order the combine kernel
-// reads them (a lane of 16 owns channels 8 i .. 8 i + 7 and fetches them as two 16-byte pieces,
-// each piece dense over the 16 lanes): channel c sits at partial_pos(c).  D = 64: in order.
+//   part_o, one of two forms:
+//   o_half == 0:  [batch, Hq, nsplit, M, D] fp32   sum_t 2^(z_t - m) v_t   (not normalised).  Inside a row
+//     with D = 128 the channels are stored in the order the combine kernel reads them (a lane of 16 owns
+//     channels 8 i .. 8 i + 7 and fetches them as two 16-byte pieces, each piece dense over the 16 lanes):
+//     channel c sits at partial_pos(c).  D = 64: in order.  (vector-ALU kernel: fp32 inputs and their 1e-5
+//     bar; single-kernel route.)
+//   o_half == 1:  [batch, Hq, nsplit, M, D] fp16   the split's own softmax result, sum_t 2^(z_t - m) v_t / l
+//     (0 if l = 0), channels in order.  A convex combination of V rows, so within fp16's range as long as
+//     |v| <= 65504 (larger magnitudes are clamped); its 11 significant bits are 8 times finer than the
+//     bf16 output.  Half the bytes of the fp32 form: the partials are the call's second-largest traffic.
 struct Partials {
     float *o;
     float *ml;
     int nsplit;
+    int o_half;
 };
 __host__ __device__ constexpr int partial_pos(int c, int D)
 {
