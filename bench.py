@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0
 # (kernels and split count); the line carries them only while the library still plans the call that way.
 RECORDED = {"llama8b_128k": {
     "plan": {"kernels": ["attn_ctx_mfma_kernel", "combine_kernel"], "splits": 8},
-    "traffic_bytes": (10216 + 4928) * 2 * 1024 + (7800 + 480) * 1024,
+    "traffic_bytes": (8663 + 2419) * 2 * 1024 + (3960 + 480) * 1024,
     "traffic_source": "profiles/pmc_traffic_llama8b_128k.md",
-    "kernels": [{"name": "attn_ctx_mfma_kernel", "us": 14.1}, {"name": "combine_kernel", "us": 4.6}],
+    "kernels": [{"name": "attn_ctx_mfma_kernel", "us": 13.2}, {"name": "combine_kernel", "us": 4.76}],
     "kernels_source": "profiles/kernel_durations_llama8b_128k.md"}}
 
 
@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--settle", type=float, default=0.3,
                     help="seconds of untimed replays during set-up, before the W warm-up steps, to bring the box to its working clocks")
+    ap.add_argument("--route", type=int, default=0,
+                    help="specpv_debug_set_route value for the partial-verify attention (0: the library's choice; 2: one kernel)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run 4 plain device copies of 256 MiB (read 256 MiB + write 256 MiB each) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -79,6 +81,7 @@ def main():
     import workloads
     import paper_2512_02337_amd as specpv
     specpv.load()   # raises if the HIP library is missing: there is no fallback
+    specpv.specpv_debug_set_route(args.route)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -408,7 +411,7 @@ def main():
         "config": {"workload": args.workload, "layers": n_layers, "context": [int(x) for x in layers[0]["case"]["ctx_len"]],
                    "block": layers[0]["case"]["B"], "kept_blocks": layers[0]["case"]["n_sel"], "tree_nodes": layers[0]["case"]["M"],
                    "q_heads": layers[0]["case"]["Hq"], "kv_heads": layers[0]["case"]["Hkv"], "head_dim": layers[0]["case"]["D"],
-                   "launch": "hip_graph" if use_graph else "eager", "settle_s_before_warmup": args.settle},
+                   "launch": "hip_graph" if use_graph else "eager", "settle_s_before_warmup": args.settle, "route": args.route},
         "achieved_hbm_GBs": round(achieved, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -297,11 +297,12 @@ int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k
  * All give results within the documented bars.  Returns SPECPV_OK or SPECPV_EINVAL. */
 int specpv_debug_set_route(int route);
 
-/* Measuring aid, process-wide.  A library built with -DSPECPV_TIMELINE (see paper_2512_02337_amd/build.py:
- * SPECPV_EXTRA_HIPCC_FLAGS) makes every workgroup of the partial-verify attention kernel store 16
+/* Measuring aid, process-wide.  A library built with -DSPECPV_TIMELINE (`python -m paper_2512_02337_amd.build
+ * --timeline` makes libspecpv_timeline.so) has every workgroup of the partial-verify attention kernel store 16
  * 64-bit readings of the 100 MHz real-time counter at fixed points of its course to
- * buf[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + i] (device memory, NULL = off).  A regular build
- * stores nothing.  profiles/ says what the points are. */
+ * buf[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + i] (device memory, NULL = off);
+ * paper_2512_02337_amd/timeline.py names the points and prints their medians.  A regular build takes no
+ * stamps and answers a non-NULL buf with SPECPV_EINVAL. */
 int specpv_debug_set_timeline(void *buf);
 
 const char *specpv_strerror(int status);

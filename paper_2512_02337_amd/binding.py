@@ -69,9 +69,11 @@ def lib_path():
 
 def load():
     """dlopen libspecpv.so.  Raises if it has not been built: there is no fallback."""
-    global _lib
+    global _lib, _LIB_PATH
     if _lib is not None:
         return _lib
+    # SPECPV_LIB names another build of the same library (the instrumented one that timeline.py measures with)
+    _LIB_PATH = os.environ.get("SPECPV_LIB") or _LIB_PATH
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError("libspecpv.so is not built (%s missing): run "
                            "`python -m paper_2512_02337_amd.build` first" % _LIB_PATH)

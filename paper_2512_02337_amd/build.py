@@ -6,6 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecpv.so")
+# the same library with time stamps inside the partial-verify attention kernel (timeline.py uses it)
+LIB_TIMELINE = os.path.join(HERE, "libspecpv_timeline.so")
 SOURCES = ["api.hip", "summarize.hip", "select.hip", "score_mfma.hip", "attn_generic.hip",
            "attn_mfma.hip", "combine.hip", "commit.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -15,11 +17,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
-def build(verbose=False, jobs=8):
-    """Compile every HIP source to an object (in parallel) and link the shared library."""
+def build(verbose=False, jobs=8, lib=LIB, defines=()):
+    """Compile every HIP source to an object (in parallel) and link the shared library `lib`."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    extra = os.environ.get("SPECPV_EXTRA_HIPCC_FLAGS", "").split()   # for experiments: e.g. -DNAME
-    objdir = os.path.join(HERE, "_build")
+    extra = os.environ.get("SPECPV_EXTRA_HIPCC_FLAGS", "").split() + ["-D" + d for d in defines]
+    objdir = os.path.join(HERE, "_build", os.path.basename(lib).replace(".so", ""))
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
@@ -42,11 +44,17 @@ def build(verbose=False, jobs=8):
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, out))
         if verbose and out.strip():
             print(out)
-    tmp = LIB + ".tmp%d" % os.getpid()
+    tmp = lib + ".tmp%d" % os.getpid()
     subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
+
+
+def build_timeline(verbose=False):
+    """The instrumented variant: same sources, -DSPECPV_TIMELINE, its own file name."""
+    return build(verbose=verbose, lib=LIB_TIMELINE, defines=("SPECPV_TIMELINE",))
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build_timeline(verbose=True) if "--timeline" in sys.argv[1:] else build(verbose=True))

@@ -496,6 +496,9 @@ const char *specpv_last_hip_error(void) { return g_hip_err; }
 
 int specpv_debug_set_timeline(void *buf)
 {
+#ifndef SPECPV_TIMELINE
+    if (buf) return SPECPV_EINVAL;   // this build takes no time stamps
+#endif
     g_timeline = (unsigned long long *)buf;
     return SPECPV_OK;
 }

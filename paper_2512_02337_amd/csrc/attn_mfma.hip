@@ -659,6 +659,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     for (int i = 0; i < nch_max; ++i) {
         const bool active = i < nch;
         const int stg = i & 1;
+        if (i < 4) SPECPV_STAMP(12 + i);   // done with chunk i - 1, about to wait for chunk i
         // own half of chunk i has landed (the only younger group is chunk i+1's)
         if (i + 1 < nch) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
