@@ -153,7 +153,10 @@ int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree,
  * sel_idx == NULL attends over every block (full verification).  The order of
  * sel_idx does not matter; entries < 0 or >= nb_b are ignored; a block listed
  * twice is attended twice.
- * out [batch, Mq, Hq, D]; lse optional [batch, Mq, Hq] fp32. */
+ * out [batch, Mq, Hq, D]; lse optional [batch, Mq, Hq] fp32.
+ * Value range (bf16, head dim 128): the context part is computed in several pieces whose
+ * normalised results (convex combinations of V rows) travel through the workspace as fp16, so
+ * V entries are assumed to lie within +-65504; larger magnitudes are clamped there, not reported. */
 int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree,
                                const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
                                void *out, float *lse,
