@@ -157,6 +157,20 @@ __device__ __forceinline__ void lds_read_k4(const uint32_t (&a)[4], uint4 (&k)[8
         : "memory");
 }
 
+// Half of that: k-steps 4 h .. 4 h + 3 (OFF = 128 h).
+template <int OFF> __device__ __forceinline__ void lds_read_k_half(const uint32_t (&a)[4], uint4 (&k)[4])
+{
+    asm volatile(
+        "ds_read_b128 %0, %4 offset:%8\n\t"
+        "ds_read_b128 %1, %5 offset:%8\n\t"
+        "ds_read_b128 %2, %6 offset:%8\n\t"
+        "ds_read_b128 %3, %7 offset:%8\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2]), "=&v"(k[3])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "n"(OFF)
+        : "memory");
+}
+
 // V operands (A operand of O^T += V^T . P^T: per lane 8 tokens of ONE channel) through the
 // transposing LDS read ds_read_b64_tr_b16.  Inside a group of 16 lanes, lane s reads 8 bytes
 // (4 channels) and receives, as lane 4a + c, element c of what lanes a, a+4, a+8, a+12 read.
@@ -189,6 +203,25 @@ __device__ __forceinline__ void lds_read_v(uint32_t addr, uint2 (&v)[16])
         : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]),
           "=&v"(v[8]), "=&v"(v[9]), "=&v"(v[10]), "=&v"(v[11]), "=&v"(v[12]), "=&v"(v[13]), "=&v"(v[14]), "=&v"(v[15])
         : "v"(addr)
+        : "memory");
+}
+
+// Half of that: the operands of token half ks2 (OFF = 512 ks2), v[j * 2 + hf].
+template <int OFF> __device__ __forceinline__ void lds_read_v_half(uint32_t addr, uint2 (&v)[8])
+{
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %8 offset:%9\n\t"
+        "ds_read_b64_tr_b16 %1, %8 offset:%10\n\t"
+        "ds_read_b64_tr_b16 %2, %8 offset:%11\n\t"
+        "ds_read_b64_tr_b16 %3, %8 offset:%12\n\t"
+        "ds_read_b64_tr_b16 %4, %8 offset:%13\n\t"
+        "ds_read_b64_tr_b16 %5, %8 offset:%14\n\t"
+        "ds_read_b64_tr_b16 %6, %8 offset:%15\n\t"
+        "ds_read_b64_tr_b16 %7, %8 offset:%16\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+        : "v"(addr), "n"(OFF), "n"(OFF + 256), "n"(OFF + 64), "n"(OFF + 320), "n"(OFF + 128), "n"(OFF + 384), "n"(OFF + 192),
+          "n"(OFF + 448)
         : "memory");
 }
 
@@ -995,8 +1028,11 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 constexpr int kGroupStages = 4;   // a power of two
 constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
 
-template <bool ALIGNED, int W>   // W wavefronts per workgroup: 2, 4, 6 or 8
-__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// W wavefronts per workgroup: 2, 4, 6, 8 or 10.  Ten (nine or ten row blocks: G = 5 with up to 64 nodes) means
+// three wavefronts on two of the SIMDs, i.e. at most 168 registers each: that variant does without the deferred
+// O^T products of the second wavefront, which keep V operands alive beside the K operands.
+template <bool ALIGNED, int W>
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W > 8 ? 3 : 2, W > 8 ? 3 : 2)))
 void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 {
     extern __shared__ char lds_raw[];
@@ -1022,7 +1058,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const int hh = rbx_c / a.rph;
     const int m0 = (rbx_c - hh * a.rph) * 32;
     const int h = g * s.G + hh;
-    const bool second = wave >= 4;            // the second wavefront of its SIMD (wavefronts w and w + 4 share one)
+    const bool second = W <= 8 && wave >= 4;  // the second wavefront of its SIMD (wavefronts w and w + 4 share one)
     const int n = lane & 31, kg = lane >> 5;
 
     const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
@@ -1197,6 +1233,21 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
                                                                as_bf16x8(ks2 ? pf1 : pf0), O[j], 0, 0, 0);
             }
     };
+    // ten wavefronts: operands in halves (16 registers at a time instead of 32)
+    auto pv_halves = [&](const uint32_t vaddr) {
+        uint2 vh[8];
+        lds_read_v_half<0>(vaddr, vh);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(vh[2 * j].x, vh[2 * j].y, vh[2 * j + 1].x, vh[2 * j + 1].y)),
+                                                           as_bf16x8(pf0), O[j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_read_v_half<512>(vaddr, vh);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(vh[2 * j].x, vh[2 * j].y, vh[2 * j + 1].x, vh[2 * j + 1].y)),
+                                                           as_bf16x8(pf1), O[j], 0, 0, 0);
+    };
     for (int i = 0; i < nch; ++i) {
         // own part of chunk i has landed: kGroupAhead - 1 younger groups of n_ops operations may
         // stay in flight (towards the end of the range there are fewer: wait for all, they are due anyway)
@@ -1213,19 +1264,37 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         const uint32_t vmask = (uint32_t)__builtin_amdgcn_readlane((int)vmv, rs);
         if (!live) continue;
         if (second && i > 0) pv();   // chunk i - 1, before its V registers are overwritten
-        uint4 kf[8];
-        {
+        f32x16 S;
+        if (W > 8) {
+            // ten wavefronts: operands in halves, the V operands read behind the softmax (pv_halves)
             const uint32_t soff = (uint32_t)rs * kStageBytes;
             const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
-            lds_read_k4(ka, kf);
+            uint4 kh[4];
+            lds_read_k_half<0>(ka, kh);
+#pragma unroll
+            for (int x = 0; x < 16; ++x) S[x] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kh[ks]), qf[ks], S, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_read_k_half<128>(ka, kh);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kh[ks]), qf[4 + ks], S, 0, 0, 0);
+        } else {
+            uint4 kf[8];
+            {
+                const uint32_t soff = (uint32_t)rs * kStageBytes;
+                const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
+                lds_read_k4(ka, kf);
+            }
+            lds_read_v(vread + (uint32_t)rs * kStageBytes, v);
+#pragma unroll
+            for (int x = 0; x < 16; ++x) S[x] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[ks], S, 0, 0, 0);
         }
-        lds_read_v(vread + (uint32_t)rs * kStageBytes, v);
-        f32x16 S;
-#pragma unroll
-        for (int x = 0; x < 16; ++x) S[x] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[ks], S, 0, 0, 0);
 
         if (vmask != 0xffffffffu) {
 #pragma unroll
@@ -1264,18 +1333,31 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         l_run += lsum;
         pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        if (!second) pv();
+        if (W > 8) pv_halves(vread + (uint32_t)rs * kStageBytes);
+        else if (!second) pv();
     }
     if (second && live && nch > 0) pv();
     __syncthreads();   // every wavefront is done with the ring: the epilogue reuses that LDS
-    if (!live) return;
 
     // ---- one partial per (head, split, node): accumulators -> row-major through LDS ------
+    // (ten wavefronts: the staging area holds five at a time, so the second five wait for the first;
+    // every wavefront, live or not, passes that one barrier)
+    constexpr int kSlots = W > 8 ? W / 2 : W;
+    const int slot = wave < kSlots ? wave : wave - kSlots;
+    if (W > 8) {
+        if (wave >= kSlots) __builtin_amdgcn_s_barrier();
+        if (!live) {
+            if (wave < kSlots) __builtin_amdgcn_s_barrier();
+            return;
+        }
+    } else if (!live) {
+        return;
+    }
     l_run = sum_xor32(l_run);
     const int64_t prow0 = ((int64_t)(b * s.Hq + h) * part.nsplit + sp) * s.M;
     {
         // accumulator element 4q + x of tile j is channel 32j + 8q + 4kg + x of this lane's row
-        float *dst = obuf + ((size_t)wave * 32 + n) * kOPitch;
+        float *dst = obuf + ((size_t)slot * 32 + n) * kOPitch;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -1288,11 +1370,14 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const float il = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll 8
     for (int uu = 0; uu < 32; ++uu) {
-        const float2 x = *(const float2 *)(obuf + ((size_t)wave * 32 + uu) * kOPitch + 2 * lane);
+        const float2 x = *(const float2 *)(obuf + ((size_t)slot * 32 + uu) * kOPitch + 2 * lane);
         const float ilu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(il), uu));
         if (jrow0 + uu < s.M) store_partial_half(part.o + (prow0 + jrow0 + uu) * 64, lane, x.x * ilu, x.y * ilu);
     }
     if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
+    if (W > 8) {
+        if (wave < kSlots) __builtin_amdgcn_s_barrier();   // the slot is free for wavefront wave + kSlots
+    }
 }
 
 bool attn_ctx_mfma_supported(const Shape &s, int dtype)
@@ -1311,6 +1396,11 @@ static GroupLayout group_layout(const Shape &s)
     GroupLayout g;
     g.rph = (s.M + 31) / 32;
     g.n_row_blocks = s.G * g.rph;
+    if (g.n_row_blocks == 9 || g.n_row_blocks == 10) {   // one workgroup of ten instead of two of five
+        g.parts = 1;
+        g.waves = 10;
+        return g;
+    }
     g.parts = (g.n_row_blocks + 7) / 8;
     const int w = (g.n_row_blocks + g.parts - 1) / g.parts;   // 1 .. 8
     g.waves = w <= 2 ? 2 : (w <= 4 ? 4 : (w <= 6 ? 6 : 8));
@@ -1348,7 +1438,7 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool aligned = s.B % 32 == 0;
     const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
-    const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, gl.waves * 32 * kOPitch * (int)sizeof(float));
+    const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, (gl.waves > 8 ? gl.waves / 2 : gl.waves) * 32 * kOPitch * (int)sizeof(float));
 #define SPECPV_SET_LDS(KERN, LDS)                                                                      \
         static PerDeviceOnce once;   /* one per kernel instantiation */                               \
         auto kern = KERN;                                                                              \
@@ -1374,6 +1464,7 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
         case 2: SPECPV_LAUNCH_GROUP(2); break;
         case 4: SPECPV_LAUNCH_GROUP(4); break;
         case 6: SPECPV_LAUNCH_GROUP(6); break;
+        case 10: SPECPV_LAUNCH_GROUP(10); break;
         default: SPECPV_LAUNCH_GROUP(8); break;
         }
     } else if (fused) {

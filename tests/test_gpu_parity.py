@@ -126,12 +126,15 @@ def test_shapes_and_edges(gpu_lib, over, tag):
     (dict(ctx=[33000], B=64, M=40, Hq=4, Hkv=2), "G=2, four wavefronts"),
     (dict(ctx=[36864], B=64, M=60, Hq=16, Hkv=2), "G=8, two workgroups of eight"),
     (dict(ctx=[34000], B=16, M=50, Hq=6, Hkv=2, tree="uniform"), "G=3, six wavefronts, block 16"),
+    (dict(ctx=[35840, 33000], B=64, M=60, Hq=10, Hkv=2, rho=[0.1, 0.1]), "G=5, ten row blocks: one workgroup of ten wavefronts, batch of 2"),
+    (dict(ctx=[34567], B=16, M=60, Hq=10, Hkv=2, tree="uniform"), "G=5, ten wavefronts, block 16"),
+    (dict(ctx=[36000], B=64, M=70, Hq=6, Hkv=2, tree="uniform"), "G=3, nine row blocks: ten wavefronts, one idle"),
 ])
 def test_long_ranges_take_the_group_kernel(gpu_lib, over, tag):
     """Full verification over tens of thousands of tokens at small head counts: each wavefront
     gets eight or more chunks, which selects the kernel that serves all query heads of a KV head
-    from one workgroup: 8 wavefronts at G = 4, 6 (one idle) at G = 5, two workgroups for two row
-    tiles, 2 (one idle) at G = 1; head-major (256-byte row stride) and token-major layouts."""
+    from one workgroup: 8 wavefronts at G = 4, 6 (one idle) at G = 5 and 32 nodes, 10 at G = 5 and 60 nodes, two
+    workgroups for more row blocks, 2 (one idle) at G = 1; head-major (256-byte row stride) and token-major layouts."""
     say("case", tag)
     cfg = dict(SMALL); cfg.update(over)
     case = workloads.to_device(workloads.make_case(cfg, seed=17), "cuda")
