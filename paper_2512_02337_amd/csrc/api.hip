@@ -137,10 +137,12 @@ static AttnPlan plan_attention(const Shape &s, int dtype, int64_t n_blocks)
             ns = best_splits(base1, 1, max1);
             if (s.batch > 1) {
                 // The sequences of a batch may differ in length, and the lengths live on the device:
-                // many small workgroups (about eight per CU, 64 chunks or more each: shorter ones are
+                // many small workgroups (about four per CU, 64 chunks or more each: shorter ones are
                 // mostly prologue and epilogue) let the hardware scheduler even that out (measured on
-                // 32K + 64K + 96K + 128K: 1089 -> 841 us).
-                int64_t c = (8 * cus + base1 - 1) / base1;
+                // 32K + 64K + 96K + 128K at G = 5: 1089 -> 841 us with eight workgroups of six wavefronts per
+                // CU; with workgroups of ten, 752 us at eight per CU, 687 at four, 704 at two: every split
+                // is another partial for the combine, 85 us at 64 splits against 37 at 32).
+                int64_t c = (4 * cus + base1 - 1) / base1;
                 if (c > max1) c = max1;
                 while (c > ns && (chunks + c - 1) / c < 64) --c;
                 if (c > ns) ns = c;
