@@ -88,7 +88,12 @@ typedef struct specpv_kv {
  * verified again, i.e. they are ordinary nodes; on a partial step they are only
  * attended, i.e. the first n_key_only nodes have K/V rows and parent entries but
  * NO query rows and no output rows.  Mq = M - n_key_only is the number of query
- * nodes; query row r belongs to node n_key_only + r. */
+ * nodes; query row r belongs to node n_key_only + r.
+ * The key-only nodes must be that chain (parent[i] = i - 1 for 0 < i < n_key_only) and every
+ * query node must descend from its last node, as specpv_extend_parents builds it: every query
+ * row then attends every key-only node, and the bf16 kernels take those K/V rows along with the
+ * cache tokens without looking at their parent entries (a tree that breaks the rule is not
+ * detected: its query rows attend all key-only nodes all the same). */
 typedef struct specpv_tree {
     const void *q;         /* [batch, Mq, Hq, D] contiguous, post-RoPE                   */
     const void *kd, *vd;   /* [batch, M, Hkv, D] contiguous; may be NULL for select      */

@@ -190,11 +190,15 @@ static Workspace layout_workspace(const Shape &s, int nsplit, void *base)
 static int g_route = 0;
 static unsigned long long *g_timeline = nullptr;   // where instrumented builds (-DSPECPV_TIMELINE) put their time stamps
 
-static int run_attention(const Shape &s, int dtype, const int32_t *sel_idx, const int32_t *sel_count,
+static int run_attention(const Shape &s_in, int dtype, const int32_t *sel_idx, const int32_t *sel_count,
                          int n_sel, void *out, float *lse, void *workspace, size_t workspace_bytes,
                          hipStream_t st)
 {
-    const AttnPlan plan = plan_attention(s, dtype, sel_idx ? n_sel : s.max_blocks);
+    const AttnPlan plan = plan_attention(s_in, dtype, sel_idx ? n_sel : s_in.max_blocks);
+    Shape s = s_in;
+    // the matrix-core kernels take the partially verified tokens in front of the tree along with the cache
+    // tokens (dense: every query row attends all of them); the vector-ALU kernel leaves them to the combine
+    s.kctx = plan.kind != kAttnGeneric ? s.koff : 0;
     const int nsplit = plan.nsplit;
     const Workspace w = layout_workspace(s, nsplit, workspace);
     if (!workspace || workspace_bytes < w.total) return SPECPV_EWORKSPACE;

@@ -301,11 +301,12 @@ __device__ __forceinline__ float oct_sum(float x)
 }
 // The root path of tree node j as a bit set; par0 / par1 hold parent[lane] / parent[lane + 64].
 // Everything is wave-uniform (scalar registers).
-__device__ __forceinline__ void root_path(int j, int n_nodes, int par0, int par1, unsigned long long &lo,
+// Nodes below `stop` (partially verified tokens that the context kernels attend) end the walk.
+__device__ __forceinline__ void root_path(int j, int n_nodes, int stop, int par0, int par1, unsigned long long &lo,
                                           unsigned long long &hi)
 {
     int aa = j;
-    for (int guard = 0; aa >= 0 && guard < n_nodes; ++guard) {
+    for (int guard = 0; aa >= stop && guard < n_nodes; ++guard) {
         if (aa < 64) lo |= 1ull << aa; else hi |= 1ull << (aa - 64);
         const int pa = aa < 64 ? __builtin_amdgcn_readlane(par0, aa) : __builtin_amdgcn_readlane(par1, aa - 64);
         aa = pa < aa ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
@@ -366,7 +367,9 @@ constexpr int kXccBits = 7;
 // recompute route.  REDO = true: that route -- the pass runs as the only split of one (sp0 = 0, ns_eff = 1).
 // Everything, the argument-dependent reads included, is done again in the second pass, so that it keeps
 // no register of the first one alive.
-template <bool ALIGNED, bool FUSED, bool REDO>
+// PEND: partially verified tokens may stand in front of the tree (s.kctx > 0); without it the kernel is the one
+// that the headline shape runs, free of that path's registers and tests.
+template <bool ALIGNED, bool FUSED, bool REDO, bool PEND>
 __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a, FusedArgs f, const int nctx,
                                               const int sp0, const int ns_eff, char *lds_raw)
 {
@@ -433,7 +436,14 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     int cnt = nb;
     if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
     const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;   // host guarantees max_blocks * B <= 2^30
-    const uint32_t C = (T + 31u) >> 5;
+    // chunks of cache tokens, then the chunks of the partially verified tokens (the first kctx draft nodes: a
+    // chain that every query node descends from, so all rows attend all of them, like cache tokens)
+    const uint32_t C_ctx = (T + 31u) >> 5;
+    const int kctx = PEND ? s.kctx : 0;
+    const uint32_t C = C_ctx + (((uint32_t)kctx + 31u) >> 5);
+    const char *kdb = (const char *)s.kd + (((int64_t)b * s.Mk) * s.Hkv + g) * 256;
+    const char *vdb = (const char *)s.vd + (((int64_t)b * s.Mk) * s.Hkv + g) * 256;
+    const uint32_t stp = (uint32_t)s.Hkv * 256u;   // bytes from one draft node's row to the next
 
     // uniform slab bases; per-lane byte offsets inside a slab fit 32 bits (host-checked)
     const char *kb = (const char *)s.k + ((int64_t)b * s.sb + (int64_t)g * s.sh) * 2;
@@ -486,7 +496,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     auto fill_rows = [&](int cb) {
         row_base = cb;
         int r = -1;
-        if (cb + lane < nch) {
+        if (cb + lane < nch && (uint32_t)(c0 + cb + lane) < C_ctx) {
             const uint32_t p0 = (uint32_t)(c0 + cb + lane) * 32u;   // < T: the slot below is < cnt
             const uint32_t slot = a.div_B.div(p0);
             r = encode_row(sel ? sel[slot] : (int)slot, p0, slot);
@@ -506,7 +516,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         const int e0 = __shfl(idv[0], src), e1 = __shfl(idv[1], src), e2 = __shfl(idv[2], src), e3 = __shfl(idv[3], src);
         const int q4 = (int)(slot >> 6);
         const int blk = q4 == 0 ? e0 : (q4 == 1 ? e1 : (q4 == 2 ? e2 : e3));
-        row0vec = lane < nch ? encode_row(blk, p0, slot) : -1;   // p0 < T there: the slot is < cnt
+        row0vec = (lane < nch && (uint32_t)(c0 + lane) < C_ctx) ? encode_row(blk, p0, slot) : -1;   // p0 < T there: the slot is < cnt
     };
     // general case: this lane's token (t = lane & 31) of chunk ci, or -1
     auto lane_row = [&](int ci) -> int {
@@ -524,11 +534,35 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     // Request this wavefront's half of chunk ci: 8 DMA operations of 1 KiB (one 256-byte row per
     // 16 lanes).  rb == 0: the K rows, operation i brings rows 4i .. 4i+3, pieces swizzled by
     // row & 7.  rb == 1: the V rows, operation i brings rows i, i+8, i+16, i+24 into piece i.
+    // rows given per lane (t = lane & 31: token tk of the chunk, bits vm say which are real)
+    auto issue_rows = [&](const char *kbase, const char *vbase, const uint32_t stride, const uint32_t tk, char *dst, char *dstv) {
+        if (rb == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * stride;
+                dma16(kbase + (tv + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * stride;
+                dma16(vbase + (tv + vsw), dstv + i * kVPiecePitch);
+            }
+        }
+    };
     auto issue = [&](int ci) {
         const int stg = ci & (kStages - 1);
         char *dst = my_ring + stg * kStageBytes;
         char *dstv = dst + 8192;
         int tok;
+        if (PEND && kctx > 0 && (uint32_t)(c0 + ci) >= C_ctx) {
+            // a chunk of partially verified tokens: rows of the draft K / V arrays
+            const int pr = (int)((uint32_t)(c0 + ci) - C_ctx) * 32 + n;
+            const int ptok = pr < kctx ? pr : -1;
+            vmask_st[stg] = (uint32_t)__ballot(ptok >= 0);
+            issue_rows(kdb, vdb, stp, (uint32_t)max(ptok, 0), dst, dstv);
+            return;
+        }
         if (ALIGNED) {
             if (ci - row_base >= 64) fill_rows(ci);
             const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
@@ -569,19 +603,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
         vmask_st[stg] = vm;
-        if (rb == 0) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
-                dma16(kb + (tv + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * st2;
-                dma16(vb + (tv + vsw), dstv + i * kVPiecePitch);
-            }
-        }
+        issue_rows(kb, vb, st2, tk, dst, dstv);
     };
 
     if (ALIGNED && nch > 0) fill_rows_first();
@@ -603,7 +625,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     auto draft_row = [&](int row, bool live, bool with_chunks) {
         const int jn = s.koff + m0 + row;
         unsigned long long anc_lo = 0ull, anc_hi = 0ull;
-        root_path(jn, s.Mk, par0, par1, anc_lo, anc_hi);
+        root_path(jn, s.Mk, kctx, par0, par1, anc_lo, anc_hi);
         const int n0 = pop_node(anc_lo, anc_hi), n1 = pop_node(anc_lo, anc_hi), n2 = pop_node(anc_lo, anc_hi),
                   n3 = pop_node(anc_lo, anc_hi), n4 = pop_node(anc_lo, anc_hi), n5 = pop_node(anc_lo, anc_hi),
                   n6 = pop_node(anc_lo, anc_hi), n7 = pop_node(anc_lo, anc_hi);
@@ -996,7 +1018,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     return false;
 }
 
-template <bool ALIGNED, bool FUSED>
+template <bool ALIGNED, bool FUSED, bool PEND>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, const int32_t *a_ctx_len,
                           const void *a_q, int a_n_sel, int a_M, int a_Hq, int a_nctx,
@@ -1007,8 +1029,8 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
     a.sel_idx = a_sel_idx; a.sel_count = a_sel_count; a.n_sel = a_n_sel;
     extern __shared__ char lds_raw[];
     const int sp0 = (int)blockIdx.y - (int)a.div_nsplit.div(blockIdx.y) * a_nctx;
-    if (attn_ctx_pass<ALIGNED, FUSED, false>(s, part, a, f, a_nctx, sp0, a_nctx, lds_raw)) {
-        if (FUSED) attn_ctx_pass<ALIGNED, true, true>(s, part, a, f, a_nctx, 0, 1, lds_raw);
+    if (attn_ctx_pass<ALIGNED, FUSED, false, PEND>(s, part, a, f, a_nctx, sp0, a_nctx, lds_raw)) {
+        if (FUSED) attn_ctx_pass<ALIGNED, true, true, PEND>(s, part, a, f, a_nctx, 0, 1, lds_raw);
     }
 }
 
@@ -1027,6 +1049,7 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // merge: it only turns the accumulators into row-major partials.
 constexpr int kGroupStages = 4;   // a power of two
 constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
+static_assert(kStageBytes % 128 == 0, "the ten-wavefront variant derives K operand addresses by XOR: stages (and the ring, which starts the workgroup's LDS) must be 128-byte aligned");
 
 // W wavefronts per workgroup: 2, 4, 6, 8 or 10.  Ten (nine or ten row blocks: G = 5 with up to 64 nodes) means
 // three wavefronts on two of the SIMDs, i.e. at most 168 registers each: that variant does without the deferred
@@ -1083,7 +1106,12 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     int cnt = nb;
     if (sel) cnt = max(0, min(cnt_raw, a.n_sel));
     const uint32_t T = nb > 0 ? (uint32_t)cnt * Bu : 0u;
-    const uint32_t C = (T + 31u) >> 5;
+    // chunks of cache tokens, then those of the partially verified tokens (see attn_ctx_mfma_kernel)
+    const uint32_t C_ctx = (T + 31u) >> 5;
+    const uint32_t C = C_ctx + (((uint32_t)s.kctx + 31u) >> 5);
+    const char *kdb = (const char *)s.kd + (((int64_t)b * s.Mk) * s.Hkv + g) * 256;
+    const char *vdb = (const char *)s.vd + (((int64_t)b * s.Mk) * s.Hkv + g) * 256;
+    const uint32_t stp = (uint32_t)s.Hkv * 256u;
     const int c0 = first_chunk(C, sp), c1 = first_chunk(C, sp + 1);
     const int nch = c1 - c0;                  // the same for all wavefronts: the barriers match up
 
@@ -1109,7 +1137,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     auto fill_rows = [&](int cb) {
         row_base = cb;
         int r = -1;
-        if (cb + lane < nch) {
+        if (cb + lane < nch && (uint32_t)(c0 + cb + lane) < C_ctx) {
             const uint32_t p0 = (uint32_t)(c0 + cb + lane) * 32u;   // < T: the slot below is < cnt
             const uint32_t slot = a.div_B.div(p0);
             const int blk = sel ? sel[slot] : (int)slot;
@@ -1143,24 +1171,55 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     // the common path is straight-line code.
     constexpr int NOPS = (16 + W - 1) / W;
     const int n_ops = (16 - wave + W - 1) / W;       // NOPS or NOPS - 1
-    const int r4 = lane >> 4, pos = lane & 15;
-    const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
-    const char *src_lane[NOPS];   // per operation: source of this lane relative to the chunk's first row
+    const char *src_base[NOPS];   // per operation: K or V slab (wave-uniform: scalar registers)
+    uint32_t src_off[NOPS];       // ... this lane's bytes from the chunk's first row (one register each)
     int dst_off[NOPS];            // ... and where it lands in the stage
+    {
+        const int r4 = lane >> 4, pos = lane & 15;
+        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
 #pragma unroll
-    for (int t = 0; t < NOPS; ++t) {
-        const int o = min(wave + W * t, 15), i = o & 7;
-        if (o < 8) {
-            src_lane[t] = kb + ((uint32_t)(4 * i + r4) * st2 + ((i & 1) ? sw_odd : sw_even));
-            dst_off[t] = i * 1024;
-        } else {
-            src_lane[t] = vb + ((uint32_t)(8 * r4 + i) * st2 + vsw);
-            dst_off[t] = 8192 + i * kVPiecePitch;
+        for (int t = 0; t < NOPS; ++t) {
+            const int o = min(wave + W * t, 15), i = o & 7;
+            if (o < 8) {
+                src_base[t] = kb;
+                src_off[t] = (uint32_t)(4 * i + r4) * st2 + ((i & 1) ? sw_odd : sw_even);
+                dst_off[t] = i * 1024;
+            } else {
+                src_base[t] = vb;
+                src_off[t] = (uint32_t)(8 * r4 + i) * st2 + vsw;
+                dst_off[t] = 8192 + i * kVPiecePitch;
+            }
         }
     }
+    auto issue_rows = [&](const char *kbase, const char *vbase, const uint32_t stride, const uint32_t tk, char *dst) {
+        // (the swizzles are recomputed here, from a lane id the compiler cannot see through: kept in registers
+        // across the loop for this rare path they cost the ten-wavefront variant its last free registers)
+        int lane_o = lane;
+        asm volatile("" : "+v"(lane_o));
+        const int r4 = lane_o >> 4, pos = lane_o & 15;
+        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+#pragma unroll
+        for (int t = 0; t < NOPS; ++t) {
+            if (16 % W != 0 && t == NOPS - 1 && n_ops != NOPS) continue;
+            const int o = wave + W * t, i = o & 7;
+            if (o < 8) {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * stride;
+                dma16(kbase + (tv + ((i & 1) ? sw_odd : sw_even)), dst + dst_off[t]);
+            } else {
+                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * stride;
+                dma16(vbase + (tv + vsw), dst + dst_off[t]);
+            }
+        }
+    };
     auto issue = [&](int ci, int stg) -> uint32_t {
         char *dst = ring + stg * kStageBytes;
         int tok;
+        if (s.kctx > 0 && (uint32_t)(c0 + ci) >= C_ctx) {
+            const int pr = (int)((uint32_t)(c0 + ci) - C_ctx) * 32 + n;
+            const int ptok = pr < s.kctx ? pr : -1;
+            issue_rows(kdb, vdb, stp, (uint32_t)max(ptok, 0), dst);
+            return (uint32_t)__ballot(ptok >= 0);
+        }
         if (ALIGNED) {
             if (ci - row_base >= 64) fill_rows(ci);
             const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
@@ -1169,7 +1228,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
                 for (int t = 0; t < NOPS; ++t)
                     if (16 % W == 0 || t < NOPS - 1 || n_ops == NOPS)
-                        __builtin_amdgcn_global_load_lds((glb_void_ptr)(src_lane[t] + row_off), (lds_void_ptr)(dst + dst_off[t]), 16, 0, kKvAux);
+                        __builtin_amdgcn_global_load_lds((glb_void_ptr)((src_base[t] + row_off) + src_off[t]), (lds_void_ptr)(dst + dst_off[t]), 16, 0, kKvAux);
                 return 0xffffffffu;
             }
             const int rr = -2 - r0;   // r0 == -1 gives -1
@@ -1179,18 +1238,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         }
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
         const uint32_t tk = tok >= 0 ? (uint32_t)tok : 0u;   // row 0 exists (L > 0); masked later
-#pragma unroll
-        for (int t = 0; t < NOPS; ++t) {
-            if (16 % W != 0 && t == NOPS - 1 && n_ops != NOPS) continue;
-            const int o = wave + W * t, i = o & 7;
-            if (o < 8) {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * st2;
-                dma16(kb + (tv + ((i & 1) ? sw_odd : sw_even)), dst + dst_off[t]);
-            } else {
-                const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * st2;
-                dma16(vb + (tv + vsw), dst + dst_off[t]);
-            }
-        }
+        issue_rows(kb, vb, st2, tk, dst);
         return vm;
     };
 
@@ -1267,8 +1315,9 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         f32x16 S;
         if (W > 8) {
             // ten wavefronts: operands in halves, the V operands read behind the softmax (pv_halves)
-            const uint32_t soff = (uint32_t)rs * kStageBytes;
-            const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
+            // (k-step ks reads 32 ks bytes further, modulo the swizzle: an XOR, as the row starts are 128-byte aligned)
+            const uint32_t ka0 = kread[0] + (uint32_t)rs * kStageBytes;
+            const uint32_t ka[4] = {ka0, ka0 ^ 32u, ka0 ^ 64u, ka0 ^ 96u};
             uint4 kh[4];
             lds_read_k_half<0>(ka, kh);
 #pragma unroll
@@ -1453,9 +1502,9 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
         else { SPECPV_SET_LDS((attn_ctx_mfma_group_kernel<false, WW>), lds_group);                      \
                hipLaunchKernelGGL(kern, grid, dim3(64 * WW), lds_group, st, s, p, a); }                 \
     } while (0)
-#define SPECPV_LAUNCH_SPLIT(AL, FU)                                                                    \
+#define SPECPV_LAUNCH_SPLIT(AL, FU, PE)                                                                \
     do {                                                                                               \
-        SPECPV_SET_LDS((attn_ctx_mfma_kernel<AL, FU>), lds_split);                                      \
+        SPECPV_SET_LDS((attn_ctx_mfma_kernel<AL, FU, PE>), lds_split);                                  \
         hipLaunchKernelGGL(kern, grid, dim3(512), lds_split, st, sel_idx, sel_count, s.ctx_len, s.q,    \
                            n_sel, s.M, s.Hq, nctx, s, p, a, f);                                         \
     } while (0)
@@ -1468,9 +1517,10 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
         default: SPECPV_LAUNCH_GROUP(8); break;
         }
     } else if (fused) {
-        if (aligned) SPECPV_LAUNCH_SPLIT(true, true); else SPECPV_LAUNCH_SPLIT(false, true);
+        if (aligned) SPECPV_LAUNCH_SPLIT(true, true, true); else SPECPV_LAUNCH_SPLIT(false, true, true);
     } else {
-        if (aligned) SPECPV_LAUNCH_SPLIT(true, false); else SPECPV_LAUNCH_SPLIT(false, false);
+        if (s.kctx > 0) { if (aligned) SPECPV_LAUNCH_SPLIT(true, false, true); else SPECPV_LAUNCH_SPLIT(false, false, true); }
+        else { if (aligned) SPECPV_LAUNCH_SPLIT(true, false, false); else SPECPV_LAUNCH_SPLIT(false, false, false); }
     }
 #undef SPECPV_LAUNCH_SPLIT
 #undef SPECPV_LAUNCH_GROUP

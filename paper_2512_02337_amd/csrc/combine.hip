@@ -162,7 +162,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
     unsigned long long anc_lo = 0ull, anc_hi = 0ull;
     {
         int a = j + s.koff;
-        for (int guard = 0; a >= 0 && guard < s.Mk; ++guard) {
+        // (nodes below kctx are partially verified tokens that the context kernels have attended already)
+        for (int guard = 0; a >= s.kctx && guard < s.Mk; ++guard) {
             if (a < 64) anc_lo |= 1ull << a; else anc_hi |= 1ull << (a - 64);
             const int pa = a < 64 ? __builtin_amdgcn_readlane(par0, a) : __builtin_amdgcn_readlane(par1, a - 64);
             a = pa < a ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
@@ -302,7 +303,7 @@ static void launch_combine_t(const Shape &s, Partials p, void *out, float *lse, 
                        (const float *)p.ml, s.M, s.Hq, s.G, p.nsplit, s, p, out, lse, scale_log2)
 #define SPECPV_LAUNCH_NP(NP, MULTI)                                                                                      \
     do {                                                                                                                \
-        if (s.koff > 0) { if (p.o_half) SPECPV_LAUNCH_K(NP, MULTI, 24, true); else SPECPV_LAUNCH_K(NP, MULTI, 24, false); } \
+        if (s.koff > s.kctx) { if (p.o_half) SPECPV_LAUNCH_K(NP, MULTI, 24, true); else SPECPV_LAUNCH_K(NP, MULTI, 24, false); } \
         else { if (p.o_half) SPECPV_LAUNCH_K(NP, MULTI, 8, true); else SPECPV_LAUNCH_K(NP, MULTI, 8, false); }           \
     } while (0)
     if (p.nsplit <= 2) SPECPV_LAUNCH_NP(2, false);

@@ -25,6 +25,10 @@ struct Shape {
     // first koff = Mk - M nodes are keys only (partially verified tokens on a partial step);
     // query row r is node koff + r.
     int Mk, koff;
+    // Of those, the first kctx (0 or koff) are attended by the context kernels as if they were cache
+    // tokens -- they are a chain from which every query node descends, so every row sees all of them --
+    // and the draft-tree segment (combine kernel, single-kernel route) stops its root paths there.
+    int kctx;
 };
 
 // Split-KV partial results of the context part, one per (b, h, split, node):

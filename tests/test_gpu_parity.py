@@ -369,3 +369,59 @@ def test_key_only_nodes(gpu_lib, name, seed, n_key, Mq):
     torch.cuda.synchronize()
     O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"], n_key_only=n_key)
     assert np.abs(_to_np(run.out)[0] - O).max() <= ATOL[case["dtype"]]
+
+
+def _with_pending(base, n_key, seed):
+    """The case with n_key partially verified tokens (a chain, Section 3.3) in front of every sequence's tree."""
+    gen = torch.Generator().manual_seed(seed)
+    dt = base["q"].dtype
+    bsz = base["batch"]
+    pk = torch.randn((bsz, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
+    pv = torch.randn((bsz, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
+    case = dict(base)
+    case["kd"], case["vd"] = torch.cat([pk, base["kd"]], 1), torch.cat([pv, base["vd"]], 1)
+    case["parent"] = torch.from_numpy(np.array([oracle.extend_parents(base["parent"][b].tolist(), n_key) for b in range(bsz)],
+                                               dtype=np.int32))
+    return case
+
+
+@pytest.mark.parametrize("over,n_key,tag", [
+    (dict(ctx=[1000]), 33, "two chunks of pending tokens, the second with one token; block 16 (chunks cross blocks)"),
+    (dict(ctx=[2048], B=64, M=60, Hq=8, Hkv=2), 64, "two full chunks, 64-token blocks"),
+    (dict(ctx=[1500, 70], B=32, rho=[0.1, 0.1]), 7, "batch of two, one shorter than a block row"),
+    (dict(ctx=[36000], B=64, M=60, Hq=8, Hkv=2), 20, "long context: the group kernel, eight wavefronts"),
+    (dict(ctx=[35840, 33000], B=64, M=60, Hq=10, Hkv=2, rho=[0.1, 0.1]), 17, "group kernel, ten wavefronts, batch of two"),
+    (dict(ctx=[34567], B=16, M=40, Hq=4, Hkv=2), 40, "group kernel, block 16, four wavefronts"),
+    (dict(ctx=[3], B=16, M=30), 12, "three cache tokens"),
+    (dict(ctx=[1200], dtype="f32", D=64), 9, "f32, D = 64: the vector-ALU kernel leaves them to the combine"),
+])
+def test_pending_tokens_go_with_the_cache_tokens(gpu_lib, over, n_key, tag):
+    """The matrix-core kernels attend the partially verified tokens as extra 32-token chunks behind the cache
+    tokens (rows of the draft K / V arrays), the combine kernel stops its root paths at the chain: partial
+    attention over the kept lists and attention over every block against the oracle, both layouts."""
+    say("case", tag)
+    cfg = dict(SMALL); cfg.update(over)
+    base = workloads.make_case(cfg, seed=23)
+    case = workloads.to_device(_with_pending(base, n_key, 100 + n_key), "cuda")
+    for layout in ("bhtd", "bthd"):
+        run = GpuRun(gpu_lib, case, layout=layout)
+        assert run.tree.n_key_only == n_key
+        run.summarize(); run.select(); run.attend()
+        torch.cuda.synchronize()
+        out, lse = _to_np(run.out), _to_np(run.lse)
+        for full in (False, True):
+            if full:
+                run.out.zero_()
+                run.attend(None, None)
+                torch.cuda.synchronize()
+                out, lse = _to_np(run.out), _to_np(run.lse)
+            worst = 0.0
+            for b in range(case["batch"]):
+                o = workloads.oracle_views(case, b)
+                gi, gc = (None, None) if full else (run.sel_idx.cpu().numpy()[b], run.sel_count.cpu().numpy()[b])
+                O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"], gi, gc,
+                                                  n_key_only=n_key)
+                worst = max(worst, np.abs(out[b] - O).max())
+                np.testing.assert_allclose(lse[b], LSE, atol=2e-5 if case["dtype"] == "f32" else 2e-3, rtol=1e-5)
+            say("   %s %s %s: max-abs err %.3g" % (tag, layout, "every block" if full else "kept lists", worst))
+            assert worst <= ATOL[case["dtype"]]
