@@ -98,3 +98,17 @@ def check_selection(got_idx, got_cnt, ref_idx, ref_cnt, sc, ns, nr, k, tag=""):
         for i in set(a) ^ set(r):
             assert abs(np.float32(sc[g, i]) - thr) <= TAU, (tag, g, i, "differs beyond the near-tie band")
     return exact
+
+
+def with_pending(base, n_key, seed):
+    """The case with n_key partially verified tokens (a chain, Section 3.3) in front of every sequence's tree."""
+    gen = torch.Generator().manual_seed(seed)
+    dt = base["q"].dtype
+    bsz = base["batch"]
+    pk = torch.randn((bsz, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
+    pv = torch.randn((bsz, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
+    case = dict(base)
+    case["kd"], case["vd"] = torch.cat([pk, base["kd"]], 1), torch.cat([pv, base["vd"]], 1)
+    case["parent"] = torch.from_numpy(np.array([oracle.extend_parents(base["parent"][b].tolist(), n_key) for b in range(bsz)],
+                                               dtype=np.int32))
+    return case

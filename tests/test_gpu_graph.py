@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import workloads
-from helpers import ATOL, GpuRun, say
+from helpers import ATOL, GpuRun, say, with_pending
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +43,7 @@ def _new_queries(case, seed):
 
 @pytest.mark.parametrize("name", ["llama8b_16k", "qwen14b_small"])
 def test_graph_replays_match_eager(gpu_lib, name):
-    if name == "qwen14b_small":   # ragged batch at G = 5 (two workgroups per KV head in the group kernel)
+    if name == "qwen14b_small":   # ragged batch at G = 5 (the ten-wavefront workgroups of the group kernel)
         cfg = dict(workloads.CONFIGS["qwen14b_batch4"])
         cfg.update(ctx=[9000, 33000, 70, 20000], name=name)
     else:
@@ -90,6 +90,39 @@ def test_graph_replays_match_eager(gpu_lib, name):
                 err = np.abs(run.out[0].float().cpu().numpy().astype(np.float64) - O).max()
                 say("  eager vs oracle: max-abs err %.3g" % err)
                 assert err <= ATOL[c["dtype"]]
+
+
+def test_graph_replays_with_pending_tokens(gpu_lib):
+    """A partial step with partially verified tokens in front of the tree (the bench's 16-pending leg): the
+    attention kernel takes them as an extra chunk read from the draft K / V arrays."""
+    n_key = 16
+    base = workloads.make_case("llama8b_16k", seed=5)
+    case = workloads.to_device(with_pending(base, n_key, 77), "cuda")
+    run = GpuRun(gpu_lib, case)
+    run.summarize(); run.select()
+    torch.cuda.synchronize()
+    g = _capture(run.attend)
+    for rep in range(4):
+        gen = torch.Generator(device="cuda").manual_seed(300 + rep)
+        for name in ("q", "kd", "vd"):   # new queries, new draft and pending K / V rows, same chain + tree
+            t = case[name]
+            t.copy_(torch.randn(t.shape, generator=gen, device="cuda", dtype=torch.float32).to(t.dtype))
+        run.out.fill_(-3); run.lse.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = run.out.clone(), run.lse.clone()
+        run.out.fill_(-3); run.lse.fill_(-3)
+        run.attend()
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], run.out) and torch.equal(got[1], run.lse), "replay %d differs from the eager call" % rep
+        if rep == 0:
+            o = workloads.oracle_views(case, 0)
+            O, lse, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"],
+                                              run.sel_idx[0].cpu().numpy(), run.sel_count[0].cpu().numpy(), n_key_only=n_key)
+            err = np.abs(run.out[0].float().cpu().numpy().astype(np.float64) - O).max()
+            say("  pending tokens, eager vs oracle: max-abs err %.3g" % err)
+            assert err <= ATOL[case["dtype"]]
 
 
 def test_commit_graph_replays_match_eager(gpu_lib):

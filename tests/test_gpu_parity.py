@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import workloads
-from helpers import ATOL, GpuRun, check_selection, oracle_select, say, topk_margin
+from helpers import ATOL, GpuRun, check_selection, oracle_select, say, topk_margin, with_pending
 
 pytestmark = pytest.mark.gpu
 
@@ -371,20 +371,6 @@ def test_key_only_nodes(gpu_lib, name, seed, n_key, Mq):
     assert np.abs(_to_np(run.out)[0] - O).max() <= ATOL[case["dtype"]]
 
 
-def _with_pending(base, n_key, seed):
-    """The case with n_key partially verified tokens (a chain, Section 3.3) in front of every sequence's tree."""
-    gen = torch.Generator().manual_seed(seed)
-    dt = base["q"].dtype
-    bsz = base["batch"]
-    pk = torch.randn((bsz, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
-    pv = torch.randn((bsz, n_key, base["Hkv"], base["D"]), generator=gen).to(dt)
-    case = dict(base)
-    case["kd"], case["vd"] = torch.cat([pk, base["kd"]], 1), torch.cat([pv, base["vd"]], 1)
-    case["parent"] = torch.from_numpy(np.array([oracle.extend_parents(base["parent"][b].tolist(), n_key) for b in range(bsz)],
-                                               dtype=np.int32))
-    return case
-
-
 @pytest.mark.parametrize("over,n_key,tag", [
     (dict(ctx=[1000]), 33, "two chunks of pending tokens, the second with one token; block 16 (chunks cross blocks)"),
     (dict(ctx=[2048], B=64, M=60, Hq=8, Hkv=2), 64, "two full chunks, 64-token blocks"),
@@ -402,7 +388,7 @@ def test_pending_tokens_go_with_the_cache_tokens(gpu_lib, over, n_key, tag):
     say("case", tag)
     cfg = dict(SMALL); cfg.update(over)
     base = workloads.make_case(cfg, seed=23)
-    case = workloads.to_device(_with_pending(base, n_key, 100 + n_key), "cuda")
+    case = workloads.to_device(with_pending(base, n_key, 100 + n_key), "cuda")
     for layout in ("bhtd", "bthd"):
         run = GpuRun(gpu_lib, case, layout=layout)
         assert run.tree.n_key_only == n_key
