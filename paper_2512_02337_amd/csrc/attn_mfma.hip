@@ -480,6 +480,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     const int c0 = first_chunk(C, wsid), c1 = first_chunk(C, wsid + 1);
     const int nch = c1 - c0;
     const int nch_max = first_chunk(C, sp * 4 + 1) - first_chunk(C, sp * 4);   // token group 0 has the most
+    if (!FUSED) SPECPV_STAMP(9);   // the scalar reads (lengths, list length) are in: the chunk counts are known
 
     // ---- chunk -> token rows ------------------------------------------------------------
     // ALIGNED (B % 32 == 0): a chunk lies inside one block, so its 32 rows are consecutive.  The

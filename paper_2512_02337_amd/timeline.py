@@ -26,7 +26,7 @@ import workloads   # noqa: E402
 
 POINTS = ["entry", "arguments, lengths, list ids, query rows in", "first chunks requested (one kernel: draft rows done)",
           "chunk 0 landed", "chunk 1 landed", "chunk 2 landed", "chunk 3 landed", "chunk loop done",
-          "partials stored (issued)", "one kernel: stores acknowledged", "one kernel: arrival known",
+          "partials stored (issued)", "two kernels: lengths and list length in (scalar reads) | one kernel: stores acknowledged", "one kernel: arrival known",
           "one kernel: merged and stored (last workgroup of a tile)",
           "wavefront 0 starts to wait for chunk 0", "... for chunk 1 (done with chunk 0)", "... for chunk 2", "... for chunk 3"]
 
