@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--layers", type=int, default=8)
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--pending", type=int, default=0, help="partially verified tokens in front of the tree (keys only)")
     a = ap.parse_args()
     if not os.path.exists(os.environ["SPECPV_LIB"]):
         raise SystemExit("build the instrumented library first: python -m paper_2512_02337_amd.build --timeline")
@@ -47,9 +48,18 @@ def main():
         case = workloads.make_case(a.workload, seed=0, layer=layer, device=dev)
         kv = sp.KV(case["k"], case["v"], case["ctx_len"], case["B"], case["max_blocks"])
         tree = sp.Tree(case["q"], case["kd"], case["vd"], case["parent"])
+        ptree = tree
+        if a.pending > 0:   # the partial step then attends a chain of `pending` key-only nodes as well
+            g = torch.Generator(device=dev).manual_seed(1234)
+            shp = (case["k"].shape[0], a.pending, case["k"].shape[1], case["q"].shape[-1])
+            pk = torch.randn(shp, generator=g, device=dev).to(case["q"].dtype)
+            pv = torch.randn(shp, generator=g, device=dev).to(case["q"].dtype)
+            par = [sp.specpv_extend_parents(case["parent"][b].tolist(), a.pending) for b in range(case["k"].shape[0])]
+            ptree = sp.Tree(case["q"], torch.cat([pk, case["kd"]], 1).contiguous(), torch.cat([pv, case["vd"]], 1).contiguous(),
+                            torch.tensor(par, dtype=torch.int32, device=dev))
         cfg = sp.SelectCfg(case["ns"], case["nr"], case["k_blocks"], "mean")
         batch, hkv = case["k"].shape[0], case["k"].shape[1]
-        st = dict(kv=kv, tree=tree, cfg=cfg, kmax=torch.empty(kv.summary_shape(), dtype=case["q"].dtype, device=dev),
+        st = dict(kv=kv, tree=tree, ptree=ptree, cfg=cfg, kmax=torch.empty(kv.summary_shape(), dtype=case["q"].dtype, device=dev),
                   sel_idx=torch.empty((batch, hkv, cfg.n_sel), dtype=torch.int32, device=dev),
                   sel_count=torch.empty((batch, hkv), dtype=torch.int32, device=dev), out=torch.empty_like(case["q"]))
         st["kmin"] = torch.empty_like(st["kmax"])
@@ -64,7 +74,7 @@ def main():
     def step(record):
         for i, l in enumerate(layers):
             sp.specpv_debug_set_timeline(tl[i] if record else None)
-            sp.specpv_partial_verify_attn(l["kv"], l["tree"], l["sel_idx"], l["sel_count"], l["out"], None, ws)
+            sp.specpv_partial_verify_attn(l["kv"], l["ptree"], l["sel_idx"], l["sel_count"], l["out"], None, ws)
 
     for _ in range(5):
         step(False)
@@ -79,7 +89,7 @@ def main():
     sp.specpv_debug_set_timeline(None)
     n_wg = res[0].shape[0]
     res = np.stack([r for r in res if r.shape[0] == n_wg])
-    print("workload %s, route %d, %d workgroups per launch, %d launches read" % (a.workload, a.route, n_wg, res.shape[0]))
+    print("workload %s, route %d, %d pending tokens, %d workgroups per launch, %d launches read" % (a.workload, a.route, a.pending, n_wg, res.shape[0]))
     print("microseconds since the first workgroup's entry: median over workgroups and launches, 10th / 90th percentile")
     for i, name in enumerate(POINTS):
         col = res[:, :, i]
