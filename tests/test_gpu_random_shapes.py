@@ -75,3 +75,40 @@ def test_random_shape(gpu_lib, seed):
     run.refresh(stale=0)
     torch.cuda.synchronize()
     _check_attn(run, case, None, "seed %d full" % seed)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shape_with_pending_tokens(gpu_lib, seed):
+    """The same draws with a chain of partially verified tokens in front of the tree (keys only, Section 3.3):
+    the matrix-core kernels attend them as chunks behind the cache tokens, the vector-ALU kernel through the
+    combine; empty and one-token contexts, ragged batches, every group size."""
+    import oracle
+    from helpers import ATOL, with_pending
+    rnd = random.Random(5000 + seed)
+    cfg, _ = _draw(rnd)
+    cfg["M"] = min(cfg["M"], 96)
+    n_key = rnd.choice([1, 3, 16, 20, 31, 32, 33, 64][: 8 if cfg["M"] <= 64 else 6])
+    layout = rnd.choice(["bhtd", "bthd"])
+    say("case", seed, {k: cfg[k] for k in ("Hq", "Hkv", "D", "dtype", "ctx", "B", "M", "tree", "ns", "nr", "k")}, "pending", n_key, layout)
+    base = workloads.make_case(cfg, seed=seed)
+    case = workloads.to_device(with_pending(base, n_key, 900 + seed), "cuda")
+    run = GpuRun(gpu_lib, case, layout=layout, reduce="mean", last_node=n_key)
+    assert run.tree.n_key_only == n_key
+    run.summarize(); run.select(); run.attend()
+    torch.cuda.synchronize()
+    for full in (False, True):
+        if full:
+            run.out.zero_(); run.lse.zero_()
+            run.attend(None, None)
+            torch.cuda.synchronize()
+        out, lse = _to_np(run.out), _to_np(run.lse)
+        worst = 0.0
+        for b in range(case["batch"]):
+            o = workloads.oracle_views(case, b)
+            gi, gc = (None, None) if full else (run.sel_idx.cpu().numpy()[b], run.sel_count.cpu().numpy()[b])
+            O, LSE, _ = oracle.tree_attention(o["Q"], o["K"], o["V"], o["Kd"], o["Vd"], o["parent"], case["B"], gi, gc,
+                                              n_key_only=n_key)
+            worst = max(worst, np.abs(out[b] - O).max())
+            np.testing.assert_allclose(lse[b], LSE, atol=2e-5 if case["dtype"] == "f32" else 2e-3, rtol=1e-5)
+        say("   seed %d %s: max-abs err %.3g" % (seed, "every block" if full else "kept lists", worst))
+        assert worst <= ATOL[case["dtype"]]
