@@ -1038,7 +1038,7 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // ---- group variant: the query heads of a KV head in one workgroup --------------------------
 // For long token ranges.  The G x ceil(M / 32) blocks of 32 query rows that share a KV head are
 // dealt to workgroups of up to 8 wavefronts, one row block per wavefront (G = 4, M <= 64: one
-// workgroup of 8; G = 5: two workgroups of 5).  A workgroup owns (sequence, KV head, its row
+// workgroup of 8; G = 5: one workgroup of 10; more row blocks: two or more workgroups).  A workgroup owns (sequence, KV head, its row
 // blocks, KV split) and walks the split's chunks once for all of them: its W wavefronts share
 // ONE ring of four stages and each brings its share of a chunk's 16 DMA operations, so every
 // K / V byte is requested from memory exactly once per workgroup, whatever the caches do.

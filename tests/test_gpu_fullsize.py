@@ -128,7 +128,7 @@ def test_qwen14b_ragged_batch(gpu_lib):
     for b in range(case["batch"]):
         qh, O, lse = _oracle_attention_on_heads(case, b, [(2 * b + 1) % 8], lists[b])
         _compare(run, case, b, qh, O, lse, "seq %d partial" % b)
-    # full verification of the shortest and of the longest sequence (G = 5: two workgroups of five
+    # full verification of the shortest and of the longest sequence (G = 5: one workgroup of ten
     # wavefronts per KV head and split, many splits because the lengths differ)
     run.refresh(stale=-1)
     torch.cuda.synchronize()
