@@ -45,7 +45,9 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 
 constexpr int kOPitch = 132;         // floats per staged output row (128 + 4: conflict-free 16-byte writes)
-// One 32-token chunk in LDS: 8 KiB of K (row-major, 16-byte pieces XOR-swizzled by row & 7) and
+// One 32-token chunk in LDS: 8 KiB of K (row-major, 16-byte pieces XOR-swizzled by row & 15: the LDS has 64
+// banks, so the 16 lanes that a 16-byte read serves per cycle must cover all 16 pieces of a 256-byte bank row;
+// with row & 7 the operand reads ran at half the rate) and
 // the V rows in 8 pieces of 4 rows (tokens i, i+8, i+16, i+24 in piece i), 1088 bytes apart, for
 // the transposing LDS reads (see lds_read_v).
 constexpr int kVPiecePitch = 1088;
@@ -106,15 +108,16 @@ __device__ __forceinline__ void dma16(const char *gsrc, char *lds_dst)
     __builtin_amdgcn_global_load_lds((glb_void_ptr)gsrc, (lds_void_ptr)lds_dst, 16, 0, kKvAux);
 }
 
-// Four such operations 1 KiB apart on both sides: gbase is wavefront-uniform, the per-lane
-// byte offsets alternate between off_even (operations 0, 2) and off_odd (1, 3).  The
+// Four such operations 1 KiB apart on both sides (K rows 4 i .. 4 i + 3 for i = 0 .. 3, or 4 .. 7): gbase is
+// wavefront-uniform, row_off the lane's row (lane / 16) in bytes, sw0 its piece 16 * ((lane & 15) ^ (lane / 16));
+// operation i fetches the piece that the swizzle by row & 15 puts at the lane's place, sw0 ^ 64 i.  The
 // immediate offset of the instruction is added to the global and to the LDS address.
-__device__ __forceinline__ void dma16x4(const char *gbase, uint32_t off_even, uint32_t off_odd, char *lds_dst)
+__device__ __forceinline__ void dma16x4(const char *gbase, uint32_t row_off, uint32_t sw0, char *lds_dst)
 {
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 0, kKvAux);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 1024, kKvAux);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_even), (lds_void_ptr)lds_dst, 16, 2048, kKvAux);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + off_odd), (lds_void_ptr)lds_dst, 16, 3072, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + (row_off + sw0)), (lds_void_ptr)lds_dst, 16, 0, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + (row_off + (sw0 ^ 64u))), (lds_void_ptr)lds_dst, 16, 1024, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + (row_off + (sw0 ^ 128u))), (lds_void_ptr)lds_dst, 16, 2048, kKvAux);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)(gbase + (row_off + (sw0 ^ 192u))), (lds_void_ptr)lds_dst, 16, 3072, kKvAux);
 }
 
 // The LDS reads of staged K / V are written in assembly so that the compiler does not
@@ -138,26 +141,7 @@ __device__ __forceinline__ void lds_read_k(const uint32_t (&a)[8], uint4 (&k)[8]
         : "memory");
 }
 
-// The same with four address registers: the operand piece of k-step ks + 4 lies 128 bytes
-// behind that of k-step ks (the swizzle only touches the address bits below).
-__device__ __forceinline__ void lds_read_k4(const uint32_t (&a)[4], uint4 (&k)[8])
-{
-    asm volatile(
-        "ds_read_b128 %0, %8\n\t"
-        "ds_read_b128 %1, %9\n\t"
-        "ds_read_b128 %2, %10\n\t"
-        "ds_read_b128 %3, %11\n\t"
-        "ds_read_b128 %4, %8 offset:128\n\t"
-        "ds_read_b128 %5, %9 offset:128\n\t"
-        "ds_read_b128 %6, %10 offset:128\n\t"
-        "ds_read_b128 %7, %11 offset:128\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2]), "=&v"(k[3]), "=&v"(k[4]), "=&v"(k[5]), "=&v"(k[6]), "=&v"(k[7])
-        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3])
-        : "memory");
-}
-
-// Half of that: k-steps 4 h .. 4 h + 3 (OFF = 128 h).
+// Four k-steps (half of a chunk's K operands).
 template <int OFF> __device__ __forceinline__ void lds_read_k_half(const uint32_t (&a)[4], uint4 (&k)[4])
 {
     asm volatile(
@@ -453,12 +437,12 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     char *my_ring = ring + tg * (kStages * kStageBytes);
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)my_ring;
     // K tile in LDS: row-major, 256 B per token, the 16-byte pieces of row t stored at
-    // piece index (p ^ (t & 7)) so that the operand reads below (32 lanes, same piece,
-    // different rows) spread over all banks.  Operand piece of k-step ks: 2*ks + kg.
-    uint32_t kread[4];   // + stage * kStageBytes; k-step ks + 4 is 128 bytes behind k-step ks
+    // piece index (p ^ (t & 15)) so that the operand reads below (16 lanes per cycle, same piece,
+    // different rows) spread over all 64 banks.  Operand piece of k-step ks: 2*ks + kg.
+    uint32_t kread[4];   // + stage * kStageBytes; k-step ks + 4: the address XOR 128 (rows and stages start 256-byte aligned)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-        kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u)));
+        kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 15u)));
     const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
                            32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
 
@@ -467,7 +451,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
 
     const int r4 = lane >> 4, pos = lane & 15;
-    const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+    const uint32_t sw0 = 16u * (uint32_t)(pos ^ r4), vsw = 16u * (uint32_t)pos;   // K row 4 i + r4: piece pos ^ ((4 i + r4) & 15) = sw0 ^ 64 (i & 3)
     const uint32_t lane_row_off = (uint32_t)r4 * st2;
     constexpr int RPW = 8;  // rows each wavefront finishes in the epilogue
 
@@ -541,7 +525,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * stride;
-                dma16(kbase + (tv + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+                dma16(kbase + (tv + (sw0 ^ (64u * (uint32_t)(i & 3)))), dst + i * 1024);
             }
         } else {
 #pragma unroll
@@ -576,8 +560,8 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
                     // between consecutive operations (K: 1 KiB on both sides; V: 256 bytes, with the
                     // LDS base adjusted for the rest of the piece pitch)
                     if (rb == 0) {
-                        dma16x4(kb + row0, lane_row_off + sw_even, lane_row_off + sw_odd, dst);
-                        dma16x4(kb + row0 + 4096, lane_row_off + sw_even, lane_row_off + sw_odd, dst + 4096);
+                        dma16x4(kb + row0, lane_row_off, sw0, dst);
+                        dma16x4(kb + row0 + 4096, lane_row_off, sw0, dst + 4096);
                     } else {
                         const char *vsrc = vb + row0 + ((uint32_t)r4 * 2048u + vsw);
 #define SPECPV_VOP(i) __builtin_amdgcn_global_load_lds((glb_void_ptr)vsrc, (lds_void_ptr)(dstv + (i) * (kVPiecePitch - 256)), 16, (i) * 256, kKvAux)
@@ -588,7 +572,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
                 } else if (rb == 0) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
-                        dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + ((i & 1) ? sw_odd : sw_even)), dst + i * 1024);
+                        dma16(kb + row0 + (size_t)(4 * i) * st2 + (lane_row_off + (sw0 ^ (64u * (uint32_t)(i & 3)))), dst + i * 1024);
                 } else {
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
@@ -726,8 +710,9 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         const uint32_t vmask = vmask_st[stg];
         if (active) {
             const uint32_t soff = (uint32_t)stg * kStageBytes;
-            const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
-            lds_read_k4(ka, kf);
+            const uint32_t k0 = kread[0] + soff, k1 = kread[1] + soff, k2 = kread[2] + soff, k3 = kread[3] + soff;
+            const uint32_t ka[8] = {k0, k1, k2, k3, k0 ^ 128u, k1 ^ 128u, k2 ^ 128u, k3 ^ 128u};
+            lds_read_k<0>(ka, kf);
             lds_read_v(vread + soff, v);
         }
         __builtin_amdgcn_s_barrier();          // both wavefronts of the pair hold chunk i in registers
@@ -1050,7 +1035,7 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // merge: it only turns the accumulators into row-major partials.
 constexpr int kGroupStages = 4;   // a power of two
 constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
-static_assert(kStageBytes % 128 == 0, "the ten-wavefront variant derives K operand addresses by XOR: stages (and the ring, which starts the workgroup's LDS) must be 128-byte aligned");
+static_assert(kStageBytes % 256 == 0, "K operand addresses are derived by XOR with multiples of 32 below 256: stages (and the rings) must start 256-byte aligned");
 
 // W wavefronts per workgroup: 2, 4, 6, 8 or 10.  Ten (nine or ten row blocks: G = 5 with up to 64 nodes) means
 // three wavefronts on two of the SIMDs, i.e. at most 168 registers each: that variant does without the deferred
@@ -1121,10 +1106,10 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const uint32_t st2 = (uint32_t)s.st * 2u;
 
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ring;
-    uint32_t kread[4];   // + stage * kStageBytes; k-step ks + 4 is 128 bytes behind k-step ks
+    uint32_t kread[4];   // + stage * kStageBytes; k-step ks + 4: the address XOR 128
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-        kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 7u)));
+        kread[ks] = ring_addr + (uint32_t)n * 256u + (((uint32_t)(32 * ks + 16 * kg)) ^ (16u * ((uint32_t)n & 15u)));
     const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
                            32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
 
@@ -1177,13 +1162,13 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     int dst_off[NOPS];            // ... and where it lands in the stage
     {
         const int r4 = lane >> 4, pos = lane & 15;
-        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+        const uint32_t sw0 = 16u * (uint32_t)(pos ^ r4), vsw = 16u * (uint32_t)pos;
 #pragma unroll
         for (int t = 0; t < NOPS; ++t) {
             const int o = min(wave + W * t, 15), i = o & 7;
             if (o < 8) {
                 src_base[t] = kb;
-                src_off[t] = (uint32_t)(4 * i + r4) * st2 + ((i & 1) ? sw_odd : sw_even);
+                src_off[t] = (uint32_t)(4 * i + r4) * st2 + (sw0 ^ (64u * (uint32_t)(i & 3)));
                 dst_off[t] = i * 1024;
             } else {
                 src_base[t] = vb;
@@ -1198,14 +1183,14 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         int lane_o = lane;
         asm volatile("" : "+v"(lane_o));
         const int r4 = lane_o >> 4, pos = lane_o & 15;
-        const uint32_t sw_even = 16u * (uint32_t)(pos ^ r4), sw_odd = sw_even ^ 64u, vsw = 16u * (uint32_t)pos;
+        const uint32_t sw0 = 16u * (uint32_t)(pos ^ r4), vsw = 16u * (uint32_t)pos;
 #pragma unroll
         for (int t = 0; t < NOPS; ++t) {
             if (16 % W != 0 && t == NOPS - 1 && n_ops != NOPS) continue;
             const int o = wave + W * t, i = o & 7;
             if (o < 8) {
                 const uint32_t tv = (uint32_t)__shfl((int)tk, 4 * i + r4) * stride;
-                dma16(kbase + (tv + ((i & 1) ? sw_odd : sw_even)), dst + dst_off[t]);
+                dma16(kbase + (tv + (sw0 ^ (64u * (uint32_t)(i & 3)))), dst + dst_off[t]);
             } else {
                 const uint32_t tv = (uint32_t)__shfl((int)tk, 8 * r4 + i) * stride;
                 dma16(vbase + (tv + vsw), dst + dst_off[t]);
@@ -1327,7 +1312,8 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             for (int ks = 0; ks < 4; ++ks)
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kh[ks]), qf[ks], S, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            lds_read_k_half<128>(ka, kh);
+            const uint32_t kb4[4] = {ka0 ^ 128u, ka0 ^ 160u, ka0 ^ 192u, ka0 ^ 224u};
+            lds_read_k_half<0>(kb4, kh);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kh[ks]), qf[4 + ks], S, 0, 0, 0);
@@ -1335,8 +1321,9 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             uint4 kf[8];
             {
                 const uint32_t soff = (uint32_t)rs * kStageBytes;
-                const uint32_t ka[4] = {kread[0] + soff, kread[1] + soff, kread[2] + soff, kread[3] + soff};
-                lds_read_k4(ka, kf);
+                const uint32_t k0 = kread[0] + soff, k1 = kread[1] + soff, k2 = kread[2] + soff, k3 = kread[3] + soff;
+                const uint32_t ka[8] = {k0, k1, k2, k3, k0 ^ 128u, k1 ^ 128u, k2 ^ 128u, k3 ^ 128u};
+                lds_read_k<0>(ka, kf);
             }
             lds_read_v(vread + (uint32_t)rs * kStageBytes, v);
 #pragma unroll

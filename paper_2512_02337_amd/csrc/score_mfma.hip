@@ -33,8 +33,8 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
                                                                          int last_node, float *__restrict__ scores)
 {
     // the two summary tiles of this workgroup's 32 blocks: row-major, 256 B per block, the
-    // 16-byte pieces of row t stored at piece index p ^ (t & 7) so that the operand reads
-    // below (32 lanes, same piece, different rows) spread over all banks
+    // 16-byte pieces of row t stored at piece index p ^ (t & 15) so that the operand reads
+    // below (16 lanes per cycle, same piece, different rows) spread over all 64 banks
     __shared__ __attribute__((aligned(1024))) char tile[2 * TILES][8192];   // [tile][Kmax | Kmin]
     __shared__ float red[kScoreMaxWaves][64 * TILES];
     const int lane = threadIdx.x & 63, W = blockDim.x >> 6;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
         for (int d = wave; d < 16 * TILES; d += W) {
             const int i = d & 7, row = 4 * i + r4, t = d >> 4;
             const int blk = min(i0 + 32 * t + row, s.max_blocks - 1);
-            const char *src = (const char *)((d & 8) ? kmin : kmax) + ((arr_row0 + blk) * 128) * 2 + 16 * (pos ^ (row & 7));
+            const char *src = (const char *)((d & 8) ? kmin : kmax) + ((arr_row0 + blk) * 128) * 2 + 16 * (pos ^ (row & 15));
             __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile[d >> 3] + i * 1024), 16, 0, 2);   // streaming hint: read once
         }
     }
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
             bf16x8 bx[8], bn[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
-                const int off = (32 * ks + 16 * kg) ^ (16 * (n & 7));
+                const int off = (32 * ks + 16 * kg) ^ (16 * (n & 15));
                 bx[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(bxp + off));
                 bn[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(bnp + off));
             }
