@@ -516,6 +516,6 @@ int specpv_debug_set_route(int route)
     return SPECPV_OK;
 }
 
-int specpv_version(void) { return 200; }
+int specpv_version(void) { return 201; }
 
 }  // extern "C"
