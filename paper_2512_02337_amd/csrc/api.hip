@@ -209,12 +209,12 @@ static int run_attention(const Shape &s_in, int dtype, const int32_t *sel_idx, c
                        (size_t)s.batch * s.Hq * 2 * sizeof(unsigned long long) <= kArriveBytes;
     hipError_t e;
     if (fused) {
-        Partials p{w.part_o, w.part_ml, nsplit + 1, 0};
+        Partials p{w.part_o, w.part_ml, nsplit + 1, 0, nullptr};
         const FusedArgs f{out, lse, w.arrive, route == 3 ? 1 : 0, g_timeline};
         e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, nsplit, plan.kind, f, st);
         return e == hipSuccess ? SPECPV_OK : fail_hip(e);
     }
-    Partials p{w.part_o, w.part_ml, nsplit, plan.kind != kAttnGeneric ? 1 : 0};
+    Partials p{w.part_o, w.part_ml, nsplit, plan.kind != kAttnGeneric ? 1 : 0, g_timeline};
     const FusedArgs none{nullptr, nullptr, nullptr, 0, g_timeline};
     if (plan.kind != kAttnGeneric) e = launch_attn_ctx_mfma(s, sel_idx, sel_count, n_sel, p, nsplit, plan.kind, none, st);
     else e = launch_attn_ctx_generic(s, dtype, sel_idx, sel_count, n_sel, p, st);

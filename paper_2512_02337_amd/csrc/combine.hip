@@ -110,6 +110,17 @@ template <int CPL> __device__ __forceinline__ void load_partial_half(const float
 // when partially verified tokens stand in front of the tree as keys (every candidate's path then starts with
 // that whole chain; more registers, so only then).
 // HALF: the partials' O rows are fp16 and normalised (see Partials); else fp32 sums.
+#ifdef SPECPV_TIMELINE
+#define SPECPV_CSTAMP(i)                                                                                     \
+    do {                                                                                                     \
+        if (part.timeline && threadIdx.x == 0)                                                               \
+            part.timeline[(2048 + ((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (i)] = \
+                __builtin_amdgcn_s_memrealtime();                                                            \
+    } while (0)
+#else
+#define SPECPV_CSTAMP(i) do {} while (0)
+#endif
+
 template <typename T, int D, int NP, bool MULTI, int NB, bool HALF>
 __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, const void *a_q, const float *a_po,
                                                     const float *a_pml, int a_M, int a_Hq, int a_G, int a_nsplit,
@@ -118,6 +129,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
     // the leading scalar arguments repeat what the first round of reads needs; they can be preloaded into registers
     s.parent = a_parent; s.q = a_q; s.M = a_M; s.Hq = a_Hq; s.G = a_G;
     part.o = const_cast<float *>(a_po); part.ml = const_cast<float *>(a_pml); part.nsplit = a_nsplit;
+    SPECPV_CSTAMP(0);   // entry
     constexpr int CPL = D / 16;   // channels per lane: d = (lane & 15) * CPL + x
     typedef typename Chan<T, CPL>::Raw Raw;
     const int lane = threadIdx.x & 63;
@@ -169,6 +181,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
             a = pa < a ? pa : -1;   // a malformed parent[] (not strictly decreasing) ends the walk
         }
     }
+    SPECPV_CSTAMP(1);   // parents in, root path walked
     // ---- second (and last) round of reads: draft K / V of the first 8 nodes of the path ----
     auto pop = [&]() -> int {
         int a = -1;
@@ -228,6 +241,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
         }
     }
 
+    SPECPV_CSTAMP(2);   // context partials in and merged
     // ---- draft-tree segment: the node itself and its ancestors --------------------------
     float qv[CPL];
     Chan<T, CPL>::unpack(qraw, qv);
@@ -279,6 +293,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
         if (a8[4] >= 0) four(a8 + 4, kd8 + 4, vd8 + 4);
     }
 
+    SPECPV_CSTAMP(3);   // draft K / V rows in, tree segment done
     // ---- merge the two and store ---------------------------------------------------------
     const float m_all = fmaxf(m, m_ctx);
     const float wd = exp2f(m - m_all);
@@ -291,6 +306,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const int32_t *a_parent, c
     for (int x = 0; x < CPL; ++x) res[x] = (od[x] * wd + o[x] * wc) * inv;
     Chan<T, CPL>::store_stream(out, qrow + d0, res);
     if (lse && (lane & 15) == 0) lse[((int64_t)b * s.M + j) * s.Hq + h] = (m_all + log2f(den)) * kLn2;
+    SPECPV_CSTAMP(4);   // stored (issued)
 }
 
 template <typename T, int D>

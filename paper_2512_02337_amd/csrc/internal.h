@@ -49,6 +49,7 @@ struct Partials {
     float *ml;
     int nsplit;
     int o_half;
+    unsigned long long *timeline;   // instrumented builds (-DSPECPV_TIMELINE): the combine kernel's time stamps go to rows 2048.. of this buffer
 };
 __host__ __device__ constexpr int partial_pos(int c, int D)
 {

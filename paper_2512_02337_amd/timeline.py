@@ -78,14 +78,19 @@ def main():
 
     for _ in range(5):
         step(False)
-    res = []
+    res, cres = [], []
     for _ in range(a.reps):
         tl.zero_()
         step(True)
         torch.cuda.synchronize()
         for x in tl[len(layers) // 2:].cpu().numpy().astype(np.float64):
-            x = x[x[:, 0] > 0]   # workgroups that ran
-            res.append(np.where(x > 0, (x - x[:, 0].min()) / 100.0, np.nan))   # microseconds
+            xa, xc = x[:2048], x[2048:]   # attention kernel's workgroups, combine kernel's
+            xa = xa[xa[:, 0] > 0]   # workgroups that ran
+            t0 = xa[:, 0].min()
+            res.append(np.where(xa > 0, (xa - t0) / 100.0, np.nan))   # microseconds
+            xc = xc[xc[:, 0] > 0]
+            if xc.shape[0]:
+                cres.append(np.where(xc > 0, (xc - t0) / 100.0, np.nan))
     sp.specpv_debug_set_timeline(None)
     n_wg = res[0].shape[0]
     res = np.stack([r for r in res if r.shape[0] == n_wg])
@@ -97,6 +102,16 @@ def main():
             continue
         print("%2d %-58s %6.2f   %6.2f  %6.2f" % (i, name, np.nanmedian(col), np.nanpercentile(col, 10), np.nanpercentile(col, 90)))
     print("last stamp of a launch, median over launches: %.2f" % np.median(np.nanmax(res, axis=(1, 2))))
+    if cres:
+        cr = np.stack([r for r in cres if r.shape[0] == cres[0].shape[0]])
+        print("combine kernel, %d workgroups per launch: microseconds since the ATTENTION kernel's first workgroup entered" % cr.shape[1])
+        for i, name in enumerate(["entry", "parents in, root path walked", "context partials in and merged",
+                                  "draft K / V rows in, tree segment done", "stored (issued)"]):
+            col = cr[:, :, i]
+            if np.all(np.isnan(col)):
+                continue
+            print("%2d %-58s %6.2f   %6.2f  %6.2f" % (i, name, np.nanmedian(col), np.nanpercentile(col, 10), np.nanpercentile(col, 90)))
+        print("last stamp of the combine, median over launches: %.2f" % np.median(np.nanmax(cr, axis=(1, 2))))
 
 
 if __name__ == "__main__":
