@@ -120,7 +120,9 @@ typedef struct specpv_select_cfg {
  * specpv_block_summarize is used.
  * A workspace must be ZERO-FILLED ONCE before its first use (hipMemset, torch.zeros): its first
  * 64 KiB hold the arrival words through which the workgroups of the single-kernel route of
- * specpv_partial_verify_attn (specpv_debug_set_route) find out which of them finishes a row tile.  Every call leaves them zero again, so one fill at
+ * specpv_partial_verify_attn (specpv_debug_set_route) find out which of them finishes a row tile, and
+ * those of the one-launch route of the selection (specpv_debug_set_select_route) which of them selects.
+ * Every call leaves them zero again, so one fill at
  * allocation is enough, whatever shapes use the workspace afterwards.  A call that is given
  * words that are not zero computes garbage (it cannot notice). */
 size_t specpv_workspace_bytes(const specpv_kv *kv, const specpv_tree *tree, const specpv_select_cfg *cfg);
@@ -142,7 +144,9 @@ int specpv_block_summarize(const specpv_kv *kv, int32_t blk_begin, int32_t blk_e
  *   every block if nb_b <= ns + k + nr.
  * sel_idx   [batch, Hkv, n_sel] int32, n_sel = ns + k + nr + n_extra_slots, ascending, padded with -1.
  * sel_count [batch, Hkv] int32.
- * scores    optional [batch, Hkv, max_blocks] fp32 (NULL: kept in the workspace). */
+ * scores    optional [batch, Hkv, max_blocks] fp32 (NULL: kept in the workspace).
+ * workspace may be NULL when scores is given; the one-launch route of specpv_debug_set_select_route
+ * uses the arrival words of a workspace of 64 KiB or more (zero before the call, zero again after it). */
 int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree,
                          const void *kmax, const void *kmin, const specpv_select_cfg *cfg,
                          int32_t *sel_idx, int32_t *sel_count, float *scores,
@@ -304,6 +308,19 @@ int specpv_commit_accepted_layers(const specpv_kv *const *kv, void *const *buf_k
  *      workgroups of a tile ran on different XCDs: it recomputes the tile by itself
  * All give results within the documented bars.  Returns SPECPV_OK or SPECPV_EINVAL. */
 int specpv_debug_set_route(int route);
+
+/* Testing and measuring aid, process-wide: how specpv_select_blocks and the refresh of
+ * specpv_full_verify_refresh run scoring + selection (Section 3.2, eq. 2-3 and the top-k).
+ *   0  the library's choice (currently two launches)
+ *   1  one launch where that is possible, two elsewhere: every scoring workgroup counts itself in on
+ *      arrival words of its (sequence, KV head) at the head of the workspace, and the last one to
+ *      arrive selects (no workgroup waits for another; the words are zero again afterwards).
+ *      Possible where the matrix-core scoring kernel applies (bf16, head dim 128), the tree has more
+ *      than 96 query rows per KV head, max_blocks <= 4096, batch * n_kv_heads <= 910 and the call
+ *      has a workspace of 64 KiB or more
+ *   2  two launches: scoring, then selection
+ * Both give the same lists and scores, bit for bit.  Returns SPECPV_OK or SPECPV_EINVAL. */
+int specpv_debug_set_select_route(int route);
 
 /* Measuring aid, process-wide.  A library built with -DSPECPV_TIMELINE (`python -m paper_2512_02337_amd.build
  * --timeline` makes libspecpv_timeline.so) has every workgroup of the partial-verify attention kernel store 16

@@ -23,7 +23,8 @@ MODE_FULL, MODE_PARTIAL, MODE_REFRESH = 0, 1, 2
 EXPORTS = ["specpv_workspace_bytes", "specpv_block_summarize", "specpv_select_blocks",
            "specpv_partial_verify_attn", "specpv_partial_verify_attn_static", "specpv_full_verify_refresh", "specpv_gather_blocks", "specpv_select_mode",
            "specpv_extend_parents", "specpv_commit_accepted", "specpv_commit_accepted_layers", "specpv_strerror",
-           "specpv_last_hip_error", "specpv_version", "specpv_debug_set_route", "specpv_debug_set_timeline"]
+           "specpv_last_hip_error", "specpv_version", "specpv_debug_set_route", "specpv_debug_set_select_route",
+           "specpv_debug_set_timeline"]
 
 
 class SpecPVError(RuntimeError):
@@ -106,6 +107,8 @@ def load():
                                                   P(vp), P(vp), P(_Lists), vp, vp, sz, vp]
     lib.specpv_debug_set_route.restype = ctypes.c_int
     lib.specpv_debug_set_route.argtypes = [ctypes.c_int]
+    lib.specpv_debug_set_select_route.restype = ctypes.c_int
+    lib.specpv_debug_set_select_route.argtypes = [ctypes.c_int]
     lib.specpv_strerror.restype = ctypes.c_char_p
     lib.specpv_strerror.argtypes = [ctypes.c_int]
     lib.specpv_last_hip_error.restype = ctypes.c_char_p
@@ -439,6 +442,10 @@ def specpv_debug_set_timeline(buf):
 
 def specpv_debug_set_route(route):
     _check(load().specpv_debug_set_route(int(route)))
+
+
+def specpv_debug_set_select_route(route):
+    _check(load().specpv_debug_set_select_route(int(route)))
 
 
 def specpv_strerror(status):

@@ -247,16 +247,28 @@ static hipError_t static_scratch(void **out)
     return hipSuccess;
 }
 
+// Process-wide choice between one and two launches for scoring + selection (a testing aid, see
+// specpv_debug_set_select_route).
+static int g_select_route = 0;
+
+// arrive: the zeroed arrival words at the head of a workspace, or nullptr where the caller gave none
 static int run_select(const Shape &s, int dtype, const specpv_tree *tree, const void *kmax, const void *kmin,
                       const specpv_select_cfg *cfg, int32_t *sel_idx, int32_t *sel_count, float *scores,
-                      hipStream_t st)
+                      unsigned long long *arrive, hipStream_t st)
 {
+    const int n_row = cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks + cfg->n_extra_slots;
+    const TopkArgs sel{cfg->n_sink_blocks, cfg->n_recent_blocks, cfg->k_blocks, n_row, sel_idx, sel_count};
+    // One launch (the last scoring workgroup of a (sequence, KV head) selects) only on request: it is the
+    // slower of the two.  Measured per call at one 128K sequence 18.8 against 16.6 us, at 16K 11.0 against
+    // 10.9, for a ragged batch of four 41.4 against 34.6: counting 64 workgroups in costs about what a launch
+    // costs, and the last workgroup then starts its selection with cold reads like a fresh kernel would.
+    const bool one = arrive && __atomic_load_n(&g_select_route, __ATOMIC_RELAXED) == 1 && score_select_supported(s, dtype);
     // the scoring kernels count query rows: node last_node is row last_node - n_key_only
     hipError_t e = launch_scores(s, dtype, kmax, kmin, (int)cfg->reduce, tree->last_node - tree->n_key_only,
-                                 (int)cfg->score, scores, st);
+                                 (int)cfg->score, scores, one ? &sel : nullptr, one ? arrive : nullptr, st);
     if (e != hipSuccess) return fail_hip(e);
-    const int n_row = cfg->n_sink_blocks + cfg->k_blocks + cfg->n_recent_blocks + cfg->n_extra_slots;
-    e = launch_topk(s, scores, cfg->n_sink_blocks, cfg->n_recent_blocks, cfg->k_blocks, n_row, sel_idx, sel_count, st);
+    if (one) return SPECPV_OK;
+    e = launch_topk(s, scores, sel.ns, sel.nr, sel.k, n_row, sel_idx, sel_count, st);
     if (e != hipSuccess) return fail_hip(e);
     return SPECPV_OK;
 }
@@ -306,12 +318,13 @@ int specpv_select_blocks(const specpv_kv *kv, const specpv_tree *tree, const voi
     if (((uintptr_t)kmax | (uintptr_t)kmin) & 15) return SPECPV_EINVAL;
     const Shape s = make_shape(kv, tree);
     if (!scores) {
-        // behind the arrival words, which stay zero
+        // behind the arrival words
         const size_t need = kArriveBytes + align_up((size_t)s.batch * s.Hkv * s.max_blocks * sizeof(float));
         if (!workspace || workspace_bytes < need) return SPECPV_EWORKSPACE;
         scores = (float *)((char *)workspace + kArriveBytes);
     }
-    return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores, (hipStream_t)stream);
+    unsigned long long *arrive = workspace && workspace_bytes >= kArriveBytes ? (unsigned long long *)workspace : nullptr;
+    return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores, arrive, (hipStream_t)stream);
 }
 
 int specpv_partial_verify_attn(const specpv_kv *kv, const specpv_tree *tree, const int32_t *sel_idx,
@@ -375,7 +388,7 @@ int specpv_full_verify_refresh(const specpv_kv *kv, const specpv_tree *tree, voi
     }
     rc = run_attention(s, kv->dtype, nullptr, nullptr, 0, out, lse, workspace, workspace_bytes, st);
     if (rc != SPECPV_OK) return rc;
-    return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores ? scores : w.scores, st);
+    return run_select(s, kv->dtype, tree, kmax, kmin, cfg, sel_idx, sel_count, scores ? scores : w.scores, w.arrive, st);
 }
 
 int specpv_gather_blocks(const specpv_kv *kv, const int32_t *sel_idx, const int32_t *sel_count, int32_t n_sel,
@@ -516,6 +529,13 @@ int specpv_debug_set_route(int route)
     return SPECPV_OK;
 }
 
-int specpv_version(void) { return 201; }
+int specpv_debug_set_select_route(int route)
+{
+    if (route < 0 || route > 2) return SPECPV_EINVAL;
+    __atomic_store_n(&g_select_route, route, __ATOMIC_RELAXED);
+    return SPECPV_OK;
+}
+
+int specpv_version(void) { return 202; }
 
 }  // extern "C"

@@ -134,9 +134,19 @@ __device__ __forceinline__ float wave_sum(float x) {
 // ---- launchers (each returns the hipError_t of its launches) ----
 hipError_t launch_summarize(const Shape &s, int dtype, int blk_begin, int blk_end,
                             void *kmax, void *kmin, hipStream_t st);
-// kind: SPECPV_SCORE_EQ2 or SPECPV_SCORE_CHANNEL_BOUND
+// One selection: kept-block lists of n_row entries (>= ns + k + nr; the rest is padding for later
+// commits), ascending, -1 behind the count.
+struct TopkArgs {
+    int ns, nr, k, n_row;
+    int32_t *sel_idx, *sel_count;
+};
+// kind: SPECPV_SCORE_EQ2 or SPECPV_SCORE_CHANNEL_BOUND.  sel != nullptr: the selection runs in the same
+// launch; only where score_select_supported() holds, with arrive pointing to the kArriveBytes of zeroed
+// arrival words at the head of a workspace (zero again when the launch has finished).
+bool score_select_supported(const Shape &s, int dtype);
 hipError_t launch_scores(const Shape &s, int dtype, const void *kmax, const void *kmin,
-                         int reduce, int last_node, int kind, float *scores, hipStream_t st);
+                         int reduce, int last_node, int kind, float *scores, const TopkArgs *sel,
+                         unsigned long long *arrive, hipStream_t st);
 // n_row: entries per list row (>= ns + k + nr; the rest is padding for later commits)
 hipError_t launch_topk(const Shape &s, const float *scores, int ns, int nr, int k, int n_row,
                        int32_t *sel_idx, int32_t *sel_count, hipStream_t st);

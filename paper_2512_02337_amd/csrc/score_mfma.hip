@@ -10,7 +10,12 @@
 // lane-local.  All reads of a wavefront are issued at once (one round trip); the
 // wavefronts' partial results meet in LDS.  The sum order is the same for every block, so
 // identical blocks get bit-identical scores wherever they sit.
+//
+// The same launch can do the selection as well: every workgroup of a (sequence, KV head)
+// counts itself in when its scores are stored, and the one that finds itself last runs the
+// top-k over the scores of all of them (no workgroup waits for another).
 #include "internal.h"
+#include "topk.h"
 
 namespace specpv {
 
@@ -27,10 +32,12 @@ typedef const __attribute__((address_space(1))) void *glb_void_ptr;
 // products as well: max(q, 0) . Kmax + min(q, 0) . Kmin, accumulated into one tile.
 // TILES tiles of 32 blocks per workgroup: the query rows are fetched once for all of them (for
 // batches, where the workgroups are many and the repeated query reads are most of the traffic).
-template <bool BOUND, int TILES>
-__global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s, const uint16_t *__restrict__ kmax,
-                                                                         const uint16_t *__restrict__ kmin, int reduce,
-                                                                         int last_node, float *__restrict__ scores)
+// ACROSS: the scores are read by another workgroup of this launch: agent-scope stores, which go
+// past the caches that are private to a part of the chip.
+template <bool BOUND, int TILES, bool ACROSS>
+__device__ __forceinline__ void score_tiles(const Shape &s, const uint16_t *__restrict__ kmax,
+                                            const uint16_t *__restrict__ kmin, int reduce, int last_node,
+                                            float *__restrict__ scores)
 {
     // the two summary tiles of this workgroup's 32 blocks: row-major, 256 B per block, the
     // 16-byte pieces of row t stored at piece index p ^ (t & 15) so that the operand reads
@@ -48,7 +55,7 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
     if (nb > s.max_blocks) nb = s.max_blocks;
     // in a batch the grid covers the longest sequence: workgroups past the end of a shorter one leave
     // at once (there the wait for the length is cheaper than their reads)
-    if (s.batch > 1 && i0 >= nb) return;
+    if (s.batch > 1 && i0 >= nb) return;   // (only out of this function: the workgroup still counts itself in)
 
     // Summary rows go from memory straight into LDS (16 DMA operations of 1 KiB shared by the
     // wavefronts; operation d brings rows 4*(d&7) .. +3 of Kmax (d < 8) or Kmin, one 256-byte
@@ -152,13 +159,74 @@ __global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s
     else if (reduce == SPECPV_REDUCE_MEAN) out = (a + other) / (float)R;
     else out = (a + other) / (float)s.G;
     const int blk = i0 + 32 * t + n;
-    if (kg == 0 && blk < nb) scores[((int64_t)b * s.Hkv + g) * s.max_blocks + blk] = out;
+    if (kg == 0 && blk < nb) {
+        float *dst = scores + ((int64_t)b * s.Hkv + g) * s.max_blocks + blk;
+        if (ACROSS) __hip_atomic_store((uint32_t *)dst, __float_as_uint(out), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *dst = out;
+    }
+}
+
+// P = 0: scores only.  P = 4, 8, 16: scores, then the selection over lists of up to 256 * P blocks
+// by the last workgroup of each (sequence, KV head) to get here (workgroups of at least 256 threads).
+// Arrival is counted on two levels, because agent-scope atomics on one address are executed one
+// after the other (64 workgroups on one word: + 4.4 us; 8 + 8: + 0.9 us): the workgroups of a
+// (sequence, KV head) are dealt to eight groups by blockIdx.x % 8, the last of a group counts
+// the group in on the pair's own word.  Pair p = b * Hkv + g owns the words arrive[(9 p + i) * wstride],
+// i = 0 for the pair, 1 + j for group j; all are zero before the launch, and whoever finds a count
+// complete sets it back to zero.
+template <bool BOUND, int TILES, int P>
+__global__ __launch_bounds__(64 * kScoreMaxWaves) void score_mfma_kernel(Shape s, const uint16_t *__restrict__ kmax,
+                                                                         const uint16_t *__restrict__ kmin, int reduce,
+                                                                         int last_node, float *__restrict__ scores,
+                                                                         TopkArgs a, unsigned long long *arrive, int wstride)
+{
+    score_tiles<BOUND, TILES, P != 0>(s, kmax, kmin, reduce, last_node, scores);
+    if constexpr (P != 0) {
+        __shared__ TopkLds lds;
+        __shared__ int is_last;
+        const int g = blockIdx.y, b = blockIdx.z;
+        // A store is counted as done (vmcnt) when it has been acknowledged at the scope it was issued
+        // with; the counters below are only touched after that, and the last workgroup only reads the
+        // scores after it has seen the full counts: no further fence is needed.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's score stores are out
+        __syncthreads();                      // ... and so are everybody else's
+        if (threadIdx.x == 0) {
+            unsigned long long *pair = arrive + ((int64_t)b * s.Hkv + g) * 9 * wstride;
+            const int j = blockIdx.x & 7;
+            unsigned long long *group = pair + (int64_t)(1 + j) * wstride;
+            const unsigned long long n_j = (gridDim.x - j + 7) >> 3;     // workgroups with blockIdx.x % 8 == j
+            const unsigned long long n_groups = gridDim.x < 8 ? gridDim.x : 8;
+            bool last = false;
+            if (__hip_atomic_fetch_add(group, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull == n_j) {
+                __hip_atomic_store(group, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__hip_atomic_fetch_add(pair, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull == n_groups) {
+                    __hip_atomic_store(pair, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    last = true;
+                }
+            }
+            is_last = last ? 1 : 0;
+        }
+        __syncthreads();
+        if (!is_last) return;
+        topk_fast_body<P, true>(lds, scores, s.ctx_len, s.B, s.max_blocks, s.Hkv, g, b, a);
+    }
 }
 
 bool score_mfma_supported(const Shape &s, int dtype) { return dtype == SPECPV_BF16 && s.D == 128; }
 
+bool score_select_supported(const Shape &s, int dtype)
+{
+    // the selection needs 256 threads, lists of at most 4096 blocks and nine arrival words per (sequence, KV head)
+    const int row_tiles = (s.M * s.G + 31) / 32;
+    return score_mfma_supported(s, dtype) && row_tiles >= 4 && s.max_blocks <= 256 * 16 &&
+           (size_t)s.batch * s.Hkv * 9 * sizeof(unsigned long long) <= kArriveBytes;
+}
+
+// sel != nullptr: the selection runs in the same launch (score_select_supported(s, dtype) holds and
+// arrive points to zeroed words)
 hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin, int reduce,
-                              int last_node, int kind, float *scores, hipStream_t st)
+                              int last_node, int kind, float *scores, const TopkArgs *sel,
+                              unsigned long long *arrive, hipStream_t st)
 {
     // one wavefront per block of 32 query rows; T tiles per workgroup need T wavefronts to finish them
     const int row_tiles = (s.M * s.G + 31) / 32;
@@ -169,14 +237,22 @@ hipError_t launch_scores_mfma(const Shape &s, const void *kmax, const void *kmin
     const int64_t wgs1 = (int64_t)tiles1 * s.Hkv * s.batch, cus = device_cu_count();
     const int T = (row_tiles >= 4 && wgs1 >= 8 * cus) ? 4 : ((row_tiles >= 2 && wgs1 >= 4 * cus) ? 2 : 1);
     dim3 grid((tiles1 + T - 1) / T, s.Hkv, s.batch), block(64 * (row_tiles < kScoreMaxWaves ? row_tiles : kScoreMaxWaves));
-#define SPECPV_LAUNCH(BOUND, TILES) \
-    hipLaunchKernelGGL((score_mfma_kernel<BOUND, TILES>), grid, block, 0, st, s, (const uint16_t *)kmax, \
-                       (const uint16_t *)kmin, reduce, last_node, scores)
+    const int P = !sel ? 0 : (s.max_blocks <= 256 * 4 ? 4 : (s.max_blocks <= 256 * 8 ? 8 : 16));
+    const TopkArgs a = sel ? *sel : TopkArgs{0, 0, 0, 0, nullptr, nullptr};
+    // every arrival word on a 128-byte line of its own where the region is large enough for that
+    const int wstride = (size_t)s.batch * s.Hkv * 9 * 128 <= kArriveBytes ? 16 : 1;
+#define SPECPV_LAUNCH(BOUND, TILES, PP) \
+    hipLaunchKernelGGL((score_mfma_kernel<BOUND, TILES, PP>), grid, block, 0, st, s, (const uint16_t *)kmax, \
+                       (const uint16_t *)kmin, reduce, last_node, scores, a, arrive, wstride)
+#define SPECPV_LAUNCH_P(BOUND, TILES) \
+    do { if (P == 0) SPECPV_LAUNCH(BOUND, TILES, 0); else if (P == 4) SPECPV_LAUNCH(BOUND, TILES, 4); \
+         else if (P == 8) SPECPV_LAUNCH(BOUND, TILES, 8); else SPECPV_LAUNCH(BOUND, TILES, 16); } while (0)
     if (kind == SPECPV_SCORE_CHANNEL_BOUND) {
-        if (T == 4) SPECPV_LAUNCH(true, 4); else if (T == 2) SPECPV_LAUNCH(true, 2); else SPECPV_LAUNCH(true, 1);
+        if (T == 4) SPECPV_LAUNCH_P(true, 4); else if (T == 2) SPECPV_LAUNCH_P(true, 2); else SPECPV_LAUNCH_P(true, 1);
     } else {
-        if (T == 4) SPECPV_LAUNCH(false, 4); else if (T == 2) SPECPV_LAUNCH(false, 2); else SPECPV_LAUNCH(false, 1);
+        if (T == 4) SPECPV_LAUNCH_P(false, 4); else if (T == 2) SPECPV_LAUNCH_P(false, 2); else SPECPV_LAUNCH_P(false, 1);
     }
+#undef SPECPV_LAUNCH_P
 #undef SPECPV_LAUNCH
     return hipGetLastError();
 }
