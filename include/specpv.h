@@ -251,9 +251,9 @@ typedef struct specpv_lists {
     int32_t n_sel;
 } specpv_lists;
 
-/* Section 3.2 (the buffer: "invalid tokens can be removed once verification is completed")
- * and Section 3.3 ("we remove the invalid tokens from both the partial and the full KV
- * cache").  accepted [batch, max_accept] int32 (device): the candidates on the accepted
+/* Section 3.2 (the buffer holds the candidates' K/V until verification has decided which of
+ * them survive) and Section 3.3 (after a full verification the rejected candidates leave both
+ * caches).  accepted [batch, max_accept] int32 (device): the candidates on the accepted
  * path as indices 0 .. M_tree-1 in increasing order; n_accepted [batch] (device).
  *   mode PARTIAL: the accepted candidates' K/V rows join the pending tokens (the buffer is
  *     compacted: everything else of this step's candidates is dropped);
@@ -261,8 +261,8 @@ typedef struct specpv_lists {
  *   mode FULL / REFRESH: the pending tokens' rows, then the accepted candidates' rows, are
  *     appended to the cache at tokens L_b, L_b + 1, ...; L_b grows by their number, at most to
  *     max_blocks * B; n_pending_b = 0; the summaries (eq. 1) of every block that received a
- *     token are recomputed (kmax == NULL: skipped); and, Section 3.3 ("the local window is
- *     updated"), with lists != NULL every block that received a token joins each KV head's
+ *     token are recomputed (kmax == NULL: skipped); and, as Section 3.3 has the local window
+ *     follow the sequence's end, with lists != NULL every block that received a token joins each KV head's
  *     list behind its last entry unless it is that entry already (the ragged last block of the
  *     local window), so that the committed tokens stay visible to the partial steps that follow.
  *     A row of n_sel entries needs n_extra_slots >= ceil((pending_cap + max_accept) / B) + 1

@@ -1,6 +1,6 @@
-// KV side of what follows a verify step (Section 3.2: the buffer keeps the candidates' K/V
-// so that invalid tokens can be removed once verification is completed; Section 3.3: a
-// full verification moves the partially verified tokens into the cache).  Pure data
+// KV side of what follows a verify step (Section 3.2: the candidates' K/V wait in the buffer
+// until verification has decided which of them survive; Section 3.3: a full verification
+// moves the partially verified tokens into the cache).  Pure data
 // movement of at most a few dozen rows per (sequence, KV head), then the block summaries
 // (eq. 1) of the blocks that received tokens.
 #include "internal.h"
