@@ -325,7 +325,10 @@ int specpv_debug_set_select_route(int route);
 /* Measuring aid, process-wide.  A library built with -DSPECPV_TIMELINE (`python -m paper_2512_02337_amd.build
  * --timeline` makes libspecpv_timeline.so) has every workgroup of the partial-verify attention kernel store 16
  * 64-bit readings of the 100 MHz real-time counter at fixed points of its course to
- * buf[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + i] (device memory, NULL = off);
+ * buf[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + i] (device memory, 4096 rows of 16 words, NULL = off);
+ * the combine kernel writes rows 2048 + workgroup, and rows 3072 + workgroup receive three words per attention
+ * workgroup: core cycles (s_memtime), 10 ns ticks and chunks of its life, from which the core clock follows.
+ * The kernel for long token ranges (full verification) writes only those three words, to row workgroup.
  * paper_2512_02337_amd/timeline.py names the points and prints their medians.  A regular build takes no
  * stamps and answers a non-NULL buf with SPECPV_EINVAL. */
 int specpv_debug_set_timeline(void *buf);

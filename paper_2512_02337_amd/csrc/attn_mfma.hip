@@ -33,6 +33,7 @@
 // down, when it has many (full verification of a long context): there a workgroup serves all
 // query heads of a KV head.
 #include "internal.h"
+#include <type_traits>
 
 namespace specpv {
 
@@ -164,29 +165,32 @@ template <int OFF> __device__ __forceinline__ void lds_read_k_half(const uint32_
 // tokens 16*ks2 + 8*hf + 4*kg + 0..3.  The four rows of a quad sit in four different V pieces,
 // 1088 bytes apart, i.e. 64 bytes apart modulo the bank cycle: no bank conflicts.
 // v[(ks2 * 4 + j) * 2 + hf]; addr = piece (4*kg + (s >> 2)), byte 32 * (group & 1) + 8 * (s & 3).
+// OFF: a constant byte offset (a ring stage), added by the instructions themselves.
+template <int OFF = 0>
 __device__ __forceinline__ void lds_read_v(uint32_t addr, uint2 (&v)[16])
 {
+    static_assert(OFF >= 0 && OFF + 960 < 65536, "the offset field has 16 bits");
     asm volatile(
-        "ds_read_b64_tr_b16 %0, %16 offset:0\n\t"
-        "ds_read_b64_tr_b16 %1, %16 offset:256\n\t"
-        "ds_read_b64_tr_b16 %2, %16 offset:64\n\t"
-        "ds_read_b64_tr_b16 %3, %16 offset:320\n\t"
-        "ds_read_b64_tr_b16 %4, %16 offset:128\n\t"
-        "ds_read_b64_tr_b16 %5, %16 offset:384\n\t"
-        "ds_read_b64_tr_b16 %6, %16 offset:192\n\t"
-        "ds_read_b64_tr_b16 %7, %16 offset:448\n\t"
-        "ds_read_b64_tr_b16 %8, %16 offset:512\n\t"
-        "ds_read_b64_tr_b16 %9, %16 offset:768\n\t"
-        "ds_read_b64_tr_b16 %10, %16 offset:576\n\t"
-        "ds_read_b64_tr_b16 %11, %16 offset:832\n\t"
-        "ds_read_b64_tr_b16 %12, %16 offset:640\n\t"
-        "ds_read_b64_tr_b16 %13, %16 offset:896\n\t"
-        "ds_read_b64_tr_b16 %14, %16 offset:704\n\t"
-        "ds_read_b64_tr_b16 %15, %16 offset:960\n\t"
+        "ds_read_b64_tr_b16 %0, %16 offset:%17\n\t"
+        "ds_read_b64_tr_b16 %1, %16 offset:%17+256\n\t"
+        "ds_read_b64_tr_b16 %2, %16 offset:%17+64\n\t"
+        "ds_read_b64_tr_b16 %3, %16 offset:%17+320\n\t"
+        "ds_read_b64_tr_b16 %4, %16 offset:%17+128\n\t"
+        "ds_read_b64_tr_b16 %5, %16 offset:%17+384\n\t"
+        "ds_read_b64_tr_b16 %6, %16 offset:%17+192\n\t"
+        "ds_read_b64_tr_b16 %7, %16 offset:%17+448\n\t"
+        "ds_read_b64_tr_b16 %8, %16 offset:%17+512\n\t"
+        "ds_read_b64_tr_b16 %9, %16 offset:%17+768\n\t"
+        "ds_read_b64_tr_b16 %10, %16 offset:%17+576\n\t"
+        "ds_read_b64_tr_b16 %11, %16 offset:%17+832\n\t"
+        "ds_read_b64_tr_b16 %12, %16 offset:%17+640\n\t"
+        "ds_read_b64_tr_b16 %13, %16 offset:%17+896\n\t"
+        "ds_read_b64_tr_b16 %14, %16 offset:%17+704\n\t"
+        "ds_read_b64_tr_b16 %15, %16 offset:%17+960\n\t"
         "s_waitcnt lgkmcnt(0)"
         : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]),
           "=&v"(v[8]), "=&v"(v[9]), "=&v"(v[10]), "=&v"(v[11]), "=&v"(v[12]), "=&v"(v[13]), "=&v"(v[14]), "=&v"(v[15])
-        : "v"(addr)
+        : "v"(addr), "n"(OFF)
         : "memory");
 }
 
@@ -342,8 +346,23 @@ constexpr int kXccBits = 7;
         if (f.timeline && threadIdx.x == 0 && !REDO)                                                          \
             f.timeline[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (i)] = __builtin_amdgcn_s_memrealtime(); \
     } while (0)
+// core clock against real time over a workgroup's life: cycles, 10 ns ticks and the number of chunks go to
+// words 0 .. 2 of row ROW of the stamp buffer (the real-time counter runs at 100 MHz whatever the chip does,
+// s_memtime counts core cycles)
+#define SPECPV_CLOCKS_BEGIN const unsigned long long clk0_ = clock64(), rt0_ = __builtin_amdgcn_s_memrealtime()
+#define SPECPV_CLOCKS_END(TL, ROW, NCH)                                                                       \
+    do {                                                                                                      \
+        if ((TL) && threadIdx.x == 0 && (size_t)(ROW) < 4096) {                                               \
+            unsigned long long *t_ = (TL) + (size_t)(ROW) * 16;                                               \
+            t_[0] = clock64() - clk0_;                                                                        \
+            t_[1] = __builtin_amdgcn_s_memrealtime() - rt0_;                                                  \
+            t_[2] = (unsigned long long)(NCH);                                                                \
+        }                                                                                                     \
+    } while (0)
 #else
 #define SPECPV_STAMP(i) do {} while (0)
+#define SPECPV_CLOCKS_BEGIN do {} while (0)
+#define SPECPV_CLOCKS_END(TL, ROW, NCH) do {} while (0)
 #endif        // per-XCC arrival count (splits <= 64)
 
 // One pass over the token ranges of split `sp0` of `ns_eff` splits.  REDO = false: the ordinary pass of
@@ -363,6 +382,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     float *obuf = (float *)(lds_raw + 2048); // [4][64][kOPitch], reuses the ring after the main loop
     constexpr bool redo = REDO;
     const int sp = sp0;
+    SPECPV_CLOCKS_BEGIN;
     SPECPV_STAMP(0);   // entry
 
     // ---- which piece of work is this workgroup -------------------------------------
@@ -713,7 +733,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
             const uint32_t k0 = kread[0] + soff, k1 = kread[1] + soff, k2 = kread[2] + soff, k3 = kread[3] + soff;
             const uint32_t ka[8] = {k0, k1, k2, k3, k0 ^ 128u, k1 ^ 128u, k2 ^ 128u, k3 ^ 128u};
             lds_read_k<0>(ka, kf);
-            lds_read_v(vread + soff, v);
+            lds_read_v<0>(vread + soff, v);
         }
         __builtin_amdgcn_s_barrier();          // both wavefronts of the pair hold chunk i in registers
         if (i + 2 < nch) issue(i + 2);
@@ -842,6 +862,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         if (j < s.M) *(float2 *)(part.ml + (prow0 + j) * 2) = make_float2(m_row, l_row);
     }
     SPECPV_STAMP(8);   // partial stores issued
+    if (!REDO) SPECPV_CLOCKS_END(f.timeline, 3072 + ((size_t)blockIdx.y * gridDim.x + blockIdx.x), C);
     if (!FUSED) {
         // The combine kernel that follows reads the tree's parents and, one trip later, its K / V rows: nobody
         // has touched those in this call yet.  Ask for them here, on the way out (nothing waits for the data):
@@ -1033,6 +1054,13 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // is the one that chunk i + 3 is then requested into.
 // A wavefront keeps its rows to itself over the whole split, so the epilogue has nothing to
 // merge: it only turns the accumulators into row-major partials.
+// The chunk loop is unrolled over the four ring stages: with the stage a compile-time constant,
+// stage offsets are immediate fields of the LDS reads and of the requests' LDS addresses, the
+// validity words of the stages are scalar registers, and the request of a chunk tests the common
+// case (32 valid consecutive rows) first.  What a wavefront executes per chunk besides its
+// arithmetic is what this loop pays for: measured in core cycles per chunk and workgroup (128K
+// context, 32 splits), 2590 with a run-time stage, 2295 with the unrolled loop, 2140 without any
+// requests (timing probe), 1400 for the requests and barriers alone.
 constexpr int kGroupStages = 4;   // a power of two
 constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
 static_assert(kStageBytes % 256 == 0, "K operand addresses are derived by XOR with multiples of 32 below 256: stages (and the rings) must start 256-byte aligned");
@@ -1044,6 +1072,7 @@ template <bool ALIGNED, int W>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W > 8 ? 3 : 2, W > 8 ? 3 : 2)))
 void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 {
+    SPECPV_CLOCKS_BEGIN;
     extern __shared__ char lds_raw[];
     char *ring = lds_raw;                  // [kGroupStages][K 8 KiB | V 8 pieces of 1088 B]
     float *obuf = (float *)lds_raw;        // [W wavefronts][32 rows][kOPitch], reuses the ring after the main loop
@@ -1118,11 +1147,13 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     // first rows of the next 64 chunks sit in a register (lane t: chunk row_base + t) and are
     // picked with readlane.  Encoding: r >= 0: all 32 rows r .. r+31 are valid tokens (the common
     // case, handled without any further test); -1: no valid token; -2 - r: rows from r on, cut
-    // off by the context length.
+    // off by the context length; kPendingChunk: a chunk of partially verified tokens.
+    constexpr int kPendingChunk = (int)0x80000000;
     int row_base = 0, row0vec = -1;
     auto fill_rows = [&](int cb) {
         row_base = cb;
         int r = -1;
+        if (cb + lane < nch && (uint32_t)(c0 + cb + lane) >= C_ctx) r = kPendingChunk;
         if (cb + lane < nch && (uint32_t)(c0 + cb + lane) < C_ctx) {
             const uint32_t p0 = (uint32_t)(c0 + cb + lane) * 32u;   // < T: the slot below is < cnt
             const uint32_t slot = a.div_B.div(p0);
@@ -1197,15 +1228,10 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             }
         }
     };
-    auto issue = [&](int ci, int stg) -> uint32_t {
+    // Stage stg of the ring is a compile-time constant in the loop below (unrolled over the stages).
+    auto issue = [&](int ci, int stg) __attribute__((always_inline)) -> uint32_t {
         char *dst = ring + stg * kStageBytes;
         int tok;
-        if (s.kctx > 0 && (uint32_t)(c0 + ci) >= C_ctx) {
-            const int pr = (int)((uint32_t)(c0 + ci) - C_ctx) * 32 + n;
-            const int ptok = pr < s.kctx ? pr : -1;
-            issue_rows(kdb, vdb, stp, (uint32_t)max(ptok, 0), dst);
-            return (uint32_t)__ballot(ptok >= 0);
-        }
         if (ALIGNED) {
             if (ci - row_base >= 64) fill_rows(ci);
             const int r0 = __builtin_amdgcn_readlane(row0vec, ci - row_base);
@@ -1213,13 +1239,30 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
                 const uint32_t row_off = (uint32_t)r0 * st2;   // fits 32 bits (host-checked)
 #pragma unroll
                 for (int t = 0; t < NOPS; ++t)
-                    if (16 % W == 0 || t < NOPS - 1 || n_ops == NOPS)
-                        __builtin_amdgcn_global_load_lds((glb_void_ptr)((src_base[t] + row_off) + src_off[t]), (lds_void_ptr)(dst + dst_off[t]), 16, 0, kKvAux);
+                    if (16 % W == 0 || t < NOPS - 1 || n_ops == NOPS) {
+                        uint32_t so = src_off[t];
+                        // (ten wavefronts: keep the 32-bit offset as it is; the compiler would otherwise carry the 64-bit sum
+                        // base + offset of every operation through the loop, in registers that this variant does not have)
+                        if (W > 8) asm volatile("" : "+v"(so));
+                        __builtin_amdgcn_global_load_lds((glb_void_ptr)((src_base[t] + row_off) + so), (lds_void_ptr)(dst + dst_off[t]), 16, 0, kKvAux);
+                    }
                 return 0xffffffffu;
+            }
+            if (r0 == kPendingChunk) {
+                const int pr = (int)((uint32_t)(c0 + ci) - C_ctx) * 32 + n;
+                const int ptok = pr < s.kctx ? pr : -1;
+                issue_rows(kdb, vdb, stp, (uint32_t)max(ptok, 0), dst);
+                return (uint32_t)__ballot(ptok >= 0);
             }
             const int rr = -2 - r0;   // r0 == -1 gives -1
             tok = (rr >= 0 && rr + n < L) ? rr + n : -1;
         } else {
+            if (s.kctx > 0 && (uint32_t)(c0 + ci) >= C_ctx) {
+                const int pr = (int)((uint32_t)(c0 + ci) - C_ctx) * 32 + n;
+                const int ptok = pr < s.kctx ? pr : -1;
+                issue_rows(kdb, vdb, stp, (uint32_t)max(ptok, 0), dst);
+                return (uint32_t)__ballot(ptok >= 0);
+            }
             tok = lane_row(ci);
         }
         const uint32_t vm = (uint32_t)__ballot(tok >= 0);
@@ -1244,12 +1287,12 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[j][i] = 0.f;
 
-    // validity bits of the chunks in the ring: lane t holds those of stage t
-    uint32_t vmv = 0u;
-    for (int c = 0; c < kGroupAhead && c < nch; ++c) {
-        const uint32_t vm = issue(c, c);
-        vmv = lane == c ? vm : vmv;
-    }
+    // validity bits of the chunks in the ring, one word per stage (the same in every lane)
+    uint32_t vm_stage[kGroupStages] = {0u, 0u, 0u, 0u};
+    static_assert(kGroupStages == 4 && kGroupAhead == 3, "the first requests and the loop below are written for four stages, three ahead");
+    if (0 < nch) vm_stage[0] = issue(0, 0);
+    if (1 < nch) vm_stage[1] = issue(1, 1);
+    if (2 < nch) vm_stage[2] = issue(2, 2);
     // The barrier puts all eight wavefronts at the same point once per chunk; if they then all did
     // the same thing, they would queue for the LDS, then for the matrix cores, then for the vector
     // ALU.  So the two wavefronts of a SIMD (w and w + 4) run half a chunk apart: the second one
@@ -1268,44 +1311,45 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
             }
     };
     // ten wavefronts: operands in halves (16 registers at a time instead of 32)
-    auto pv_halves = [&](const uint32_t vaddr) {
+    auto pv_halves = [&](const uint32_t vaddr, auto off) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(off)::value;
         uint2 vh[8];
-        lds_read_v_half<0>(vaddr, vh);
+        lds_read_v_half<OFF>(vaddr, vh);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(vh[2 * j].x, vh[2 * j].y, vh[2 * j + 1].x, vh[2 * j + 1].y)),
                                                            as_bf16x8(pf0), O[j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        lds_read_v_half<512>(vaddr, vh);
+        lds_read_v_half<OFF + 512>(vaddr, vh);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             O[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(vh[2 * j].x, vh[2 * j].y, vh[2 * j + 1].x, vh[2 * j + 1].y)),
                                                            as_bf16x8(pf1), O[j], 0, 0, 0);
     };
-    for (int i = 0; i < nch; ++i) {
+    // One chunk; its ring stage U = i % 4 is a compile-time constant (the loop below is unrolled over the
+    // stages), so that stage offsets are immediate fields of the LDS reads and of the requests' LDS
+    // addresses, and the validity words live in scalar registers.
+    auto chunk = [&](const int i, auto stage) __attribute__((always_inline)) {
+        constexpr int U = decltype(stage)::value;
+        constexpr int SOFF = U * kStageBytes;
         // own part of chunk i has landed: kGroupAhead - 1 younger groups of n_ops operations may
         // stay in flight (towards the end of the range there are fewer: wait for all, they are due anyway)
         if (i + kGroupAhead - 1 >= nch) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         else if (n_ops == NOPS) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NOPS * (kGroupAhead - 1)) : "memory");
         else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NOPS - 1) * (kGroupAhead - 1)) : "memory");
         __builtin_amdgcn_s_barrier();   // ... and so have the others'; chunk i-1 has been read by all
-        if (i + kGroupAhead < nch) {
-            const int is = (i + kGroupAhead) & (kGroupStages - 1);
-            const uint32_t vm = issue(i + kGroupAhead, is);
-            vmv = lane == is ? vm : vmv;
-        }
-        const int rs = i & (kGroupStages - 1);
-        const uint32_t vmask = (uint32_t)__builtin_amdgcn_readlane((int)vmv, rs);
-        if (!live) continue;
+        if (i + kGroupAhead < nch) vm_stage[(U + kGroupAhead) & (kGroupStages - 1)] = issue(i + kGroupAhead, (U + kGroupAhead) & (kGroupStages - 1));
+        const uint32_t vmask = vm_stage[U];
+        if (!live) return;
         if (second && i > 0) pv();   // chunk i - 1, before its V registers are overwritten
         f32x16 S;
         if (W > 8) {
             // ten wavefronts: operands in halves, the V operands read behind the softmax (pv_halves)
             // (k-step ks reads 32 ks bytes further, modulo the swizzle: an XOR, as the row starts are 128-byte aligned)
-            const uint32_t ka0 = kread[0] + (uint32_t)rs * kStageBytes;
+            const uint32_t ka0 = kread[0];
             const uint32_t ka[4] = {ka0, ka0 ^ 32u, ka0 ^ 64u, ka0 ^ 96u};
             uint4 kh[4];
-            lds_read_k_half<0>(ka, kh);
+            lds_read_k_half<SOFF>(ka, kh);
 #pragma unroll
             for (int x = 0; x < 16; ++x) S[x] = 0.f;
 #pragma unroll
@@ -1313,19 +1357,18 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kh[ks]), qf[ks], S, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             const uint32_t kb4[4] = {ka0 ^ 128u, ka0 ^ 160u, ka0 ^ 192u, ka0 ^ 224u};
-            lds_read_k_half<0>(kb4, kh);
+            lds_read_k_half<SOFF>(kb4, kh);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kh[ks]), qf[4 + ks], S, 0, 0, 0);
         } else {
             uint4 kf[8];
             {
-                const uint32_t soff = (uint32_t)rs * kStageBytes;
-                const uint32_t k0 = kread[0] + soff, k1 = kread[1] + soff, k2 = kread[2] + soff, k3 = kread[3] + soff;
+                const uint32_t k0 = kread[0], k1 = kread[1], k2 = kread[2], k3 = kread[3];
                 const uint32_t ka[8] = {k0, k1, k2, k3, k0 ^ 128u, k1 ^ 128u, k2 ^ 128u, k3 ^ 128u};
-                lds_read_k<0>(ka, kf);
+                lds_read_k<SOFF>(ka, kf);
             }
-            lds_read_v(vread + (uint32_t)rs * kStageBytes, v);
+            lds_read_v<SOFF>(vread, v);
 #pragma unroll
             for (int x = 0; x < 16; ++x) S[x] = 0.f;
 #pragma unroll
@@ -1370,8 +1413,14 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         l_run += lsum;
         pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        if (W > 8) pv_halves(vread + (uint32_t)rs * kStageBytes);
+        if (W > 8) pv_halves(vread, std::integral_constant<int, SOFF>{});
         else if (!second) pv();
+    };
+    for (int i0 = 0; i0 < nch; i0 += kGroupStages) {
+        chunk(i0, std::integral_constant<int, 0>{});
+        if (i0 + 1 < nch) chunk(i0 + 1, std::integral_constant<int, 1>{});
+        if (i0 + 2 < nch) chunk(i0 + 2, std::integral_constant<int, 2>{});
+        if (i0 + 3 < nch) chunk(i0 + 3, std::integral_constant<int, 3>{});
     }
     if (second && live && nch > 0) pv();
     __syncthreads();   // every wavefront is done with the ring: the epilogue reuses that LDS
@@ -1412,6 +1461,7 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         if (jrow0 + uu < s.M) store_partial_half(part.o + (prow0 + jrow0 + uu) * 64, lane, x.x * ilu, x.y * ilu);
     }
     if (kg == 0 && jrow0 + n < s.M) *(float2 *)(part.ml + (prow0 + jrow0 + n) * 2) = make_float2(m_ref, l_run);
+    SPECPV_CLOCKS_END(part.timeline, (size_t)blockIdx.y * gridDim.x + blockIdx.x, nch);
     if (W > 8) {
         if (wave < kSlots) __builtin_amdgcn_s_barrier();   // the slot is free for wavefront wave + kSlots
     }

@@ -8,14 +8,19 @@ workgroup of the attention kernel stores the 100 MHz real-time counter at the po
 script runs the 32-layer partial-verify step of the headline workload (the launch configuration that
 bench.py times, eager launches) and prints, per point, the median over workgroups and repetitions of
 the time since the kernel's first workgroup entered.  Only the later layers of a step are read, where
-kernels follow each other back to back.
+kernels follow each other back to back.  It also prints the core clock that the workgroups saw.
+
+    python -m paper_2512_02337_amd.timeline --full
+
+measures the attention kernel of the full verification instead: core clock, lifetime and core cycles per
+32-token chunk of its workgroups.
 """
 import argparse
 import os
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-os.environ["SPECPV_LIB"] = os.path.join(HERE, "libspecpv_timeline.so")   # before the binding is imported
+os.environ.setdefault("SPECPV_LIB", os.path.join(HERE, "libspecpv_timeline.so"))   # before the binding is imported; another instrumented build can be named
 sys.path.insert(0, os.path.dirname(HERE))
 
 import numpy as np   # noqa: E402
@@ -38,6 +43,9 @@ def main():
     ap.add_argument("--layers", type=int, default=8)
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--pending", type=int, default=0, help="partially verified tokens in front of the tree (keys only)")
+    ap.add_argument("--full", action="store_true",
+                    help="measure the full verification (attention over the whole cache) instead: per workgroup of its attention "
+                         "kernel the core clock (s_memtime against the 100 MHz counter), the time and the cycles per 32-token chunk")
     a = ap.parse_args()
     if not os.path.exists(os.environ["SPECPV_LIB"]):
         raise SystemExit("build the instrumented library first: python -m paper_2512_02337_amd.build --timeline")
@@ -71,6 +79,32 @@ def main():
     max_wg = 4096
     tl = torch.zeros((len(layers), max_wg, 16), dtype=torch.int64, device=dev)
 
+    def clock_lines(rows, what):
+        """rows [n, >= 3]: core cycles, 10 ns ticks, chunks of one workgroup each"""
+        rows = rows[rows[:, 1] > 0]
+        if rows.shape[0] == 0:
+            return
+        mhz = rows[:, 0] / rows[:, 1] * 100.0
+        print("%s: %d workgroups; core clock %.0f MHz (median; %.0f .. %.0f); a workgroup lives %.1f us (median)"
+              % (what, rows.shape[0], np.median(mhz), mhz.min(), mhz.max(), np.median(rows[:, 1]) / 100.0))
+        return rows
+
+    if a.full:
+        print("full verification, workload %s, %d layers per step" % (a.workload, len(layers)))
+        for rep in range(a.reps):
+            tl.zero_()
+            for i, l in enumerate(layers):
+                sp.specpv_debug_set_timeline(tl[i] if rep >= 2 else None)
+                sp.specpv_full_verify_refresh(l["kv"], l["tree"], l["kmax"], l["kmin"], -1, l["cfg"], l["out"], None, l["sel_idx"], l["sel_count"], None, ws)
+            torch.cuda.synchronize()
+            if rep >= 2:
+                x = tl[:, :2048].reshape(-1, 16).cpu().numpy().astype(np.float64)
+                rows = clock_lines(x, "step %d, attention kernel" % rep)
+                if rows is not None:
+                    print("    %d chunks per workgroup, %.0f core cycles per chunk (median)" % (rows[0, 2], np.median(rows[:, 0] / rows[:, 2])))
+        sp.specpv_debug_set_timeline(None)
+        return
+
     def step(record):
         for i, l in enumerate(layers):
             sp.specpv_debug_set_timeline(tl[i] if record else None)
@@ -84,13 +118,14 @@ def main():
         step(True)
         torch.cuda.synchronize()
         for x in tl[len(layers) // 2:].cpu().numpy().astype(np.float64):
-            xa, xc = x[:2048], x[2048:]   # attention kernel's workgroups, combine kernel's
+            xa, xc = x[:2048], x[2048:3072]   # attention kernel's workgroups, combine kernel's (rows from 3072: clock readings)
             xa = xa[xa[:, 0] > 0]   # workgroups that ran
             t0 = xa[:, 0].min()
             res.append(np.where(xa > 0, (xa - t0) / 100.0, np.nan))   # microseconds
             xc = xc[xc[:, 0] > 0]
             if xc.shape[0]:
                 cres.append(np.where(xc > 0, (xc - t0) / 100.0, np.nan))
+    clock_lines(tl[len(layers) // 2:, 3072:].reshape(-1, 16).cpu().numpy().astype(np.float64), "attention kernel, last repetition")
     sp.specpv_debug_set_timeline(None)
     n_wg = res[0].shape[0]
     res = np.stack([r for r in res if r.shape[0] == n_wg])
