@@ -1048,10 +1048,12 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // blocks, KV split) and walks the split's chunks once for all of them: its W wavefronts share
 // ONE ring of four stages and each brings its share of a chunk's 16 DMA operations, so every
 // K / V byte is requested from memory exactly once per workgroup, whatever the caches do.
-// Chunks are requested three ahead of the arithmetic (measured: two is slightly slower, four
-// and six are no faster).  One workgroup barrier per chunk: past the barrier of chunk i every
-// part of chunk i has landed, and every wavefront has finished reading chunk i - 1, whose stage
-// is the one that chunk i + 3 is then requested into.
+// The ring has two halves of four chunks.  One workgroup barrier per FOUR chunks: at the barrier in
+// front of chunks i .. i + 3 all of them have landed (requested one period earlier), every wavefront
+// is done with the other half, and chunks i + 4 .. i + 7 are requested into it at once.  (A barrier
+// per chunk, with the requests three chunks ahead in a ring of four, cost 430 of 2300 core cycles
+// per chunk: it puts the wavefronts of a SIMD back in step every chunk, so that they queue for
+// the LDS, the matrix cores and the vector ALU together instead of filling each other's gaps.)
 // A wavefront keeps its rows to itself over the whole split, so the epilogue has nothing to
 // merge: it only turns the accumulators into row-major partials.
 // The chunk loop is unrolled over the four ring stages: with the stage a compile-time constant,
@@ -1061,13 +1063,13 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // arithmetic is what this loop pays for: measured in core cycles per chunk and workgroup (128K
 // context, 32 splits), 2590 with a run-time stage, 2295 with the unrolled loop, 2140 without any
 // requests (timing probe), 1400 for the requests and barriers alone.
-constexpr int kGroupStages = 4;   // a power of two
-constexpr int kGroupAhead = 3;    // <= kGroupStages - 1
+constexpr int kGroupStages = 8;   // two halves of kGroupPeriod chunks
+constexpr int kGroupPeriod = 4;   // chunks between two workgroup barriers
 static_assert(kStageBytes % 256 == 0, "K operand addresses are derived by XOR with multiples of 32 below 256: stages (and the rings) must start 256-byte aligned");
 
 // W wavefronts per workgroup: 2, 4, 6, 8 or 10.  Ten (nine or ten row blocks: G = 5 with up to 64 nodes) means
-// three wavefronts on two of the SIMDs, i.e. at most 168 registers each: that variant does without the deferred
-// O^T products of the second wavefront, which keep V operands alive beside the K operands.
+// three wavefronts on two of the SIMDs, i.e. at most 168 registers each: that variant takes its K and V
+// operands in halves.
 template <bool ALIGNED, int W>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W > 8 ? 3 : 2, W > 8 ? 3 : 2)))
 void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
@@ -1096,7 +1098,6 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     const int hh = rbx_c / a.rph;
     const int m0 = (rbx_c - hh * a.rph) * 32;
     const int h = g * s.G + hh;
-    const bool second = W <= 8 && wave >= 4;  // the second wavefront of its SIMD (wavefronts w and w + 4 share one)
     const int n = lane & 31, kg = lane >> 5;
 
     const int32_t *sel = a.sel_idx ? a.sel_idx + (int64_t)bg * a.n_sel : nullptr;
@@ -1288,16 +1289,12 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         for (int i = 0; i < 16; ++i) O[j][i] = 0.f;
 
     // validity bits of the chunks in the ring, one word per stage (the same in every lane)
-    uint32_t vm_stage[kGroupStages] = {0u, 0u, 0u, 0u};
-    static_assert(kGroupStages == 4 && kGroupAhead == 3, "the first requests and the loop below are written for four stages, three ahead");
+    uint32_t vm_stage[kGroupStages] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    static_assert(kGroupStages == 8 && kGroupPeriod == 4, "the first requests and the loop below are written for two halves of four stages");
     if (0 < nch) vm_stage[0] = issue(0, 0);
     if (1 < nch) vm_stage[1] = issue(1, 1);
     if (2 < nch) vm_stage[2] = issue(2, 2);
-    // The barrier puts all eight wavefronts at the same point once per chunk; if they then all did
-    // the same thing, they would queue for the LDS, then for the matrix cores, then for the vector
-    // ALU.  So the two wavefronts of a SIMD (w and w + 4) run half a chunk apart: the second one
-    // keeps P and V of its chunk in registers and does the O^T += V^T . P^T products after the next
-    // barrier, while the first one reads its operands from LDS.
+    if (3 < nch) vm_stage[3] = issue(3, 3);
     uint2 v[16];
     uint4 pf0 = make_uint4(0u, 0u, 0u, 0u), pf1 = pf0;
     auto pv = [&]() {
@@ -1330,23 +1327,22 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     // stages), so that stage offsets are immediate fields of the LDS reads and of the requests' LDS
     // addresses, and the validity words live in scalar registers.
     auto chunk = [&](const int i, auto stage) __attribute__((always_inline)) {
+        // (the offset field of an LDS instruction has 16 bits: the second half of the ring is reached through the
+        // address register, the stage inside the half through the field)
         constexpr int U = decltype(stage)::value;
-        constexpr int SOFF = U * kStageBytes;
-        // own part of chunk i has landed: kGroupAhead - 1 younger groups of n_ops operations may
-        // stay in flight (towards the end of the range there are fewer: wait for all, they are due anyway)
-        if (i + kGroupAhead - 1 >= nch) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (n_ops == NOPS) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NOPS * (kGroupAhead - 1)) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NOPS - 1) * (kGroupAhead - 1)) : "memory");
-        __builtin_amdgcn_s_barrier();   // ... and so have the others'; chunk i-1 has been read by all
-        if (i + kGroupAhead < nch) vm_stage[(U + kGroupAhead) & (kGroupStages - 1)] = issue(i + kGroupAhead, (U + kGroupAhead) & (kGroupStages - 1));
+        constexpr int SOFF = (U % kGroupPeriod) * kStageBytes;
+        constexpr uint32_t HOFF_C = (uint32_t)(U / kGroupPeriod) * kGroupPeriod * kStageBytes;
+        uint32_t HOFF = HOFF_C;
+        // (ten wavefronts: add the half's offset anew in every chunk; the compiler would otherwise keep a second
+        // set of address registers for the second half, which this variant does not have)
+        if (W > 8 && HOFF_C != 0) asm volatile("" : "+s"(HOFF));
         const uint32_t vmask = vm_stage[U];
         if (!live) return;
-        if (second && i > 0) pv();   // chunk i - 1, before its V registers are overwritten
         f32x16 S;
         if (W > 8) {
             // ten wavefronts: operands in halves, the V operands read behind the softmax (pv_halves)
             // (k-step ks reads 32 ks bytes further, modulo the swizzle: an XOR, as the row starts are 128-byte aligned)
-            const uint32_t ka0 = kread[0];
+            const uint32_t ka0 = kread[0] + HOFF;
             const uint32_t ka[4] = {ka0, ka0 ^ 32u, ka0 ^ 64u, ka0 ^ 96u};
             uint4 kh[4];
             lds_read_k_half<SOFF>(ka, kh);
@@ -1364,11 +1360,11 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         } else {
             uint4 kf[8];
             {
-                const uint32_t k0 = kread[0], k1 = kread[1], k2 = kread[2], k3 = kread[3];
+                const uint32_t k0 = kread[0] + HOFF, k1 = kread[1] + HOFF, k2 = kread[2] + HOFF, k3 = kread[3] + HOFF;
                 const uint32_t ka[8] = {k0, k1, k2, k3, k0 ^ 128u, k1 ^ 128u, k2 ^ 128u, k3 ^ 128u};
                 lds_read_k<SOFF>(ka, kf);
             }
-            lds_read_v<SOFF>(vread, v);
+            lds_read_v<SOFF>(vread + HOFF, v);
 #pragma unroll
             for (int x = 0; x < 16; ++x) S[x] = 0.f;
 #pragma unroll
@@ -1377,11 +1373,14 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         }
 
         if (vmask != 0xffffffffu) {
+            // (rare: the lane's share of the bits is worked out here, from a value the compiler cannot see through,
+            // so that nothing of it is kept in registers across the loop)
+            int kg_o = kg;
+            asm volatile("" : "+v"(kg_o));
+            const uint32_t mine = vmask >> (kg_o * 4);
 #pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                const int tt = (x >> 2) * 8 + kg * 4 + (x & 3);
-                if (!((vmask >> tt) & 1u)) S[x] = -INFINITY;
-            }
+            for (int x = 0; x < 16; ++x)
+                if (!((mine >> ((x >> 2) * 8 + (x & 3))) & 1u)) S[x] = -INFINITY;
         }
         float mx = fmaxf(S[0], S[1]);
 #pragma unroll
@@ -1413,16 +1412,30 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         l_run += lsum;
         pf0 = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         pf1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        if (W > 8) pv_halves(vread, std::integral_constant<int, SOFF>{});
-        else if (!second) pv();
+        if (W > 8) pv_halves(vread + HOFF, std::integral_constant<int, SOFF>{});
+        else pv();
+    };
+    // Four chunks between two barriers.  At the barrier in front of chunks i0 .. i0 + 3 (ring half H) every
+    // wavefront's requests have landed -- they were made a whole period ago, so the wait is for all of
+    // them -- and every wavefront is done with the other half, into which the next four chunks are
+    // requested at once; then come four chunks of arithmetic without a request or a wait in between.
+    auto period = [&](const int i0, auto half) __attribute__((always_inline)) {
+        constexpr int H = decltype(half)::value, S0 = kGroupPeriod * H, N0 = kGroupPeriod * (1 - H);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        if (i0 + 4 < nch) vm_stage[N0] = issue(i0 + 4, N0);
+        if (i0 + 5 < nch) vm_stage[N0 + 1] = issue(i0 + 5, N0 + 1);
+        if (i0 + 6 < nch) vm_stage[N0 + 2] = issue(i0 + 6, N0 + 2);
+        if (i0 + 7 < nch) vm_stage[N0 + 3] = issue(i0 + 7, N0 + 3);
+        chunk(i0, std::integral_constant<int, S0>{});
+        if (i0 + 1 < nch) chunk(i0 + 1, std::integral_constant<int, S0 + 1>{});
+        if (i0 + 2 < nch) chunk(i0 + 2, std::integral_constant<int, S0 + 2>{});
+        if (i0 + 3 < nch) chunk(i0 + 3, std::integral_constant<int, S0 + 3>{});
     };
     for (int i0 = 0; i0 < nch; i0 += kGroupStages) {
-        chunk(i0, std::integral_constant<int, 0>{});
-        if (i0 + 1 < nch) chunk(i0 + 1, std::integral_constant<int, 1>{});
-        if (i0 + 2 < nch) chunk(i0 + 2, std::integral_constant<int, 2>{});
-        if (i0 + 3 < nch) chunk(i0 + 3, std::integral_constant<int, 3>{});
+        period(i0, std::integral_constant<int, 0>{});
+        if (i0 + kGroupPeriod < nch) period(i0 + kGroupPeriod, std::integral_constant<int, 1>{});
     }
-    if (second && live && nch > 0) pv();
     __syncthreads();   // every wavefront is done with the ring: the epilogue reuses that LDS
 
     // ---- one partial per (head, split, node): accumulators -> row-major through LDS ------
