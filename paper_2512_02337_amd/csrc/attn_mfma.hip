@@ -1290,11 +1290,13 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
 
     // validity bits of the chunks in the ring, one word per stage (the same in every lane)
     uint32_t vm_stage[kGroupStages] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    static_assert(kGroupStages == 8 && kGroupPeriod == 4, "the first requests and the loop below are written for two halves of four stages");
-    if (0 < nch) vm_stage[0] = issue(0, 0);
-    if (1 < nch) vm_stage[1] = issue(1, 1);
-    if (2 < nch) vm_stage[2] = issue(2, 2);
-    if (3 < nch) vm_stage[3] = issue(3, 3);
+    static_assert(kGroupStages == 8 && kGroupPeriod == 4, "the first requests and the loops below are written for two halves of four stages");
+    if (W <= 8) {
+        if (0 < nch) vm_stage[0] = issue(0, 0);
+        if (1 < nch) vm_stage[1] = issue(1, 1);
+        if (2 < nch) vm_stage[2] = issue(2, 2);
+        if (3 < nch) vm_stage[3] = issue(3, 3);
+    }
     uint2 v[16];
     uint4 pf0 = make_uint4(0u, 0u, 0u, 0u), pf1 = pf0;
     auto pv = [&]() {
@@ -1326,17 +1328,13 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
     // One chunk; its ring stage U = i % 4 is a compile-time constant (the loop below is unrolled over the
     // stages), so that stage offsets are immediate fields of the LDS reads and of the requests' LDS
     // addresses, and the validity words live in scalar registers.
-    auto chunk = [&](const int i, auto stage) __attribute__((always_inline)) {
-        // (the offset field of an LDS instruction has 16 bits: the second half of the ring is reached through the
-        // address register, the stage inside the half through the field)
+    // Stage U compile-time (the unrolled loop): the stage inside its ring half is an immediate field of the LDS
+    // reads (16 bits), the half is reached through the address register.  The ten-wavefront loop passes stage 0
+    // and the whole offset at run time (roff).
+    auto chunk = [&](const int i, auto stage, const uint32_t roff, const uint32_t vmask) __attribute__((always_inline)) {
         constexpr int U = decltype(stage)::value;
         constexpr int SOFF = (U % kGroupPeriod) * kStageBytes;
-        constexpr uint32_t HOFF_C = (uint32_t)(U / kGroupPeriod) * kGroupPeriod * kStageBytes;
-        uint32_t HOFF = HOFF_C;
-        // (ten wavefronts: add the half's offset anew in every chunk; the compiler would otherwise keep a second
-        // set of address registers for the second half, which this variant does not have)
-        if (W > 8 && HOFF_C != 0) asm volatile("" : "+s"(HOFF));
-        const uint32_t vmask = vm_stage[U];
+        const uint32_t HOFF = (uint32_t)(U / kGroupPeriod) * kGroupPeriod * kStageBytes + roff;
         if (!live) return;
         f32x16 S;
         if (W > 8) {
@@ -1427,14 +1425,41 @@ void attn_ctx_mfma_group_kernel(Shape s, Partials part, MfmaArgs a)
         if (i0 + 5 < nch) vm_stage[N0 + 1] = issue(i0 + 5, N0 + 1);
         if (i0 + 6 < nch) vm_stage[N0 + 2] = issue(i0 + 6, N0 + 2);
         if (i0 + 7 < nch) vm_stage[N0 + 3] = issue(i0 + 7, N0 + 3);
-        chunk(i0, std::integral_constant<int, S0>{});
-        if (i0 + 1 < nch) chunk(i0 + 1, std::integral_constant<int, S0 + 1>{});
-        if (i0 + 2 < nch) chunk(i0 + 2, std::integral_constant<int, S0 + 2>{});
-        if (i0 + 3 < nch) chunk(i0 + 3, std::integral_constant<int, S0 + 3>{});
+        chunk(i0, std::integral_constant<int, S0>{}, 0u, vm_stage[S0]);
+        if (i0 + 1 < nch) chunk(i0 + 1, std::integral_constant<int, S0 + 1>{}, 0u, vm_stage[S0 + 1]);
+        if (i0 + 2 < nch) chunk(i0 + 2, std::integral_constant<int, S0 + 2>{}, 0u, vm_stage[S0 + 2]);
+        if (i0 + 3 < nch) chunk(i0 + 3, std::integral_constant<int, S0 + 3>{}, 0u, vm_stage[S0 + 3]);
     };
-    for (int i0 = 0; i0 < nch; i0 += kGroupStages) {
-        period(i0, std::integral_constant<int, 0>{});
-        if (i0 + kGroupPeriod < nch) period(i0 + kGroupPeriod, std::integral_constant<int, 1>{});
+    if (W <= 8) {
+        for (int i0 = 0; i0 < nch; i0 += kGroupStages) {
+            period(i0, std::integral_constant<int, 0>{});
+            if (i0 + kGroupPeriod < nch) period(i0 + kGroupPeriod, std::integral_constant<int, 1>{});
+        }
+    } else {
+        // Ten wavefronts (three on two of the SIMDs, 168 registers): a barrier per chunk, requests three chunks
+        // ahead, the stage a run-time value -- measured against the period loop above on the ragged batch of four
+        // at G = 5: partial step (16 chunks per workgroup) 32.1 against 37.1 us, full pass 532 against 525 us.
+        constexpr int kAhead = 3;
+        uint32_t vmv = 0u;   // validity words of the chunks in the ring: lane t holds those of stage t
+        for (int c = 0; c < kAhead && c < nch; ++c) {
+            const uint32_t vm = issue(c, c);
+            vmv = lane == c ? vm : vmv;
+        }
+        for (int i = 0; i < nch; ++i) {
+            // own part of chunk i has landed: kAhead - 1 younger groups of n_ops operations may stay in flight
+            // (towards the end of the range there are fewer: wait for all, they are due anyway)
+            if (i + kAhead - 1 >= nch) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else if (n_ops == NOPS) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NOPS * (kAhead - 1)) : "memory");
+            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NOPS - 1) * (kAhead - 1)) : "memory");
+            __builtin_amdgcn_s_barrier();   // ... and so have the others'; chunk i-1 has been read by all
+            if (i + kAhead < nch) {
+                const int is = (i + kAhead) & (kGroupStages - 1);
+                const uint32_t vm = issue(i + kAhead, is);
+                vmv = lane == is ? vm : vmv;
+            }
+            const int rs = i & (kGroupStages - 1);
+            chunk(i, std::integral_constant<int, 0>{}, (uint32_t)rs * kStageBytes, (uint32_t)__builtin_amdgcn_readlane((int)vmv, rs));
+        }
     }
     __syncthreads();   // every wavefront is done with the ring: the epilogue reuses that LDS
 
