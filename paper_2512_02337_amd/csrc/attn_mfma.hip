@@ -1043,11 +1043,12 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 
 // ---- group variant: the query heads of a KV head in one workgroup --------------------------
 // For long token ranges.  The G x ceil(M / 32) blocks of 32 query rows that share a KV head are
-// dealt to workgroups of up to 8 wavefronts, one row block per wavefront (G = 4, M <= 64: one
-// workgroup of 8; G = 5: one workgroup of 10; more row blocks: two or more workgroups).  A workgroup owns (sequence, KV head, its row
-// blocks, KV split) and walks the split's chunks once for all of them: its W wavefronts share
-// ONE ring of four stages and each brings its share of a chunk's 16 DMA operations, so every
-// K / V byte is requested from memory exactly once per workgroup, whatever the caches do.
+// dealt to workgroups of up to 10 wavefronts, one row block per wavefront (G = 4, M <= 64: one
+// workgroup of 8; G = 5: one workgroup of 10; more row blocks: two or more workgroups).  A workgroup
+// owns (sequence, KV head, its row blocks, KV split) and walks the split's chunks once for all of
+// them: its W wavefronts share ONE ring of eight stages and each brings its share of a chunk's 16 DMA
+// operations, so every K / V byte is requested from memory exactly once per workgroup, whatever
+// the caches do.
 // The ring has two halves of four chunks.  One workgroup barrier per FOUR chunks: at the barrier in
 // front of chunks i .. i + 3 all of them have landed (requested one period earlier), every wavefront
 // is done with the other half, and chunks i + 4 .. i + 7 are requested into it at once.  (A barrier
@@ -1056,13 +1057,14 @@ void attn_ctx_mfma_kernel(const int32_t *a_sel_idx, const int32_t *a_sel_count, 
 // the LDS, the matrix cores and the vector ALU together instead of filling each other's gaps.)
 // A wavefront keeps its rows to itself over the whole split, so the epilogue has nothing to
 // merge: it only turns the accumulators into row-major partials.
-// The chunk loop is unrolled over the four ring stages: with the stage a compile-time constant,
+// The chunk loop is unrolled over the eight ring stages: with the stage a compile-time constant,
 // stage offsets are immediate fields of the LDS reads and of the requests' LDS addresses, the
 // validity words of the stages are scalar registers, and the request of a chunk tests the common
 // case (32 valid consecutive rows) first.  What a wavefront executes per chunk besides its
 // arithmetic is what this loop pays for: measured in core cycles per chunk and workgroup (128K
-// context, 32 splits), 2590 with a run-time stage, 2295 with the unrolled loop, 2140 without any
-// requests (timing probe), 1400 for the requests and barriers alone.
+// context, 32 splits), 2590 with a run-time stage and a barrier per chunk, 2295 unrolled, 2085
+// with the four-chunk period; 1400 for the requests and barriers alone (timing probe), 1024 for
+// the matrix instructions.  (The ten-wavefront variant keeps a barrier per chunk, see below.)
 constexpr int kGroupStages = 8;   // two halves of kGroupPeriod chunks
 constexpr int kGroupPeriod = 4;   // chunks between two workgroup barriers
 static_assert(kStageBytes % 256 == 0, "K operand addresses are derived by XOR with multiples of 32 below 256: stages (and the rings) must start 256-byte aligned");
