@@ -129,6 +129,10 @@ def test_shapes_and_edges(gpu_lib, over, tag):
     (dict(ctx=[35840, 33000], B=64, M=60, Hq=10, Hkv=2, rho=[0.1, 0.1]), "G=5, ten row blocks: one workgroup of ten wavefronts, batch of 2"),
     (dict(ctx=[34567], B=16, M=60, Hq=10, Hkv=2, tree="uniform"), "G=5, ten wavefronts, block 16"),
     (dict(ctx=[36000], B=64, M=70, Hq=6, Hkv=2, tree="uniform"), "G=3, nine row blocks: ten wavefronts, one idle"),
+    (dict(ctx=[40960, 36000, 30000, 22222, 15000, 9000, 3000, 64], B=64, M=40, rho=[0.1] * 8),
+     "G=4, eight wavefronts, ragged batch of 8: workgroups with 0 .. 30 chunks (every remainder of the four-chunk period)"),
+    (dict(ctx=[33000, 21000, 9500, 2000, 100], B=64, M=40, Hq=10, Hkv=2, rho=[0.1] * 5),
+     "G=5, ten wavefronts, ragged batch of 5"),
 ])
 def test_long_ranges_take_the_group_kernel(gpu_lib, over, tag):
     """Full verification over tens of thousands of tokens at small head counts: each wavefront
