@@ -100,3 +100,55 @@ def test_one_launch_equals_two(routes, tag, ctx, B, M, Hq, Hkv, sel, reduce, sco
             np.testing.assert_allclose(scores[0, g], sc[0], atol=1e-3, rtol=0)
             exact = check_selection(idx[0, g:g + 1], cnt[0, g:g + 1], ridx, rcnt, sc, ns, nr, k, tag)
             say("   KV head %d against the oracle: %s" % (g, "identical" if exact else "within the near-tie band"))
+
+
+def test_one_launch_in_a_graph(routes):
+    """The one-launch route inside a HIP graph: the arrival words reset themselves (no memset node), so every replay
+    -- with new queries and summaries in the captured buffers, and eager work in between -- gives what the two
+    eager launches give on the same inputs."""
+    sp = routes
+    ctx, B, M, Hq, Hkv, D = [40000, 131072, 9000], 64, 60, 32, 8, 128
+    batch, nbm = len(ctx), (max(ctx) + B - 1) // B
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    kv_rows = torch.empty((batch, Hkv, nbm * B, D), dtype=torch.bfloat16, device="cuda")   # never read
+    kv = sp.KV(kv_rows, kv_rows, torch.tensor(ctx, dtype=torch.int32, device="cuda"), B, nbm)
+    q = torch.zeros((batch, M, Hq, D), dtype=torch.bfloat16, device="cuda")
+    kmax = torch.zeros((batch, Hkv, nbm, D), dtype=torch.bfloat16, device="cuda")
+    kmin = torch.zeros_like(kmax)
+    tree, cfg = sp.Tree(q), sp.SelectCfg(1, 8, 55, "mean")
+    ws = torch.zeros((sp.specpv_workspace_bytes(kv, tree, cfg),), dtype=torch.uint8, device="cuda")
+    idx = torch.zeros((batch, Hkv, cfg.n_sel), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((batch, Hkv), dtype=torch.int32, device="cuda")
+    scores = torch.zeros((batch, Hkv, nbm), device="cuda")
+
+    def call():
+        sp.specpv_select_blocks(kv, tree, kmax, kmin, cfg, idx, cnt, scores, ws)
+
+    sp.specpv_debug_set_select_route(1)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        call()
+        stream.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            call()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        a, b, c = _inputs(gen, batch, Hkv, nbm, D, M, Hq, 0, 1)
+        kmax.copy_(a); kmin.copy_(b); q.copy_(c)              # eager work between the replays
+        for t in (idx, cnt, scores):
+            t.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (idx, cnt, scores)]
+        assert int((ws[:65536].view(torch.int64) != 0).sum()) == 0, "arrival words must be zero after a replay"
+        for t in (idx, cnt, scores):
+            t.fill_(-3)
+        sp.specpv_debug_set_select_route(2)
+        call()
+        torch.cuda.synchronize()
+        sp.specpv_debug_set_select_route(1)
+        for name, x, y in zip(("sel_idx", "sel_count", "scores"), got, (idx, cnt, scores)):
+            assert torch.equal(x, y), "replay %d differs from the two eager launches in %s" % (rep, name)
