@@ -55,6 +55,7 @@ constexpr int kVPiecePitch = 1088;
 constexpr int kStageBytes = 8192 + 8 * kVPiecePitch;
 constexpr int kStages = 2;           // ring depth per wavefront pair (eight-wavefront kernel)
 constexpr int kRingBytes = 4 * kStages * kStageBytes;
+constexpr int kQStageBytes = 2 * 8 * 1024;   // the query rows of a workgroup's two row blocks as MFMA operands (eight-wavefront kernel)
 // Cache policy of the K / V requests: 2 = the streaming hint (nt).  K / V rows are used once per
 // workgroup; with the hint the requests are served faster, and the sharing of a KV head's rows
 // between its query heads' workgroups through L2 is unaffected (same fetch counters).
@@ -417,12 +418,18 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         for (int x = 0; x < 4; ++x)
             if (lane + 64 * x < a.n_sel) idv[x] = sel[lane + 64 * x];
     }
-    uint4 qraw[8];
+    // The query rows of a row block are the same for its four wavefronts (one per token group): each brings
+    // a quarter of them (k-steps 2 tg, 2 tg + 1) straight into LDS, laid out as the operands are read
+    // (k-step ks of row block rb: 1 KiB, lane l's 16 bytes at 16 l), and all four read the whole from there
+    // once the requests have landed -- a quarter of the bytes through the CU's memory path in the phase
+    // where the first K / V chunks are requested.
+    char *qstage = lds_raw + 2048 + max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
     {
         const int j = min(m0 + rb * 32 + n, s.M - 1);   // rows past M repeat row M-1; never stored
-        const uint16_t *qrow = (const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qraw[ks] = *(const uint4 *)(qrow + ks * 16);
+        const char *qrow = (const char *)((const uint16_t *)s.q + (((int64_t)b * s.M + j) * s.Hq + h) * 128 + kg * 8);
+        char *dst = qstage + (rb * 8 + 2 * tg) * 1024;
+        __builtin_amdgcn_global_load_lds((glb_void_ptr)(qrow + 64 * tg), (lds_void_ptr)dst, 16, 0, 0);   // a k-step is 16 channels: 32 bytes
+        __builtin_amdgcn_global_load_lds((glb_void_ptr)(qrow + 64 * tg + 32), (lds_void_ptr)(dst + 1024), 16, 0, 0);
     }
     const int rows_tile = min(64, s.M - m0);            // >= 1
     int par0 = -1, par1 = -1;
@@ -466,9 +473,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
     const uint32_t vread = ring_addr + 8192u + (uint32_t)(4 * kg + ((lane & 15) >> 2)) * kVPiecePitch +
                            32u * (uint32_t)((lane >> 4) & 1) + 8u * (uint32_t)(lane & 3);   // + stage * kStageBytes
 
-    bf16x8 qf[8];   // Q fragments (B operand of S^T = K . Q^T): row = lane & 31
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
+    bf16x8 qf[8];   // Q fragments (B operand of S^T = K . Q^T): row = lane & 31; read from LDS in front of the main loop
 
     const int r4 = lane >> 4, pos = lane & 15;
     const uint32_t sw0 = 16u * (uint32_t)(pos ^ r4), vsw = 16u * (uint32_t)pos;   // K row 4 i + r4: piece pos ^ ((4 i + r4) & 15) = sw0 ^ 64 (i & 3)
@@ -709,6 +714,16 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         for (int i = 0; i < 16; ++i) O[j][i] = 0.f;
 
     // ---- main loop ---------------------------------------------------------------------
+    // The query operands: this wavefront's quarter has landed (the wait for everything requested in the prologue,
+    // above); the barrier covers the other wavefronts' quarters.
+    auto read_q = [&]() {
+        const uint32_t q0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)qstage + (uint32_t)(rb * 8192 + lane * 16);
+        const uint32_t qa[8] = {q0, q0 + 1024u, q0 + 2048u, q0 + 3072u, q0 + 4096u, q0 + 5120u, q0 + 6144u, q0 + 7168u};
+        uint4 qraw[8];
+        lds_read_k<0>(qa, qraw);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(qraw[ks]);
+    };
     if (FUSED) {
         draft_rows();
     } else {
@@ -725,6 +740,7 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();          // ... and so has the partner's half
         if (i < 4) SPECPV_STAMP(3 + i);   // chunk i has landed
+        if (i == 0) read_q();
         uint4 kf[8];
         uint2 v[16];
         const uint32_t vmask = vmask_st[stg];
@@ -1564,7 +1580,7 @@ hipError_t launch_attn_ctx_mfma(const Shape &s, const int32_t *sel_idx, const in
     const dim3 grid(8 * GR, kind == kAttnGroup ? (a.n_units + 7) / 8 : ((a.n_bg + 7) / 8) * nctx);
     if (grid.y > 65535u) return hipErrorInvalidConfiguration;
     const bool aligned = s.B % 32 == 0;
-    const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float));
+    const size_t lds_split = 2048 + (size_t)max(kRingBytes, 4 * 64 * kOPitch * (int)sizeof(float)) + kQStageBytes;
     const size_t lds_group = (size_t)max(kGroupStages * kStageBytes, (gl.waves > 8 ? gl.waves / 2 : gl.waves) * 32 * kOPitch * (int)sizeof(float));
 #define SPECPV_SET_LDS(KERN, LDS)                                                                      \
         static PerDeviceOnce once;   /* one per kernel instantiation */                               \
