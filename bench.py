@@ -31,7 +31,7 @@ RECORDED = {"llama8b_128k": {
     "plan": {"kernels": ["attn_ctx_mfma_kernel", "combine_kernel"], "splits": 8},
     "traffic_bytes": (8663 + 2419) * 2 * 1024 + (3960 + 480) * 1024,
     "traffic_source": "profiles/pmc_traffic_llama8b_128k.md",
-    "kernels": [{"name": "attn_ctx_mfma_kernel", "us": 13.0}, {"name": "combine_kernel", "us": 4.8}],
+    "kernels": [{"name": "attn_ctx_mfma_kernel", "us": 12.5}, {"name": "combine_kernel", "us": 4.8}],
     "kernels_source": "profiles/kernel_durations_llama8b_128k.md"}}
 
 
