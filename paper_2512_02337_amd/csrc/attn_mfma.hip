@@ -772,9 +772,12 @@ __device__ __forceinline__ bool attn_ctx_pass(Shape s, Partials part, MfmaArgs a
         float mx = fmaxf(S[0], S[1]);
 #pragma unroll
         for (int x = 2; x < 16; x += 2) mx = fmaxf(fmaxf(mx, S[x]), S[x + 1]);
-        mx = max_xor32(mx) * a.scale_log2;
-        // the reference max only moves when the true max gets more than 2^slack ahead
+        mx *= a.scale_log2;
+        // the reference max only moves when the true max gets more than 2^slack ahead (tested on each lane's half of
+        // the chunk's tokens; the row's maximum is formed behind the branch -- in the group kernel the same change
+        // measured 3 % slower, so it keeps the exchange in front)
         if (__any(mx > m_ref + kRescaleSlack)) {
+            mx = max_xor32(mx);
             const float m_new = mx > m_ref + kRescaleSlack ? mx : m_ref;
             const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
             m_ref = m_new;
