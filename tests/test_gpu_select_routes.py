@@ -152,3 +152,37 @@ def test_one_launch_in_a_graph(routes):
         sp.specpv_debug_set_select_route(1)
         for name, x, y in zip(("sel_idx", "sel_count", "scores"), got, (idx, cnt, scores)):
             assert torch.equal(x, y), "replay %d differs from the two eager launches in %s" % (rep, name)
+
+
+@pytest.mark.parametrize("reduce", ["mean", "max", "last"])
+def test_batched_scoring_against_the_oracle(routes, reduce):
+    """The scoring kernel that batches take at G = 5 (query rows held in registers over eight tiles of 32 blocks per
+    workgroup, Section 3.2 eq. 2-3) against the oracle: scores and kept lists of the shortest and the longest sequence
+    of a ragged batch, every reducer (the last wavefront's rows end ragged: 300 rows in ten blocks of 32)."""
+    sp = routes
+    ctx, B, M, Hq, Hkv, D = [32768, 65536, 98304, 131072], 64, 60, 40, 8, 128
+    ns, nr, k = 1, 8, 55
+    batch, nbm = len(ctx), (max(ctx) + B - 1) // B
+    gen = torch.Generator(device="cuda").manual_seed(29)
+    kv_rows = torch.empty((batch, Hkv, nbm * B, D), dtype=torch.bfloat16, device="cuda")   # never read
+    kv = sp.KV(kv_rows, kv_rows, torch.tensor(ctx, dtype=torch.int32, device="cuda"), B, nbm)
+    kmax, kmin, q = _inputs(gen, batch, Hkv, nbm, D, M, Hq, 0, ns)
+    last_node = 37
+    tree, cfg = sp.Tree(q, last_node=last_node), sp.SelectCfg(ns, nr, k, reduce)
+    ws = torch.zeros((sp.specpv_workspace_bytes(kv, tree, cfg),), dtype=torch.uint8, device="cuda")
+    idx = torch.full((batch, Hkv, cfg.n_sel), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((batch, Hkv), -7, dtype=torch.int32, device="cuda")
+    scores = torch.full((batch, Hkv, nbm), -7.0, device="cuda")
+    sp.specpv_select_blocks(kv, tree, kmax, kmin, cfg, idx, cnt, scores, ws)
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    for b, g in ((0, 0), (0, Hkv - 1), (3, 2), (3, Hkv - 1)):
+        nb = (ctx[b] + B - 1) // B
+        sc = oracle.block_scores(q[b].cpu()[:, g * G:(g + 1) * G], kmax[b, g:g + 1, :nb].permute(1, 0, 2).cpu(),
+                                 kmin[b, g:g + 1, :nb].permute(1, 0, 2).cpu(), reduce, last_node, "eq2")
+        ridx, rcnt = oracle.select_blocks(sc, ns, nr, k)
+        got = scores[b, g, :nb].cpu().numpy()
+        np.testing.assert_allclose(got, sc[0], atol=1e-3 * max(1.0, float(np.abs(sc).max()) / 16), rtol=2e-5)
+        exact = check_selection(idx[b, g:g + 1].cpu().numpy(), cnt[b, g:g + 1].cpu().numpy(), ridx, rcnt, sc, ns, nr, k,
+                                "sequence %d head %d %s" % (b, g, reduce))
+        say("   sequence %d KV head %d, %s: %s" % (b, g, reduce, "identical" if exact else "within the near-tie band"))
